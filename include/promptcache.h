@@ -1,0 +1,258 @@
+/*
+ * promptcache.h -- C ABI of the MI355X (gfx950) Prompt Cache hot path.
+ *
+ * The library implements the request-time part of Prompt Cache
+ * (arXiv 2311.04934, Sec. 3.3 - 3.4 and Sec. 4.2):
+ *
+ *   1. prompt-module attention states (K, V), encoded once at the position IDs
+ *      their schema fixes, are kept in a pool in HBM          (pc_store_module);
+ *   2. a prompt that imports some of those modules gets its KV cache by
+ *      concatenating the modules' states                      (pc_assemble_kv);
+ *   3. the tokens of the prompt that are not cached are rotated at their own
+ *      schema position IDs, their K/V are appended, and they attend over the
+ *      assembled KV, which replaces the prefill               (pc_rope,
+ *                                                 pc_append_kv, pc_prefill_attn).
+ *
+ * Conventions that hold for every call
+ * ------------------------------------
+ * Layout      Every K, V, Q and output tensor is token-major
+ *             [tokens][heads][head_dim], head_dim contiguous, no padding.
+ *             K/V tensors have n_kv_heads heads, Q/out have n_q_heads.
+ *             Query head h reads KV head  h / (n_q_heads / n_kv_heads).
+ * Element     pc_config.dtype: PC_F32 (4 bytes) or PC_BF16 (2 bytes, the upper
+ *             half of an IEEE binary32, round-to-nearest-even on store).
+ * Positions   int32 position IDs in [0, max_pos).  The assembled buffer is
+ *             PACKED in the order modules are listed; a module left out of a
+ *             prompt leaves a gap in the position IDs, never in the buffer.
+ * RoPE        half-split pairing: element i rotates with element i + d/2 by the
+ *             angle pos * rope_base^(-2i/d), i in [0, d/2).  Angles come from a
+ *             table built in fp64 and indexed by position ID (Sec. 4.2).
+ * Mask        key j is visible to query q  iff  pos[j] <= q_pos[q]: causality is
+ *             decided by schema position IDs, not by buffer order.
+ * "device"    pointer to GPU memory reachable from the current HIP device.
+ * "host"      ordinary host memory; read (or written) before the call returns.
+ * stream      a hipStream_t passed as void* (NULL = the default stream).  All
+ *             device work is enqueued on it; no call synchronises or allocates
+ *             device memory except pc_create / pc_destroy.
+ * Ownership   The pool owns a copy of every stored module.  All other buffers
+ *             belong to the caller and must stay valid until the stream has
+ *             executed the call.
+ * Errors      0 on success, a negative pc_status otherwise.  On error no device
+ *             work has been enqueued by that call.  pc_strerror names the code.
+ * Threads     a pc_ctx must not be used from two host threads at once.
+ */
+#ifndef PROMPTCACHE_H
+#define PROMPTCACHE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct pc_ctx pc_ctx;
+
+typedef enum { PC_F32 = 0, PC_BF16 = 1 } pc_dtype;
+
+typedef enum {
+    PC_OK = 0,
+    PC_E_BADARG = -1,         /* NULL pointer, negative size, misaligned buffer          */
+    PC_E_LAYER = -2,          /* layer outside [0, n_layers)                             */
+    PC_E_UNKNOWN_MODULE = -3, /* module id was never stored for that layer               */
+    PC_E_OVERLAP = -4,        /* two selected modules share a position ID                */
+    PC_E_CAPACITY = -5,       /* result does not fit the caller's buffer                 */
+    PC_E_POOL_FULL = -6,      /* module pool exhausted                                   */
+    PC_E_DUP_MODULE = -7,     /* id stored before with another length or start position  */
+    PC_E_POS_RANGE = -8,      /* a position ID would fall outside [0, max_pos)           */
+    PC_E_UNSUPPORTED = -9,    /* head_dim / dtype / head ratio the kernels do not cover  */
+    PC_E_HIP = -10,           /* a HIP runtime call failed (no GPU, out of memory, ...)  */
+    PC_E_SCHEMA = -11         /* malformed schema description                            */
+} pc_status;
+
+typedef struct {
+    int n_layers;
+    int n_q_heads;
+    int n_kv_heads;      /* must divide n_q_heads                                        */
+    int head_dim;        /* PC_BF16: 64 or 128;  PC_F32: even, <= 256                    */
+    int dtype;           /* pc_dtype                                                     */
+    double rope_base;    /* e.g. 10000.0                                                 */
+    int max_pos;         /* position IDs live in [0, max_pos)                            */
+    size_t pool_bytes;   /* HBM reserved for stored modules, all layers together         */
+    size_t scratch_bytes;/* HBM for split-KV partial results; 0 = library default        */
+} pc_config;
+
+/* ---------------------------------------------------------------- context */
+
+/* Allocate the pool, the RoPE table (max_pos x head_dim/2 cos/sin pairs, computed
+ * in fp64 on the host) and the split-KV scratch on the current HIP device. */
+int pc_create(const pc_config *cfg, pc_ctx **out_ctx);
+
+/* Synchronise the device and free everything pc_create allocated. */
+int pc_destroy(pc_ctx *ctx);
+
+const char *pc_strerror(int status);
+
+/* ---------------------------------------------- the three calls of the path */
+
+/*
+ * Prompt-module encoding result -> pool  (Sec. 3.3; Sec. 4.1 "GPU memory").
+ *
+ * K, V       device, [n_tokens][n_kv_heads][head_dim].  K must already carry the
+ *            positional encoding for positions start_pos .. start_pos+n_tokens-1
+ *            (that is what the model emits when the module is encoded at its
+ *            schema positions); V is position-free.  Both are copied
+ *            (device-to-device, asynchronously on `stream`).
+ * module_id  any non-negative int, unique per layer.  Storing an id again with
+ *            the same n_tokens and start_pos overwrites its states (modules may
+ *            be refreshed at run time); with different ones: PC_E_DUP_MODULE.
+ * Errors     PC_E_LAYER, PC_E_BADARG, PC_E_POS_RANGE, PC_E_POOL_FULL,
+ *            PC_E_DUP_MODULE.
+ */
+int pc_store_module(pc_ctx *ctx, int layer, int module_id, const void *K, const void *V,
+                    int n_tokens, int start_pos, void *stream);
+
+/*
+ * Cached inference, step 1: concatenate the imported modules' states (Sec. 3.4,
+ * "(k_C, v_C) = (concat(k_A, k_B), concat(v_A, v_B))").  One bandwidth-bound
+ * gather kernel; bytes are copied verbatim.
+ *
+ * module_ids      host, n_modules ids, in the order they are to appear in the
+ *                 buffer (any order is valid: the mask works on positions).
+ * out_K, out_V    device, caller-owned, room for capacity_tokens rows of
+ *                 n_kv_heads*head_dim elements, 16-byte aligned.
+ *                 Row r of module m lands at row (sum of lengths of the modules
+ *                 listed before m) + r.
+ * out_pos         device, int32[capacity_tokens]; row r of module m gets
+ *                 start_pos(m) + r.
+ * out_n_tokens    host, receives the number of rows written (may be NULL).
+ * Errors          PC_E_UNKNOWN_MODULE (an import the pool does not hold),
+ *                 PC_E_OVERLAP (e.g. two children of one union), PC_E_CAPACITY,
+ *                 PC_E_LAYER, PC_E_BADARG.
+ */
+int pc_assemble_kv(pc_ctx *ctx, int layer, const int *module_ids, int n_modules,
+                   void *out_K, void *out_V, int32_t *out_pos, int capacity_tokens,
+                   int *out_n_tokens, void *stream);
+
+/*
+ * Cached inference, step 2: attention of the uncached tokens over the assembled
+ * KV, which stands in for the prefill (Sec. 3.4, "using (k_C, v_C) as a KV cache").
+ *
+ *   out[q][h] = sum_j softmax_j( rope(Q_new[q][h], q_pos[q]) . asm_K[j][kv(h)] / sqrt(d) )
+ *               * asm_V[j][kv(h)]        over rows j with asm_pos[j] <= q_pos[q].
+ *
+ * Q_new    device, [n_q][n_q_heads][head_dim], NOT yet rotated: the rotation at
+ *          q_pos is fused into this call.  Not modified.
+ * q_pos    device, int32[n_q] schema position IDs of the uncached tokens.
+ * asm_K/V  device, [n_kv][n_kv_heads][head_dim]: the assembled modules, normally
+ *          followed by the uncached tokens' own K/V (pc_append_kv).
+ * asm_pos  device, int32[n_kv].
+ * out      device, [n_q][n_q_heads][head_dim] in the context dtype.  A query with
+ *          no visible key gets zeros.
+ * PC_BF16: QK^T and PV run on bf16 MFMA with fp32 accumulation and fp32 softmax
+ * statistics; PC_F32: everything in fp32.  The work is split over the KV axis
+ * when that is needed to fill the GPU; partial results go through the context's
+ * scratch and a small merge kernel, all on `stream`.
+ * Errors   PC_E_LAYER, PC_E_BADARG, PC_E_CAPACITY (scratch too small for n_q).
+ */
+int pc_prefill_attn(pc_ctx *ctx, int layer, const void *Q_new, const int32_t *q_pos, int n_q,
+                    const void *asm_K, const void *asm_V, const int32_t *asm_pos, int n_kv,
+                    void *out, void *stream);
+
+/* --------------------------------------------------------- supporting calls */
+
+/*
+ * RoPE at arbitrary position IDs, in place (Sec. 3.3: module positions do not
+ * start at zero; Sec. 4.2: rotation looked up by position ID).
+ * x device [n_tokens][n_heads][head_dim]; pos device int32[n_tokens], every
+ * value in [0, max_pos) (the caller guarantees it; the kernel clamps).
+ */
+int pc_rope(pc_ctx *ctx, void *x, int n_tokens, int n_heads, const int32_t *pos, void *stream);
+
+/*
+ * Append the uncached tokens' own states behind the assembled modules
+ * (Sec. 3.4: the new segments' states are concatenated with the cached ones to
+ * give the states of the entire prompt).
+ * K_new_raw  device [n_q][n_kv_heads][head_dim], not rotated; rotated at q_pos on
+ *            the way.   V_new  device, same shape, copied.
+ * Rows n_kv_before .. n_kv_before+n_q-1 of asm_K/asm_V/asm_pos are written.
+ * Errors     PC_E_CAPACITY if n_kv_before + n_q > capacity_tokens.
+ */
+int pc_append_kv(pc_ctx *ctx, int layer, const void *K_new_raw, const void *V_new,
+                 const int32_t *q_pos, int n_q, void *asm_K, void *asm_V, int32_t *asm_pos,
+                 int n_kv_before, int capacity_tokens, void *stream);
+
+/* ------------------------------------------- batched (several prompts at once) */
+
+/*
+ * Sec. 3.4 "batch inference": B prompts derived from one schema, possibly
+ * importing the same module.  Buffers are packed: prompt b owns rows
+ * kv_offsets[b] .. kv_offsets[b+1]-1 of out_K/out_V/out_pos (that span is its
+ * capacity, sized by the caller to also hold the tokens appended later) and its
+ * modules fill the first out_n_tokens[b] of them.  A shared module is read from
+ * the pool once per prompt that imports it (copying form of batch sharing).
+ *
+ * module_ids_flat  host, ids of prompt 0, then prompt 1, ...
+ * mod_offsets      host int[B+1]: prompt b imports module_ids_flat[mod_offsets[b] .. mod_offsets[b+1])
+ * kv_offsets       host int[B+1], non-decreasing row offsets
+ * out_n_tokens     host int[B]
+ */
+int pc_assemble_kv_batched(pc_ctx *ctx, int layer, const int *module_ids_flat, const int *mod_offsets,
+                           int n_prompts, void *out_K, void *out_V, int32_t *out_pos,
+                           const int *kv_offsets, int *out_n_tokens, void *stream);
+
+/* Batched pc_append_kv.  Prompt b's new tokens are rows q_offsets[b] .. q_offsets[b+1]-1
+ * of K_new_raw/V_new/q_pos and go to rows kv_offsets[b]+kv_lens[b] ... of the packed
+ * buffer; they must fit below kv_offsets[b+1].  All offset arrays are host. */
+int pc_append_kv_batched(pc_ctx *ctx, int layer, const void *K_new_raw, const void *V_new,
+                         const int32_t *q_pos, const int *q_offsets, int n_prompts, void *asm_K,
+                         void *asm_V, int32_t *asm_pos, const int *kv_offsets, const int *kv_lens,
+                         void *stream);
+
+/* Batched pc_prefill_attn.  Prompt b's queries are rows q_offsets[b] .. q_offsets[b+1]-1
+ * of Q_new/q_pos/out and see rows kv_offsets[b] .. kv_offsets[b]+kv_lens[b]-1 of the
+ * packed KV.  q_offsets host int[B+1]; kv_offsets host int[B+1]; kv_lens host int[B]. */
+int pc_prefill_attn_batched(pc_ctx *ctx, int layer, const void *Q_new, const int32_t *q_pos,
+                            const int *q_offsets, int n_prompts, const void *asm_K, const void *asm_V,
+                            const int32_t *asm_pos, const int *kv_offsets, const int *kv_lens,
+                            void *out, void *stream);
+
+/* ----------------------------------------------- host-side integer helpers */
+
+/*
+ * Schema position layout (Sec. 3.3): an entry starts where the entries before
+ * it end (predecessors of 50 and 60 tokens -> start 110); the children of a
+ * union share one start and the union spans its largest child (Sec. 3.2.3).
+ * sizes, union_ids, starts: host int[n]; union_ids[i] < 0 for an ordinary module,
+ * otherwise the id of its union, whose children must be adjacent.
+ * Returns the schema's total span (>= 0) or PC_E_SCHEMA.
+ */
+long pc_schema_layout(int n, const int *sizes, const int *union_ids, int *starts);
+
+/* Position IDs of a run of uncached text that follows an imported module
+ * (Sec. 3.4): prev_start + prev_len + i.  Text at the very start of a prompt uses
+ * prev_start = prev_len = 0.  pos: host int32[n_tokens]. */
+int pc_uncached_positions(int prev_start, int prev_len, int n_tokens, int32_t *pos);
+
+/* Would these modules be accepted together?  PC_OK, PC_E_OVERLAP, PC_E_POS_RANGE or
+ * PC_E_BADARG.  starts, lens: host int[n]. */
+int pc_check_selection(int n, const int *starts, const int *lens, int max_pos);
+
+/* K+V bytes one cached token occupies over all layers (the closed form behind
+ * Table 2, with n_kv_heads*head_dim in place of the hidden size). */
+long pc_bytes_per_token(int n_layers, int n_kv_heads, int head_dim, int dtype);
+
+/* Look a stored module up: PC_OK and its length/start, or PC_E_UNKNOWN_MODULE. */
+int pc_module_info(const pc_ctx *ctx, int layer, int module_id, int *n_tokens, int *start_pos);
+
+/* Bytes of pool in use / total. */
+int pc_pool_usage(const pc_ctx *ctx, size_t *used, size_t *total);
+
+/* How the last pc_prefill_attn[_batched] call was launched: number of KV splits,
+ * workgroups of the main kernel and waves per workgroup (for benchmarks). */
+int pc_last_attn_launch(const pc_ctx *ctx, int *n_splits, int *n_workgroups, int *waves_per_wg);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PROMPTCACHE_H */
