@@ -1,0 +1,267 @@
+"""ctypes binding of ``libpromptcache.so`` (see ``include/promptcache.h``).
+
+Argument marshalling only: every step of the path runs in the library's HIP
+kernels.  Torch tensors are used as device memory (``data_ptr()``) and for the
+current stream; nothing here computes.  If the shared library is missing the
+import of a symbol raises -- there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpromptcache.so")
+
+PC_F32, PC_BF16 = 0, 1
+
+EXPORTS = [
+    "pc_create", "pc_destroy", "pc_strerror", "pc_store_module", "pc_assemble_kv", "pc_prefill_attn",
+    "pc_rope", "pc_append_kv", "pc_assemble_kv_batched", "pc_append_kv_batched", "pc_prefill_attn_batched",
+    "pc_schema_layout", "pc_uncached_positions", "pc_check_selection", "pc_bytes_per_token",
+    "pc_module_info", "pc_pool_usage", "pc_last_attn_launch", "pc_profile_enable", "pc_profile_read",
+]
+PROF_GATHER, PROF_APPEND, PROF_ATTN, PROF_COMBINE, PROF_ROPE = range(5)
+
+
+class PcConfig(ctypes.Structure):
+    _fields_ = [
+        ("n_layers", ctypes.c_int), ("n_q_heads", ctypes.c_int), ("n_kv_heads", ctypes.c_int),
+        ("head_dim", ctypes.c_int), ("dtype", ctypes.c_int), ("rope_base", ctypes.c_double),
+        ("max_pos", ctypes.c_int), ("pool_bytes", ctypes.c_size_t), ("scratch_bytes", ctypes.c_size_t),
+    ]
+
+
+class PcError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {strerror(status)} ({status})")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Open the shared library (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2311_04934_amd.build` (hipcc, gfx950)")
+    L = ctypes.CDLL(LIB_PATH)
+    i, vp, ip = ctypes.c_int, ctypes.c_void_p, ctypes.POINTER(ctypes.c_int)
+    L.pc_create.argtypes = [ctypes.POINTER(PcConfig), ctypes.POINTER(vp)]
+    L.pc_destroy.argtypes = [vp]
+    L.pc_strerror.argtypes = [i]
+    L.pc_strerror.restype = ctypes.c_char_p
+    L.pc_store_module.argtypes = [vp, i, i, vp, vp, i, i, vp]
+    L.pc_assemble_kv.argtypes = [vp, i, vp, i, vp, vp, vp, i, ip, vp]
+    L.pc_prefill_attn.argtypes = [vp, i, vp, vp, i, vp, vp, vp, i, vp, vp]
+    L.pc_rope.argtypes = [vp, vp, i, i, vp, vp]
+    L.pc_append_kv.argtypes = [vp, i, vp, vp, vp, i, vp, vp, vp, i, i, vp]
+    L.pc_assemble_kv_batched.argtypes = [vp, i, vp, vp, i, vp, vp, vp, vp, vp, vp]
+    L.pc_append_kv_batched.argtypes = [vp, i, vp, vp, vp, vp, i, vp, vp, vp, vp, vp, vp]
+    L.pc_prefill_attn_batched.argtypes = [vp, i, vp, vp, vp, i, vp, vp, vp, vp, vp, vp, vp]
+    L.pc_schema_layout.argtypes = [i, vp, vp, vp]
+    L.pc_schema_layout.restype = ctypes.c_long
+    L.pc_uncached_positions.argtypes = [i, i, i, vp]
+    L.pc_check_selection.argtypes = [i, vp, vp, i]
+    L.pc_bytes_per_token.argtypes = [i, i, i, i]
+    L.pc_bytes_per_token.restype = ctypes.c_long
+    L.pc_module_info.argtypes = [vp, i, i, ip, ip]
+    L.pc_pool_usage.argtypes = [vp, ctypes.POINTER(ctypes.c_size_t), ctypes.POINTER(ctypes.c_size_t)]
+    L.pc_last_attn_launch.argtypes = [vp, ip, ip, ip]
+    L.pc_profile_enable.argtypes = [vp, i]
+    L.pc_profile_read.argtypes = [vp, i, ip, ctypes.POINTER(ctypes.c_double)]
+    for name in EXPORTS:
+        fn = getattr(L, name)
+        if name not in ("pc_strerror", "pc_schema_layout", "pc_bytes_per_token"):
+            fn.restype = ctypes.c_int
+    _lib = L
+    return L
+
+
+def strerror(status: int) -> str:
+    return lib().pc_strerror(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise PcError(status, where)
+
+
+def _ints(a: Sequence[int]) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a, dtype=np.intc))
+
+
+def _np_ptr(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _dev(t) -> Optional[int]:
+    """Device pointer of a torch tensor (None passes NULL)."""
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device-resident contiguous tensor expected"
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+# ------------------------------------------------------------------ host integer helpers
+def pc_schema_layout(sizes: Sequence[int], union_ids: Optional[Sequence[int]] = None) -> Tuple[List[int], int]:
+    n = len(sizes)
+    s = _ints(sizes)
+    u = _ints(union_ids if union_ids is not None else [-1] * n)
+    out = np.zeros(max(n, 1), dtype=np.intc)
+    span = lib().pc_schema_layout(n, _np_ptr(s), _np_ptr(u), _np_ptr(out))
+    if span < 0:
+        raise PcError(int(span), "pc_schema_layout")
+    return [int(x) for x in out[:n]], int(span)
+
+
+def pc_uncached_positions(prev_start: int, prev_len: int, n_tokens: int) -> np.ndarray:
+    pos = np.zeros(n_tokens, dtype=np.int32)
+    _check(lib().pc_uncached_positions(prev_start, prev_len, n_tokens, _np_ptr(pos)), "pc_uncached_positions")
+    return pos
+
+
+def pc_check_selection(starts: Sequence[int], lens: Sequence[int], max_pos: int) -> int:
+    s, l = _ints(starts), _ints(lens)
+    return int(lib().pc_check_selection(len(s), _np_ptr(s), _np_ptr(l), int(max_pos)))
+
+
+def pc_bytes_per_token(n_layers: int, n_kv_heads: int, head_dim: int, dtype: int) -> int:
+    return int(lib().pc_bytes_per_token(n_layers, n_kv_heads, head_dim, dtype))
+
+
+# ------------------------------------------------------------------ context
+class PromptCache:
+    """Owner of a ``pc_ctx``.  Methods mirror the C entry points one to one."""
+
+    def __init__(self, n_layers: int, n_q_heads: int, n_kv_heads: int, head_dim: int, dtype: int,
+                 rope_base: float = 10000.0, max_pos: int = 16384, pool_bytes: int = 1 << 30,
+                 scratch_bytes: int = 0):
+        self.cfg = PcConfig(n_layers, n_q_heads, n_kv_heads, head_dim, dtype, rope_base, max_pos,
+                            pool_bytes, scratch_bytes)
+        self._ctx = ctypes.c_void_p()
+        _check(lib().pc_create(ctypes.byref(self.cfg), ctypes.byref(self._ctx)), "pc_create")
+
+    @classmethod
+    def for_workload(cls, w, pool_bytes: Optional[int] = None, n_layers: Optional[int] = None, **kw):
+        L = n_layers if n_layers is not None else w.n_layers
+        if pool_bytes is None:
+            rows = sum(w.sizes[m] for m in w.used_module_ids())
+            pool_bytes = L * (2 * rows * w.row_bytes + 512 * len(w.sizes)) + (1 << 20)
+        return cls(L, w.n_q_heads, w.n_kv_heads, w.head_dim, PC_F32 if w.dtype == "f32" else PC_BF16,
+                   w.rope_base, w.max_pos, pool_bytes, **kw)
+
+    def close(self) -> None:
+        if self._ctx:
+            lib().pc_destroy(self._ctx)
+            self._ctx = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- the three calls of the path
+    def pc_store_module(self, layer: int, module_id: int, K, V, start_pos: int, stream=None) -> None:
+        n = int(K.shape[0])
+        _check(lib().pc_store_module(self._ctx, layer, module_id, _dev(K), _dev(V), n, start_pos, _stream(stream)),
+               "pc_store_module")
+
+    def pc_assemble_kv(self, layer: int, module_ids: Sequence[int], out_K, out_V, out_pos,
+                       capacity_tokens: Optional[int] = None, stream=None) -> int:
+        ids = _ints(module_ids)
+        cap = int(out_K.shape[0]) if capacity_tokens is None else capacity_tokens
+        n_out = ctypes.c_int(0)
+        _check(lib().pc_assemble_kv(self._ctx, layer, _np_ptr(ids), len(ids), _dev(out_K), _dev(out_V), _dev(out_pos),
+                                    cap, ctypes.byref(n_out), _stream(stream)), "pc_assemble_kv")
+        return n_out.value
+
+    def pc_prefill_attn(self, layer: int, Q_new, q_pos, asm_K, asm_V, asm_pos, n_kv: int, out, stream=None) -> None:
+        n_q = int(Q_new.shape[0])
+        _check(lib().pc_prefill_attn(self._ctx, layer, _dev(Q_new), _dev(q_pos), n_q, _dev(asm_K), _dev(asm_V),
+                                     _dev(asm_pos), n_kv, _dev(out), _stream(stream)), "pc_prefill_attn")
+
+    # -- supporting calls
+    def pc_rope(self, x, pos, stream=None) -> None:
+        _check(lib().pc_rope(self._ctx, _dev(x), int(x.shape[0]), int(x.shape[1]), _dev(pos), _stream(stream)), "pc_rope")
+
+    def pc_append_kv(self, layer: int, K_new_raw, V_new, q_pos, asm_K, asm_V, asm_pos, n_kv_before: int,
+                     capacity_tokens: Optional[int] = None, stream=None) -> None:
+        cap = int(asm_K.shape[0]) if capacity_tokens is None else capacity_tokens
+        _check(lib().pc_append_kv(self._ctx, layer, _dev(K_new_raw), _dev(V_new), _dev(q_pos), int(K_new_raw.shape[0]),
+                                  _dev(asm_K), _dev(asm_V), _dev(asm_pos), n_kv_before, cap, _stream(stream)),
+               "pc_append_kv")
+
+    # -- batched
+    def pc_assemble_kv_batched(self, layer: int, module_ids: Sequence[Sequence[int]], out_K, out_V, out_pos,
+                               kv_offsets: Sequence[int], stream=None) -> List[int]:
+        flat = _ints([m for ids in module_ids for m in ids])
+        offs = _ints(np.concatenate([[0], np.cumsum([len(ids) for ids in module_ids])]))
+        kvo = _ints(kv_offsets)
+        B = len(module_ids)
+        assert len(kvo) == B + 1
+        n_out = np.zeros(max(B, 1), dtype=np.intc)
+        _check(lib().pc_assemble_kv_batched(self._ctx, layer, _np_ptr(flat), _np_ptr(offs), B, _dev(out_K), _dev(out_V),
+                                            _dev(out_pos), _np_ptr(kvo), _np_ptr(n_out), _stream(stream)),
+               "pc_assemble_kv_batched")
+        return [int(x) for x in n_out[:B]]
+
+    def pc_append_kv_batched(self, layer: int, K_new_raw, V_new, q_pos, q_offsets: Sequence[int], asm_K, asm_V,
+                             asm_pos, kv_offsets: Sequence[int], kv_lens: Sequence[int], stream=None) -> None:
+        qo, kvo, kvl = _ints(q_offsets), _ints(kv_offsets), _ints(kv_lens)
+        B = len(kvl)
+        assert len(qo) == B + 1 and len(kvo) == B + 1
+        _check(lib().pc_append_kv_batched(self._ctx, layer, _dev(K_new_raw), _dev(V_new), _dev(q_pos), _np_ptr(qo), B,
+                                          _dev(asm_K), _dev(asm_V), _dev(asm_pos), _np_ptr(kvo), _np_ptr(kvl),
+                                          _stream(stream)), "pc_append_kv_batched")
+
+    def pc_prefill_attn_batched(self, layer: int, Q_new, q_pos, q_offsets: Sequence[int], asm_K, asm_V, asm_pos,
+                                kv_offsets: Sequence[int], kv_lens: Sequence[int], out, stream=None) -> None:
+        qo, kvo, kvl = _ints(q_offsets), _ints(kv_offsets), _ints(kv_lens)
+        B = len(kvl)
+        assert len(qo) == B + 1 and len(kvo) == B + 1
+        _check(lib().pc_prefill_attn_batched(self._ctx, layer, _dev(Q_new), _dev(q_pos), _np_ptr(qo), B, _dev(asm_K),
+                                             _dev(asm_V), _dev(asm_pos), _np_ptr(kvo), _np_ptr(kvl), _dev(out),
+                                             _stream(stream)), "pc_prefill_attn_batched")
+
+    # -- queries
+    def pc_module_info(self, layer: int, module_id: int) -> Tuple[int, int]:
+        n, s = ctypes.c_int(0), ctypes.c_int(0)
+        _check(lib().pc_module_info(self._ctx, layer, module_id, ctypes.byref(n), ctypes.byref(s)), "pc_module_info")
+        return n.value, s.value
+
+    def pc_pool_usage(self) -> Tuple[int, int]:
+        u, t = ctypes.c_size_t(0), ctypes.c_size_t(0)
+        _check(lib().pc_pool_usage(self._ctx, ctypes.byref(u), ctypes.byref(t)), "pc_pool_usage")
+        return u.value, t.value
+
+    def pc_last_attn_launch(self) -> Tuple[int, int, int]:
+        a, b, c = ctypes.c_int(0), ctypes.c_int(0), ctypes.c_int(0)
+        _check(lib().pc_last_attn_launch(self._ctx, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)),
+               "pc_last_attn_launch")
+        return a.value, b.value, c.value
+
+    def pc_profile_enable(self, max_records_per_kind: int) -> None:
+        _check(lib().pc_profile_enable(self._ctx, int(max_records_per_kind)), "pc_profile_enable")
+
+    def pc_profile_read(self, kind: int) -> Tuple[int, float]:
+        n, ms = ctypes.c_int(0), ctypes.c_double(0.0)
+        _check(lib().pc_profile_read(self._ctx, int(kind), ctypes.byref(n), ctypes.byref(ms)), "pc_profile_read")
+        return n.value, ms.value

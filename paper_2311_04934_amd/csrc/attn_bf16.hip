@@ -1,0 +1,525 @@
+// Uncached-token prefill attention over the assembled KV, bf16 MFMA path (gfx950).
+//
+// Computes, for every uncached query q and query head h (Sec. 3.4 of the paper:
+// the uncached tokens run through attention with the concatenated module states
+// as their KV cache):
+//     out[q][h] = sum_j softmax_j( rope(Q[q][h], q_pos[q]) . K[j][kv(h)] / sqrt(d) ) V[j][kv(h)]
+// over the rows j whose schema position ID is <= q_pos[q].
+//
+// Decomposition
+//   work unit  = (prompt, kv head, KV split, row block)
+//   row tile   = 32 queries of one query head; one wavefront owns one row tile for
+//                the whole kernel.  The query heads that share a kv head (GQA) are
+//                stacked: a workgroup's NW waves take NW row tiles of the same kv
+//                head, so each K/V tile is fetched once per workgroup and used by
+//                all of them.
+//   KV tile    = 64 keys, staged through LDS (double buffered): K row-major with a
+//                16-byte pad per row, V transposed on the way in so that the PV
+//                MFMA reads 8 consecutive keys per lane with one 16-byte LDS load.
+//   MFMA       v_mfma_f32_32x32x16_bf16.  Scores are produced TRANSPOSED
+//                (S^T = K . Q^T: rows = keys, columns = queries) so that every lane
+//                owns one query column: the softmax row reductions are 16 in-lane
+//                values plus one exchange with lane^32, and P^T in the accumulator
+//                layout is directly the B operand of  O^T += V^T . P^T.
+//   softmax    online, base 2 (log2(e)/sqrt(d) is folded into Q), fp32 statistics;
+//                P is rounded to bf16 for the PV product.
+//   mask       per key tile the min/max position ID decides "all visible",
+//                "none visible" (tile skipped) or "mixed" (per-element compare).
+//   split-KV   when one pass would not fill the GPU, the key range is cut into
+//                n_splits pieces; partial (m, l, O) go to scratch and a merge kernel
+//                combines them by log-sum-exp.
+//   XCD        workgroups are handed out round-robin over the 8 XCDs, so the group
+//                index is laid out such that all row blocks of one (kv head, split)
+//                land on the same XCD and share its L2.
+#include "common.h"
+
+namespace pc {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int KT = 64;          // keys per LDS tile
+constexpr int RW = 32;          // query rows per wave
+constexpr int kPosInf = 0x7fffffff;
+
+template <int D>
+struct Lds {
+    static constexpr int K_STRIDE = D * 2 + 16;        // bytes per K row (padded)
+    static constexpr int V_STRIDE = KT * 2 + 16;       // bytes per V^T row (padded)
+    static constexpr int K_BYTES = KT * K_STRIDE;
+    static constexpr int V_BYTES = D * V_STRIDE;
+    static constexpr int POS_BYTES = KT * 4;
+    static constexpr int META_BYTES = 16;
+    static constexpr int BUF_BYTES = K_BYTES + V_BYTES + POS_BYTES + META_BYTES;
+    static constexpr int TOTAL = 2 * BUF_BYTES;
+};
+
+struct AttnParams {
+    const uint16_t *q;       // [total_q][Hq][D] bf16 bits
+    const int32_t *q_pos;
+    const uint16_t *k;       // [total_kv][Hkv][D]
+    const uint16_t *v;
+    const int32_t *kv_pos;
+    uint16_t *out;           // [total_q][Hq][D]
+    float *part_o;           // [n_splits][total_q][Hq][D]
+    float2 *part_ml;         // [n_splits][total_q][Hq]
+    const float2 *rope;      // [max_pos][D/2]
+    int max_pos;
+    int Hq, Hkv, G;
+    int n_splits;
+    int rb_max;              // row blocks per (prompt, kv head)
+    int n_groups;            // n_seqs * n_splits * Hkv
+    int total_q;
+    float q_scale;           // log2(e) / sqrt(D)
+    AttnBatch batch;
+};
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+
+__device__ __forceinline__ float wave_xor32(float x) { return __shfl_xor(x, 32, 64); }
+
+__device__ __forceinline__ int wave_min_i32(int x)
+{
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) x = min(x, __shfl_xor(x, o, 64));
+    return x;
+}
+__device__ __forceinline__ int wave_max_i32(int x)
+{
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) x = max(x, __shfl_xor(x, o, 64));
+    return x;
+}
+
+// 4x4 transpose of 16-bit values held as four (lo,hi) dword pairs: in[e] = 4 dims of key e,
+// out[i] = 4 keys of dim i.
+__device__ __forceinline__ void transpose4x4_b16(const u32x2 in[4], u32x2 out[4])
+{
+    out[0].x = (in[0].x & 0xffffu) | (in[1].x << 16);
+    out[0].y = (in[2].x & 0xffffu) | (in[3].x << 16);
+    out[1].x = (in[0].x >> 16) | (in[1].x & 0xffff0000u);
+    out[1].y = (in[2].x >> 16) | (in[3].x & 0xffff0000u);
+    out[2].x = (in[0].y & 0xffffu) | (in[1].y << 16);
+    out[2].y = (in[2].y & 0xffffu) | (in[3].y << 16);
+    out[3].x = (in[0].y >> 16) | (in[1].y & 0xffff0000u);
+    out[3].y = (in[2].y >> 16) | (in[3].y & 0xffff0000u);
+}
+
+template <int D, int NW>
+__global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p)
+{
+    constexpr int NT = NW * 64;
+    constexpr int KB = D / 16;              // MFMA k-blocks over the head dim (QK^T)
+    constexpr int DB = D / 32;              // 32-row blocks of O^T
+    constexpr int K_CHUNKS = KT * D / 8;    // 16-byte chunks in a K tile
+    constexpr int V_BLOCKS = 16 * (D / 4);  // 4-key x 4-dim blocks in a V tile
+    constexpr int K_PER_T = (K_CHUNKS + NT - 1) / NT;
+    constexpr int V_PER_T = (V_BLOCKS + NT - 1) / NT;
+    using L = Lds<D>;
+
+    extern __shared__ __align__(16) uint8_t smem[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int col = lane & 31;   // query column inside the row tile
+    const int hh = lane >> 5;    // which half of the wave
+
+    // ---- which work unit (XCD-aware: consecutive block ids go to consecutive XCDs)
+    const int xcd = blockIdx.x & 7;
+    const int slot = blockIdx.x >> 3;
+    const int g = (slot / p.rb_max) * 8 + xcd;
+    const int rb = slot % p.rb_max;
+    if (g >= p.n_groups) return;
+    const int kvh = g % p.Hkv;
+    const int split = (g / p.Hkv) % p.n_splits;
+    const int seq_i = g / (p.Hkv * p.n_splits);
+    const AttnSeq seq = p.batch.seq[seq_i];
+
+    const int tiles_q = (seq.n_q + RW - 1) / RW;
+    const int row_tiles = p.G * tiles_q;
+    if (rb * NW >= row_tiles) return;   // whole workgroup has nothing to do
+    const int n_tiles = (seq.n_kv + KT - 1) / KT;
+    const int t0 = (int)(((long)split * n_tiles) / p.n_splits);
+    const int t1 = (int)(((long)(split + 1) * n_tiles) / p.n_splits);
+
+    // ---- this wave's row tile
+    const int rt = rb * NW + wave;
+    const bool wave_active = rt < row_tiles;
+    const int g_head = wave_active ? rt / tiles_q : 0;
+    const int qt = wave_active ? rt % tiles_q : 0;
+    const int head = kvh * p.G + g_head;
+    const int qi = qt * RW + col;                       // query index inside the prompt
+    const bool q_valid = wave_active && qi < seq.n_q;
+    const int q_row = seq.q_begin + (q_valid ? qi : 0);  // clamped for loads
+    const int my_qpos = q_valid ? p.q_pos[q_row] : kPosInf;
+
+    // ---- prologue: load Q, rotate at the query's position ID, scale, round to bf16
+    bf16x8 qf[KB];
+    {
+        const uint16_t *qrow = p.q + ((size_t)q_row * p.Hq + head) * D;
+        int tpos = my_qpos;
+        tpos = tpos < 0 ? 0 : (tpos >= p.max_pos ? p.max_pos - 1 : tpos);
+        const float2 *trow = p.rope + (size_t)tpos * (D / 2);
+#pragma unroll
+        for (int kb = 0; kb < KB / 2; ++kb) {
+            const int d0 = kb * 16 + hh * 8;  // < D/2
+            u32x4 lo = *reinterpret_cast<const u32x4 *>(qrow + d0);
+            u32x4 hi = *reinterpret_cast<const u32x4 *>(qrow + d0 + D / 2);
+            bf16x8 olo, ohi;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                uint32_t wl = lo[e >> 1], wh = hi[e >> 1];
+                float xl = bf16_bits_to_f32((e & 1) ? (wl >> 16) : (wl & 0xffffu));
+                float xh = bf16_bits_to_f32((e & 1) ? (wh >> 16) : (wh & 0xffffu));
+                float2 cs = trow[d0 + e];
+                olo[e] = (__bf16)((xl * cs.x - xh * cs.y) * p.q_scale);
+                ohi[e] = (__bf16)((xh * cs.x + xl * cs.y) * p.q_scale);
+            }
+            qf[kb] = olo;
+            qf[kb + KB / 2] = ohi;
+        }
+    }
+    // position range of this wave's real queries (decides masking per key tile)
+    const int wave_min_qpos = wave_min_i32(q_valid ? my_qpos : kPosInf);
+    const int wave_max_qpos = wave_max_i32(q_valid ? my_qpos : -1);
+
+    // ---- accumulators
+    f32x16 o_acc[DB];
+#pragma unroll
+    for (int b = 0; b < DB; ++b)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o_acc[b][i] = 0.f;
+    float m_run = -INFINITY;  // running max (log2 domain), identical in both halves of the wave
+    float l_run = 0.f;        // this lane's share of the running sum (halves added at the end)
+
+    // ---- staging registers for the next K/V tile
+    u32x4 k_reg[K_PER_T];
+    u32x2 v_reg[V_PER_T][4];
+    int pos_reg = kPosInf;
+
+    const size_t kv_row_stride = (size_t)p.Hkv * D;  // elements
+    const uint16_t *k_base = p.k + (size_t)seq.kv_begin * kv_row_stride + (size_t)kvh * D;
+    const uint16_t *v_base = p.v + (size_t)seq.kv_begin * kv_row_stride + (size_t)kvh * D;
+    const int32_t *pos_base = p.kv_pos + seq.kv_begin;
+
+    auto load_tile = [&](int t) {
+        const int row0 = t * KT;
+#pragma unroll
+        for (int it = 0; it < K_PER_T; ++it) {
+            const int c = tid + it * NT;
+            const int r = c / (D / 8), ch = c % (D / 8);
+            u32x4 val = {0u, 0u, 0u, 0u};
+            if (c < K_CHUNKS && row0 + r < seq.n_kv)
+                val = *reinterpret_cast<const u32x4 *>(k_base + (size_t)(row0 + r) * kv_row_stride + ch * 8);
+            k_reg[it] = val;
+        }
+#pragma unroll
+        for (int it = 0; it < V_PER_T; ++it) {
+            const int c = tid + it * NT;
+            const int dc = c % (D / 4), kg = c / (D / 4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int r = kg * 4 + e;
+                u32x2 val = {0u, 0u};
+                if (c < V_BLOCKS && row0 + r < seq.n_kv)
+                    val = *reinterpret_cast<const u32x2 *>(v_base + (size_t)(row0 + r) * kv_row_stride + dc * 4);
+                v_reg[it][e] = val;
+            }
+        }
+        if (tid < KT) pos_reg = (row0 + tid < seq.n_kv) ? pos_base[row0 + tid] : kPosInf;
+    };
+
+    auto store_tile = [&](int buf) {
+        uint8_t *sK = smem + buf * L::BUF_BYTES;
+        uint8_t *sV = sK + L::K_BYTES;
+        int32_t *sPos = reinterpret_cast<int32_t *>(sV + L::V_BYTES);
+        int32_t *sMeta = sPos + KT;
+#pragma unroll
+        for (int it = 0; it < K_PER_T; ++it) {
+            const int c = tid + it * NT;
+            const int r = c / (D / 8), ch = c % (D / 8);
+            if (c < K_CHUNKS) *reinterpret_cast<u32x4 *>(sK + r * L::K_STRIDE + ch * 16) = k_reg[it];
+        }
+#pragma unroll
+        for (int it = 0; it < V_PER_T; ++it) {
+            const int c = tid + it * NT;
+            const int dc = c % (D / 4), kg = c / (D / 4);
+            if (c < V_BLOCKS) {
+                u32x2 tr[4];
+                transpose4x4_b16(v_reg[it], tr);
+                // keys 4*kg .. 4*kg+3 of the tile; inside each block of 16 keys the four
+                // 4-key groups are stored in the order 0,2,1,3 so that the 8 keys a lane
+                // needs for one PV MFMA are contiguous
+                const int blk = kg >> 2, g4 = kg & 3;
+                const int sg = ((g4 & 1) << 1) | (g4 >> 1);
+                const int slot0 = blk * 16 + sg * 4;
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    *reinterpret_cast<u32x2 *>(sV + (dc * 4 + i) * L::V_STRIDE + slot0 * 2) = tr[i];
+            }
+        }
+        if (tid < KT) {
+            sPos[tid] = pos_reg;
+            // wave 0 holds all 64 position IDs of the tile: publish their range
+            const int real_min = wave_min_i32(pos_reg);                         // padding is +inf
+            const int real_max = wave_max_i32(pos_reg);                         // +inf if any padding
+            if (tid == 0) { sMeta[0] = real_min; sMeta[1] = real_max; }
+        }
+    };
+
+    auto compute_tile = [&](int buf) {
+        const uint8_t *sK = smem + buf * L::BUF_BYTES;
+        const uint8_t *sV = sK + L::K_BYTES;
+        const int32_t *sPos = reinterpret_cast<const int32_t *>(sV + L::V_BYTES);
+        const int32_t *sMeta = sPos + KT;
+        const int tile_min = __builtin_amdgcn_readfirstlane(sMeta[0]);
+        const int tile_max = __builtin_amdgcn_readfirstlane(sMeta[1]);
+        if (tile_min > wave_max_qpos) return;             // nothing in this tile is visible to this wave
+        const bool need_mask = tile_max > wave_min_qpos;  // some (query, key) pair is hidden
+
+#pragma unroll
+        for (int sub = 0; sub < KT / 32; ++sub) {
+            // S^T (32 keys x 32 queries) = K_sub . Q^T
+            f32x16 s;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) s[i] = 0.f;
+            const uint8_t *krow = sK + (sub * 32 + col) * L::K_STRIDE + hh * 16;
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) {
+                u32x4 raw = *reinterpret_cast<const u32x4 *>(krow + kb * 32);
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, raw), qf[kb], s, 0, 0, 0);
+            }
+            if (need_mask) {
+                // accumulator register i holds key 8*(i/4) + 4*hh + i%4 of the sub-tile
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    const u32x4 kp = *reinterpret_cast<const u32x4 *>(sPos + sub * 32 + 8 * i4 + 4 * hh);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if ((int)kp[e] > my_qpos) s[i4 * 4 + e] = -INFINITY;
+                }
+            }
+            // online softmax for the lane's query column
+            float mx = s[0];
+#pragma unroll
+            for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[i]);
+            mx = fmaxf(mx, wave_xor32(mx));
+            const float m_new = fmaxf(m_run, mx);
+            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
+            m_run = m_new;
+            float psum = 0.f;
+            bf16x8 pf[2];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const float pv = __builtin_amdgcn_exp2f(s[i] - m_use);
+                psum += pv;
+                pf[i >> 3][i & 7] = (__bf16)pv;
+            }
+            l_run = l_run * alpha + psum;
+            if (__any(alpha != 1.f)) {
+#pragma unroll
+                for (int b = 0; b < DB; ++b)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) o_acc[b][i] *= alpha;
+            }
+            // O^T (D x 32 queries) += V^T_sub . P^T
+            const uint8_t *vrow = sV + col * L::V_STRIDE + (sub * 2) * 32 + hh * 16;
+#pragma unroll
+            for (int b = 0; b < DB; ++b) {
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    u32x4 raw = *reinterpret_cast<const u32x4 *>(vrow + b * 32 * L::V_STRIDE + j * 32);
+                    o_acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, raw), pf[j], o_acc[b], 0, 0, 0);
+                }
+            }
+        }
+    };
+
+    // ---- main loop over this split's key tiles (double-buffered LDS)
+    if (t0 < t1) {
+        load_tile(t0);
+        store_tile(0);
+        __syncthreads();
+        for (int t = t0; t < t1; ++t) {
+            const int buf = (t - t0) & 1;
+            const bool more = t + 1 < t1;
+            if (more) load_tile(t + 1);
+            if (wave_active) compute_tile(buf);
+            if (more) store_tile(buf ^ 1);
+            __syncthreads();
+        }
+    }
+
+    // ---- epilogue
+    if (!q_valid) return;
+    const float l_tot = l_run + wave_xor32(l_run);
+    const size_t out_row = (size_t)(seq.q_begin + qi) * p.Hq + head;
+    if (p.n_splits == 1) {
+        const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+        uint16_t *orow = p.out + out_row * D;
+#pragma unroll
+        for (int b = 0; b < DB; ++b)
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+                bf16x4 w;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) w[e] = (__bf16)(o_acc[b][i4 * 4 + e] * inv);
+                *reinterpret_cast<bf16x4 *>(orow + b * 32 + i4 * 8 + hh * 4) = w;
+            }
+    } else {
+        const size_t prow = (size_t)split * p.total_q * p.Hq + out_row;
+        float *orow = p.part_o + prow * D;
+#pragma unroll
+        for (int b = 0; b < DB; ++b)
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+                f32x4 w;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) w[e] = o_acc[b][i4 * 4 + e];
+                *reinterpret_cast<f32x4 *>(orow + b * 32 + i4 * 8 + hh * 4) = w;
+            }
+        if (hh == 0) p.part_ml[prow] = make_float2(m_run, l_tot);
+    }
+}
+
+// Merge the split-KV partials: out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
+template <int D>
+__global__ __launch_bounds__(256) void attn_combine_kernel(const float *part_o, const float2 *part_ml, uint16_t *out,
+                                                           int n_splits, long n_rows /* total_q * Hq */,
+                                                           long row_lo, long row_hi /* rows this launch owns */)
+{
+    constexpr int CH = D / 4;  // 4-element chunks per row
+    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (row_hi - row_lo) * CH) return;
+    const long row = row_lo + idx / CH;
+    const int ch = (int)(idx % CH);
+    float M = -INFINITY;
+    for (int s = 0; s < n_splits; ++s) M = fmaxf(M, part_ml[(size_t)s * n_rows + row].x);
+    float Lsum = 0.f;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    if (M != -INFINITY) {
+        for (int s = 0; s < n_splits; ++s) {
+            const float2 ml = part_ml[(size_t)s * n_rows + row];
+            if (ml.x == -INFINITY) continue;   // that split saw no visible key (its O may be unset)
+            const float w = __builtin_amdgcn_exp2f(ml.x - M);
+            Lsum += w * ml.y;
+            const f32x4 o = *reinterpret_cast<const f32x4 *>(part_o + ((size_t)s * n_rows + row) * D + ch * 4);
+            acc += o * w;
+        }
+    }
+    const float inv = Lsum > 0.f ? 1.f / Lsum : 0.f;
+    bf16x4 w4;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) w4[e] = (__bf16)(acc[e] * inv);
+    *reinterpret_cast<bf16x4 *>(out + (size_t)row * D + ch * 4) = w4;
+}
+
+template <int D, int NW>
+int launch_variant(pc_ctx *ctx, AttnParams &p, int n_blocks, hipStream_t stream)
+{
+    static bool attr_set[16] = {false};
+    auto kern = attn_bf16_kernel<D, NW>;
+    const int smem = Lds<D>::TOTAL;
+    if (!attr_set[ctx->device & 15]) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
+            return PC_E_HIP;
+        attr_set[ctx->device & 15] = true;
+    }
+    ProfScope prof(ctx, kProfAttn, stream);
+    hipLaunchKernelGGL(kern, dim3(n_blocks), dim3(NW * 64), smem, stream, p);
+    return hip_status(hipGetLastError());
+}
+
+}  // namespace
+
+int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const int32_t *q_pos, const void *k,
+                     const void *v, const int32_t *kv_pos, void *out, hipStream_t stream)
+{
+    const int D = ctx->cfg.head_dim, Hq = ctx->cfg.n_q_heads, Hkv = ctx->cfg.n_kv_heads, G = Hq / Hkv;
+    if (D != 64 && D != 128) return PC_E_UNSUPPORTED;
+
+    int total_q = 0, q_lo = 1 << 30, max_row_tiles = 0, min_kv_tiles = 1 << 30;
+    for (int s = 0; s < batch.n_seqs; ++s) {
+        const AttnSeq &sq = batch.seq[s];
+        total_q = sq.q_begin + sq.n_q > total_q ? sq.q_begin + sq.n_q : total_q;
+        q_lo = sq.q_begin < q_lo ? sq.q_begin : q_lo;
+        const int rt = G * ((sq.n_q + RW - 1) / RW);
+        if (rt > max_row_tiles) max_row_tiles = rt;
+        const int kt = (sq.n_kv + KT - 1) / KT;
+        if (kt < min_kv_tiles) min_kv_tiles = kt;
+    }
+    if (total_q == 0 || max_row_tiles == 0) return PC_OK;
+
+    const int NW = max_row_tiles <= 4 ? 4 : 8;
+    const int rb_max = (max_row_tiles + NW - 1) / NW;
+    const long base_wgs = (long)batch.n_seqs * Hkv * rb_max;
+    const long target = (long)ctx->n_cu * (8 / NW);
+
+    // KV splits: enough workgroups to fill the GPU, at least 2 key tiles per split,
+    // and the partials must fit the scratch.
+    int n_splits = (int)((target + base_wgs - 1) / base_wgs);
+    const int max_by_tiles = min_kv_tiles / 2 > 1 ? min_kv_tiles / 2 : 1;
+    if (n_splits > max_by_tiles) n_splits = max_by_tiles;
+    if (n_splits > 32) n_splits = 32;
+    if (n_splits < 1) n_splits = 1;
+    const size_t per_split = (size_t)total_q * Hq * (D * sizeof(float) + sizeof(float2));
+    if (n_splits > 1) {
+        const size_t fit = ctx->scratch_bytes / per_split;
+        if (fit < 2) n_splits = 1;
+        else if ((size_t)n_splits > fit) n_splits = (int)fit;
+    }
+
+    AttnParams p;
+    p.q = static_cast<const uint16_t *>(q);
+    p.q_pos = q_pos;
+    p.k = static_cast<const uint16_t *>(k);
+    p.v = static_cast<const uint16_t *>(v);
+    p.kv_pos = kv_pos;
+    p.out = static_cast<uint16_t *>(out);
+    p.part_o = ctx->scratch;
+    p.part_ml = reinterpret_cast<float2 *>(ctx->scratch + (size_t)n_splits * total_q * Hq * D);
+    p.rope = ctx->rope_table;
+    p.max_pos = ctx->cfg.max_pos;
+    p.Hq = Hq;
+    p.Hkv = Hkv;
+    p.G = G;
+    p.n_splits = n_splits;
+    p.rb_max = rb_max;
+    p.n_groups = batch.n_seqs * n_splits * Hkv;
+    p.total_q = total_q;
+    p.q_scale = 1.4426950408889634f / sqrtf((float)D);
+    p.batch = batch;
+
+    const int n_blocks = 8 * ((p.n_groups + 7) / 8) * rb_max;
+    int rc;
+    if (D == 128) rc = NW == 8 ? launch_variant<128, 8>(ctx, p, n_blocks, stream) : launch_variant<128, 4>(ctx, p, n_blocks, stream);
+    else rc = NW == 8 ? launch_variant<64, 8>(ctx, p, n_blocks, stream) : launch_variant<64, 4>(ctx, p, n_blocks, stream);
+    if (rc != PC_OK) return rc;
+
+    if (n_splits > 1) {
+        // the prompts of one launch own the contiguous query rows [q_lo, total_q)
+        const long n_rows = (long)total_q * Hq;
+        const long row_lo = (long)q_lo * Hq;
+        const long n_thr = (n_rows - row_lo) * (D / 4);
+        const int blocks = (int)((n_thr + 255) / 256);
+        ProfScope prof(ctx, kProfCombine, stream);
+        if (D == 128)
+            hipLaunchKernelGGL(attn_combine_kernel<128>, dim3(blocks), dim3(256), 0, stream, p.part_o, p.part_ml, p.out, n_splits, n_rows, row_lo, n_rows);
+        else
+            hipLaunchKernelGGL(attn_combine_kernel<64>, dim3(blocks), dim3(256), 0, stream, p.part_o, p.part_ml, p.out, n_splits, n_rows, row_lo, n_rows);
+        rc = hip_status(hipGetLastError());
+    }
+    ctx->last_attn.n_splits = n_splits;
+    ctx->last_attn.n_workgroups = n_blocks;
+    ctx->last_attn.waves_per_wg = NW;
+    return rc;
+}
+
+}  // namespace pc

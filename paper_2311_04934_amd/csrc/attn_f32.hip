@@ -1,0 +1,160 @@
+// Uncached-token attention over the assembled KV, fp32 path (Sec. 3.4 of the paper).
+//
+// Same contract as the bf16 MFMA kernel, everything in fp32 (tolerance 1e-4 against
+// an fp64 reference).  One wavefront owns one (query, head) pair: the query is
+// rotated at its position ID and parked in LDS; keys are taken 64 at a time, one key
+// per lane for the score, then the lanes switch roles and each owns output
+// dimensions lane, lane+64, ... for the P.V accumulation.  Online softmax with the
+// running maximum and sum kept per wave.
+#include "common.h"
+
+namespace pc {
+namespace {
+
+constexpr int kWaves = 4;
+constexpr int kMaxD = 256;
+
+__device__ __forceinline__ float wave_max_f(float x)
+{
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, 64));
+    return x;
+}
+__device__ __forceinline__ float wave_sum_f(float x)
+{
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o, 64);
+    return x;
+}
+
+struct F32Params {
+    const float *q;
+    const int32_t *q_pos;
+    const float *k;
+    const float *v;
+    const int32_t *kv_pos;
+    float *out;
+    const float2 *rope;
+    int max_pos, Hq, Hkv, d;
+    int q_lo, q_hi;  // query rows covered by this launch
+    float scale;
+    AttnBatch batch;
+};
+
+__global__ __launch_bounds__(kWaves * 64) void attn_f32_kernel(const F32Params p)
+{
+    __shared__ float s_q[kWaves][kMaxD];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const long pair = (long)blockIdx.x * kWaves + wave;
+    const long n_pairs = (long)(p.q_hi - p.q_lo) * p.Hq;
+    const bool in_range = pair < n_pairs;
+    const int q_row = p.q_lo + (int)((in_range ? pair : 0) / p.Hq);
+    const int h = (int)((in_range ? pair : 0) % p.Hq);
+    const int kvh = h / (p.Hq / p.Hkv);
+    const int d = p.d, half = d >> 1;
+
+    // which prompt owns this query row
+    int si = -1;
+    if (in_range)
+        for (int s = 0; s < p.batch.n_seqs; ++s)
+            if (q_row >= p.batch.seq[s].q_begin && q_row < p.batch.seq[s].q_begin + p.batch.seq[s].n_q) si = s;
+    const bool active = si >= 0;
+    const AttnSeq seq = p.batch.seq[active ? si : 0];
+
+    // rotate the query at its position ID, fold in 1/sqrt(d)
+    const int qpos = active ? p.q_pos[q_row] : 0;
+    if (active) {
+        int tp = qpos < 0 ? 0 : (qpos >= p.max_pos ? p.max_pos - 1 : qpos);
+        const float2 *trow = p.rope + (size_t)tp * half;
+        const float *qr = p.q + ((size_t)q_row * p.Hq + h) * d;
+        for (int i = lane; i < half; i += 64) {
+            const float2 cs = trow[i];
+            const float lo = qr[i], hi = qr[i + half];
+            s_q[wave][i] = (lo * cs.x - hi * cs.y) * p.scale;
+            s_q[wave][i + half] = (hi * cs.x + lo * cs.y) * p.scale;
+        }
+    }
+    __syncthreads();
+    if (!active) return;
+    float *orow = p.out + ((size_t)q_row * p.Hq + h) * d;
+
+    const size_t row_stride = (size_t)p.Hkv * d;
+    const float *kb = p.k + (size_t)seq.kv_begin * row_stride + (size_t)kvh * d;
+    const float *vb = p.v + (size_t)seq.kv_begin * row_stride + (size_t)kvh * d;
+    const int32_t *pb = p.kv_pos + seq.kv_begin;
+
+    float m_run = -INFINITY, l_run = 0.f;
+    float acc[kMaxD / 64] = {0.f, 0.f, 0.f, 0.f};
+
+    for (int j0 = 0; j0 < seq.n_kv; j0 += 64) {
+        const int j = j0 + lane;
+        const bool vis = j < seq.n_kv && pb[j] <= qpos;
+        float s = -INFINITY;
+        if (vis) {
+            const float *kr = kb + (size_t)j * row_stride;
+            float dot = 0.f;
+            for (int c = 0; c < d; ++c) dot = fmaf(s_q[wave][c], kr[c], dot);
+            s = dot;
+        }
+        const float tmax = wave_max_f(s);
+        if (tmax == -INFINITY) continue;  // no visible key in these 64 (uniform)
+        const float m_new = fmaxf(m_run, tmax);
+        const float alpha = expf(m_run - m_new);  // m_run = -inf -> 0
+        const float pj = vis ? expf(s - m_new) : 0.f;
+        l_run = l_run * alpha + wave_sum_f(pj);
+        m_run = m_new;
+#pragma unroll
+        for (int u = 0; u < kMaxD / 64; ++u) acc[u] *= alpha;
+        const int n_here = seq.n_kv - j0 < 64 ? seq.n_kv - j0 : 64;
+        for (int kk = 0; kk < n_here; ++kk) {
+            const float pk = __shfl(pj, kk, 64);
+            if (pk == 0.f) continue;  // uniform: masked or underflowed key contributes nothing
+            const float *vr = vb + (size_t)(j0 + kk) * row_stride;
+#pragma unroll
+            for (int u = 0; u < kMaxD / 64; ++u) {
+                const int c = lane + 64 * u;
+                if (c < d) acc[u] = fmaf(pk, vr[c], acc[u]);
+            }
+        }
+    }
+    const float inv = l_run > 0.f ? 1.f / l_run : 0.f;
+#pragma unroll
+    for (int u = 0; u < kMaxD / 64; ++u) {
+        const int c = lane + 64 * u;
+        if (c < d) orow[c] = acc[u] * inv;
+    }
+}
+
+}  // namespace
+
+int launch_attn_f32(pc_ctx *ctx, const AttnBatch &batch, const float *q, const int32_t *q_pos, const float *k,
+                    const float *v, const int32_t *kv_pos, float *out, hipStream_t stream)
+{
+    const int d = ctx->cfg.head_dim;
+    if (d > kMaxD || (d & 1)) return PC_E_UNSUPPORTED;
+    int q_lo = 1 << 30, q_hi = 0;
+    for (int s = 0; s < batch.n_seqs; ++s) {
+        if (batch.seq[s].n_q == 0) continue;
+        if (batch.seq[s].q_begin < q_lo) q_lo = batch.seq[s].q_begin;
+        if (batch.seq[s].q_begin + batch.seq[s].n_q > q_hi) q_hi = batch.seq[s].q_begin + batch.seq[s].n_q;
+    }
+    if (q_hi <= q_lo) return PC_OK;
+    F32Params p;
+    p.q = q; p.q_pos = q_pos; p.k = k; p.v = v; p.kv_pos = kv_pos; p.out = out;
+    p.rope = ctx->rope_table;
+    p.max_pos = ctx->cfg.max_pos;
+    p.Hq = ctx->cfg.n_q_heads; p.Hkv = ctx->cfg.n_kv_heads; p.d = d;
+    p.q_lo = q_lo; p.q_hi = q_hi;
+    p.scale = 1.0f / sqrtf((float)d);
+    p.batch = batch;
+    const long n_pairs = (long)(q_hi - q_lo) * p.Hq;
+    const int blocks = (int)((n_pairs + kWaves - 1) / kWaves);
+    ProfScope prof(ctx, kProfAttn, stream);
+    hipLaunchKernelGGL(attn_f32_kernel, dim3(blocks), dim3(kWaves * 64), 0, stream, p);
+    ctx->last_attn.n_splits = 1;
+    ctx->last_attn.n_workgroups = blocks;
+    ctx->last_attn.waves_per_wg = kWaves;
+    return hip_status(hipGetLastError());
+}
+
+}  // namespace pc

@@ -1,0 +1,150 @@
+// Internal declarations shared by the host runtime and the kernel launchers.
+// Nothing here is part of the public ABI (see include/promptcache.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include <unordered_map>
+#include <vector>
+
+#include "promptcache.h"
+
+namespace pc {
+
+// One stored prompt module of one layer: where its K block starts in the pool
+// (the V block follows it), how many rows it has and its first position ID.
+struct ModuleEntry {
+    size_t k_offset;
+    size_t v_offset;
+    int n_tokens;
+    int start_pos;
+};
+
+// Optional per-kernel timing with HIP events recorded on the caller's stream right
+// around each kernel launch (off by default; see pc_profile_enable).
+enum ProfKind { kProfGather = 0, kProfAppend = 1, kProfAttn = 2, kProfCombine = 3, kProfRope = 4, kProfKinds = 5 };
+struct Profiler {
+    int capacity = 0;  // event pairs per kind; 0 = disabled
+    std::vector<hipEvent_t> start[kProfKinds], stop[kProfKinds];
+    int used[kProfKinds] = {0, 0, 0, 0, 0};
+};
+
+// How the last attention call was decomposed (reported to benchmarks).
+struct AttnLaunchInfo {
+    int n_splits = 0;
+    int n_workgroups = 0;
+    int waves_per_wg = 0;
+};
+
+}  // namespace pc
+
+struct pc_ctx {
+    pc_config cfg;
+    int device = 0;
+    int elem_bytes = 0;
+    size_t row_bytes = 0;  // n_kv_heads * head_dim * elem_bytes
+
+    uint8_t *pool = nullptr;  // module pool (device)
+    size_t pool_used = 0;
+    std::vector<std::unordered_map<int, pc::ModuleEntry>> modules;  // per layer
+
+    float2 *rope_table = nullptr;  // device, [max_pos][head_dim/2] (cos, sin)
+
+    float *scratch = nullptr;  // device, split-KV partials
+    size_t scratch_bytes = 0;
+
+    int n_cu = 256;
+    pc::AttnLaunchInfo last_attn;
+    pc::Profiler prof;
+};
+
+namespace pc {
+
+// ---- gather (KV assembly) ---------------------------------------------------
+// One contiguous run of rows copied from the pool to the packed output.
+struct GatherSeg {
+    const uint8_t *src_k;
+    const uint8_t *src_v;
+    int dst_row;     // first output row
+    int n_rows;
+    int start_pos;   // position ID of the first row
+    int first_tile;  // index of this segment's first tile in the launch
+};
+
+constexpr int kMaxGatherSegs = 64;
+
+struct GatherArgs {
+    int n_segs;
+    int total_tiles;
+    int rows_per_tile;
+    int row_bytes;
+    GatherSeg seg[kMaxGatherSegs];
+};
+
+int launch_gather(pc_ctx *ctx, const GatherArgs &args, uint8_t *out_k, uint8_t *out_v, int32_t *out_pos,
+                  hipStream_t stream);
+
+// ---- RoPE / append -----------------------------------------------------------
+int launch_rope(pc_ctx *ctx, void *x, int n_tokens, int n_heads, const int32_t *pos, hipStream_t stream);
+
+// One prompt's slice for the batched append: rows [q_begin, q_begin+n) of the new
+// tokens go to rows [dst_row, dst_row+n) of the packed KV.
+struct AppendSeg {
+    int q_begin;
+    int n;
+    int dst_row;
+};
+constexpr int kMaxAppendSegs = 128;
+struct AppendArgs {
+    int n_segs;
+    int total_rows;
+    AppendSeg seg[kMaxAppendSegs];
+};
+int launch_append(pc_ctx *ctx, const AppendArgs &args, const void *k_new, const void *v_new, const int32_t *q_pos,
+                  void *asm_k, void *asm_v, int32_t *asm_pos, hipStream_t stream);
+
+// ---- attention -----------------------------------------------------------------
+// One prompt of a (possibly batched) attention call.
+struct AttnSeq {
+    int q_begin;   // first query row in Q_new / out
+    int n_q;
+    int kv_begin;  // first row in the packed KV
+    int n_kv;
+};
+constexpr int kMaxAttnSeqs = 64;
+struct AttnBatch {
+    int n_seqs;
+    AttnSeq seq[kMaxAttnSeqs];
+};
+
+int launch_attn_f32(pc_ctx *ctx, const AttnBatch &batch, const float *q, const int32_t *q_pos, const float *k,
+                    const float *v, const int32_t *kv_pos, float *out, hipStream_t stream);
+
+int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const int32_t *q_pos, const void *k,
+                     const void *v, const int32_t *kv_pos, void *out, hipStream_t stream);
+
+inline int hip_status(hipError_t e) { return e == hipSuccess ? PC_OK : PC_E_HIP; }
+
+// Records a start event now and a stop event when it goes out of scope, both on `stream`,
+// if profiling is on and a free event pair is left for `kind`.
+struct ProfScope {
+    pc_ctx *ctx;
+    int kind, slot;
+    hipStream_t stream;
+    ProfScope(pc_ctx *c, int k, hipStream_t s) : ctx(c), kind(k), slot(-1), stream(s)
+    {
+        Profiler &p = ctx->prof;
+        if (p.capacity > 0 && p.used[kind] < p.capacity) {
+            slot = p.used[kind]++;
+            (void)hipEventRecord(p.start[kind][slot], stream);
+        }
+    }
+    ~ProfScope()
+    {
+        if (slot >= 0) (void)hipEventRecord(ctx->prof.stop[kind][slot], stream);
+    }
+};
+
+}  // namespace pc

@@ -1,0 +1,510 @@
+// Host runtime of the Prompt Cache hot path: context, module pool, request planning
+// (which pool rows go where, validation of the imported modules) and the C ABI.
+// All numerical work happens in the kernels; this file only moves integers and
+// pointers.  See include/promptcache.h for the contract of every entry point.
+#include <math.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+
+#include "common.h"
+
+using namespace pc;
+
+namespace {
+
+constexpr size_t kPoolAlign = 256;
+constexpr size_t kDefaultScratch = (size_t)256 << 20;
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+inline hipStream_t as_stream(void *s) { return static_cast<hipStream_t>(s); }
+
+int elem_size(int dtype) { return dtype == PC_F32 ? 4 : (dtype == PC_BF16 ? 2 : 0); }
+
+int validate_config(const pc_config *c)
+{
+    if (!c) return PC_E_BADARG;
+    if (c->n_layers <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0 || c->head_dim <= 0) return PC_E_BADARG;
+    if (c->n_q_heads % c->n_kv_heads) return PC_E_BADARG;
+    if (c->max_pos <= 0 || !(c->rope_base > 1.0)) return PC_E_BADARG;
+    if (c->dtype == PC_BF16) {
+        if (c->head_dim != 64 && c->head_dim != 128) return PC_E_UNSUPPORTED;
+    } else if (c->dtype == PC_F32) {
+        if ((c->head_dim & 3) || c->head_dim > 256) return PC_E_UNSUPPORTED;  // rows must be 16-byte multiples
+    } else {
+        return PC_E_UNSUPPORTED;
+    }
+    return PC_OK;
+}
+
+// Sorted-interval test: do any two [start, start+len) ranges share a position ID?
+int check_ranges(int n, const int *starts, const int *lens, int max_pos)
+{
+    if (n < 0 || (n > 0 && (!starts || !lens))) return PC_E_BADARG;
+    std::vector<std::pair<long, long>> iv;
+    iv.reserve(n);
+    for (int i = 0; i < n; ++i) {
+        if (lens[i] < 0 || starts[i] < 0) return PC_E_BADARG;
+        if ((long)starts[i] + lens[i] > (long)max_pos) return PC_E_POS_RANGE;
+        if (lens[i] > 0) iv.emplace_back(starts[i], (long)starts[i] + lens[i]);
+    }
+    std::sort(iv.begin(), iv.end());
+    for (size_t i = 1; i < iv.size(); ++i)
+        if (iv[i].first < iv[i - 1].second) return PC_E_OVERLAP;
+    return PC_OK;
+}
+
+// Resolve one prompt's imports into gather segments appended to `segs`.
+// dst_row0: first output row of this prompt; capacity: rows available to it.
+int plan_prompt(const pc_ctx *ctx, int layer, const int *ids, int n, int dst_row0, int capacity,
+                std::vector<GatherSeg> &segs, int *n_rows_out)
+{
+    const auto &table = ctx->modules[layer];
+    std::vector<int> starts(n), lens(n);
+    long rows = 0;
+    for (int i = 0; i < n; ++i) {
+        auto it = table.find(ids[i]);
+        if (it == table.end()) return PC_E_UNKNOWN_MODULE;
+        starts[i] = it->second.start_pos;
+        lens[i] = it->second.n_tokens;
+        rows += lens[i];
+    }
+    int rc = check_ranges(n, starts.data(), lens.data(), ctx->cfg.max_pos);
+    if (rc != PC_OK) return rc;
+    if (rows > capacity) return PC_E_CAPACITY;
+    int row = dst_row0;
+    for (int i = 0; i < n; ++i) {
+        const ModuleEntry &m = table.find(ids[i])->second;
+        if (m.n_tokens == 0) continue;
+        GatherSeg s;
+        s.src_k = ctx->pool + m.k_offset;
+        s.src_v = ctx->pool + m.v_offset;
+        s.dst_row = row;
+        s.n_rows = m.n_tokens;
+        s.start_pos = m.start_pos;
+        s.first_tile = 0;
+        segs.push_back(s);
+        row += m.n_tokens;
+    }
+    *n_rows_out = (int)rows;
+    return PC_OK;
+}
+
+int run_gather(pc_ctx *ctx, const std::vector<GatherSeg> &segs, void *out_K, void *out_V, int32_t *out_pos,
+               hipStream_t stream)
+{
+    // about 16 KiB of K (and as much of V) per workgroup
+    int rows_per_tile = (int)(16384 / ctx->row_bytes);
+    if (rows_per_tile < 1) rows_per_tile = 1;
+    for (size_t base = 0; base < segs.size(); base += kMaxGatherSegs) {
+        GatherArgs a;
+        a.n_segs = (int)std::min<size_t>(kMaxGatherSegs, segs.size() - base);
+        a.rows_per_tile = rows_per_tile;
+        a.row_bytes = (int)ctx->row_bytes;
+        int tiles = 0;
+        for (int i = 0; i < a.n_segs; ++i) {
+            a.seg[i] = segs[base + i];
+            a.seg[i].first_tile = tiles;
+            tiles += (a.seg[i].n_rows + rows_per_tile - 1) / rows_per_tile;
+        }
+        a.total_tiles = tiles;
+        int rc = launch_gather(ctx, a, static_cast<uint8_t *>(out_K), static_cast<uint8_t *>(out_V), out_pos, stream);
+        if (rc != PC_OK) return rc;
+    }
+    return PC_OK;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int run_attn(pc_ctx *ctx, const AttnBatch &b, const void *Q, const int32_t *q_pos, const void *K, const void *V,
+             const int32_t *pos, void *out, hipStream_t stream)
+{
+    if (ctx->cfg.dtype == PC_F32)
+        return launch_attn_f32(ctx, b, static_cast<const float *>(Q), q_pos, static_cast<const float *>(K),
+                               static_cast<const float *>(V), pos, static_cast<float *>(out), stream);
+    return launch_attn_bf16(ctx, b, Q, q_pos, K, V, pos, out, stream);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *pc_strerror(int status)
+{
+    switch (status) {
+    case PC_OK: return "ok";
+    case PC_E_BADARG: return "bad argument";
+    case PC_E_LAYER: return "layer out of range";
+    case PC_E_UNKNOWN_MODULE: return "module not stored for this layer";
+    case PC_E_OVERLAP: return "selected modules overlap in position IDs";
+    case PC_E_CAPACITY: return "output buffer or scratch too small";
+    case PC_E_POOL_FULL: return "module pool exhausted";
+    case PC_E_DUP_MODULE: return "module id already stored with another length or start position";
+    case PC_E_POS_RANGE: return "position ID outside [0, max_pos)";
+    case PC_E_UNSUPPORTED: return "unsupported head_dim / dtype";
+    case PC_E_HIP: return "HIP runtime error";
+    case PC_E_SCHEMA: return "malformed schema";
+    default: return "unknown status";
+    }
+}
+
+int pc_create(const pc_config *cfg, pc_ctx **out_ctx)
+{
+    if (!out_ctx) return PC_E_BADARG;
+    *out_ctx = nullptr;
+    int rc = validate_config(cfg);
+    if (rc != PC_OK) return rc;
+
+    pc_ctx *ctx = new (std::nothrow) pc_ctx();
+    if (!ctx) return PC_E_HIP;
+    ctx->cfg = *cfg;
+    ctx->elem_bytes = elem_size(cfg->dtype);
+    ctx->row_bytes = (size_t)cfg->n_kv_heads * cfg->head_dim * ctx->elem_bytes;
+    ctx->modules.resize(cfg->n_layers);
+    ctx->scratch_bytes = cfg->scratch_bytes ? cfg->scratch_bytes : kDefaultScratch;
+
+    bool ok = hipGetDevice(&ctx->device) == hipSuccess;
+    hipDeviceProp_t prop;
+    if (ok && hipGetDeviceProperties(&prop, ctx->device) == hipSuccess) ctx->n_cu = prop.multiProcessorCount;
+    if (ok && cfg->pool_bytes) ok = hipMalloc(reinterpret_cast<void **>(&ctx->pool), cfg->pool_bytes) == hipSuccess;
+    if (ok) ok = hipMalloc(reinterpret_cast<void **>(&ctx->scratch), ctx->scratch_bytes) == hipSuccess;
+
+    // RoPE table: (cos, sin) of pos * base^(-2i/d), angles in fp64 (Sec. 4.2: a table looked up by position ID)
+    const int half = cfg->head_dim / 2;
+    const size_t n_entries = (size_t)cfg->max_pos * half;
+    if (ok) ok = hipMalloc(reinterpret_cast<void **>(&ctx->rope_table), n_entries * sizeof(float2)) == hipSuccess;
+    if (ok) {
+        std::vector<float2> host(n_entries);
+        std::vector<double> theta(half);
+        for (int i = 0; i < half; ++i) theta[i] = pow(cfg->rope_base, -2.0 * (double)i / (double)cfg->head_dim);
+        for (int p = 0; p < cfg->max_pos; ++p)
+            for (int i = 0; i < half; ++i) {
+                const double a = (double)p * theta[i];
+                host[(size_t)p * half + i] = make_float2((float)cos(a), (float)sin(a));
+            }
+        ok = hipMemcpy(ctx->rope_table, host.data(), n_entries * sizeof(float2), hipMemcpyHostToDevice) == hipSuccess;
+    }
+    if (!ok) {
+        (void)hipGetLastError();
+        if (ctx->pool) (void)hipFree(ctx->pool);
+        if (ctx->scratch) (void)hipFree(ctx->scratch);
+        if (ctx->rope_table) (void)hipFree(ctx->rope_table);
+        delete ctx;
+        return PC_E_HIP;
+    }
+    *out_ctx = ctx;
+    return PC_OK;
+}
+
+static void free_profiler(pc_ctx *ctx)
+{
+    for (int k = 0; k < kProfKinds; ++k) {
+        for (hipEvent_t e : ctx->prof.start[k]) (void)hipEventDestroy(e);
+        for (hipEvent_t e : ctx->prof.stop[k]) (void)hipEventDestroy(e);
+        ctx->prof.start[k].clear();
+        ctx->prof.stop[k].clear();
+        ctx->prof.used[k] = 0;
+    }
+    ctx->prof.capacity = 0;
+}
+
+int pc_profile_enable(pc_ctx *ctx, int max_records_per_kind)
+{
+    if (!ctx || max_records_per_kind < 0) return PC_E_BADARG;
+    (void)hipDeviceSynchronize();
+    free_profiler(ctx);
+    for (int k = 0; k < kProfKinds; ++k)
+        for (int i = 0; i < max_records_per_kind; ++i) {
+            hipEvent_t a, b;
+            if (hipEventCreate(&a) != hipSuccess) { free_profiler(ctx); return PC_E_HIP; }
+            if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); free_profiler(ctx); return PC_E_HIP; }
+            ctx->prof.start[k].push_back(a);
+            ctx->prof.stop[k].push_back(b);
+        }
+    ctx->prof.capacity = max_records_per_kind;
+    return PC_OK;
+}
+
+int pc_profile_read(pc_ctx *ctx, int kind, int *n_records, double *total_ms)
+{
+    if (!ctx || kind < 0 || kind >= kProfKinds) return PC_E_BADARG;
+    double sum = 0.0;
+    const int n = ctx->prof.used[kind];
+    for (int i = 0; i < n; ++i) {
+        float ms = 0.f;
+        if (hipEventSynchronize(ctx->prof.stop[kind][i]) != hipSuccess ||
+            hipEventElapsedTime(&ms, ctx->prof.start[kind][i], ctx->prof.stop[kind][i]) != hipSuccess) {
+            (void)hipGetLastError();
+            return PC_E_HIP;
+        }
+        sum += ms;
+    }
+    ctx->prof.used[kind] = 0;
+    if (n_records) *n_records = n;
+    if (total_ms) *total_ms = sum;
+    return PC_OK;
+}
+
+int pc_destroy(pc_ctx *ctx)
+{
+    if (!ctx) return PC_E_BADARG;
+    (void)hipDeviceSynchronize();
+    free_profiler(ctx);
+    if (ctx->pool) (void)hipFree(ctx->pool);
+    if (ctx->scratch) (void)hipFree(ctx->scratch);
+    if (ctx->rope_table) (void)hipFree(ctx->rope_table);
+    delete ctx;
+    return PC_OK;
+}
+
+int pc_store_module(pc_ctx *ctx, int layer, int module_id, const void *K, const void *V, int n_tokens, int start_pos,
+                    void *stream)
+{
+    if (!ctx || module_id < 0 || n_tokens < 0) return PC_E_BADARG;
+    if (layer < 0 || layer >= ctx->cfg.n_layers) return PC_E_LAYER;
+    if (n_tokens > 0 && (!K || !V)) return PC_E_BADARG;
+    if (start_pos < 0 || (long)start_pos + n_tokens > (long)ctx->cfg.max_pos) return PC_E_POS_RANGE;
+
+    auto &table = ctx->modules[layer];
+    const size_t bytes = (size_t)n_tokens * ctx->row_bytes;
+    auto it = table.find(module_id);
+    ModuleEntry e;
+    if (it != table.end()) {
+        if (it->second.n_tokens != n_tokens || it->second.start_pos != start_pos) return PC_E_DUP_MODULE;
+        e = it->second;  // refresh in place
+    } else {
+        const size_t k_off = align_up(ctx->pool_used, kPoolAlign);
+        const size_t v_off = align_up(k_off + bytes, kPoolAlign);
+        if (v_off + bytes > ctx->cfg.pool_bytes) return PC_E_POOL_FULL;
+        e.k_offset = k_off;
+        e.v_offset = v_off;
+        e.n_tokens = n_tokens;
+        e.start_pos = start_pos;
+    }
+    if (bytes) {
+        if (hipMemcpyAsync(ctx->pool + e.k_offset, K, bytes, hipMemcpyDeviceToDevice, as_stream(stream)) != hipSuccess ||
+            hipMemcpyAsync(ctx->pool + e.v_offset, V, bytes, hipMemcpyDeviceToDevice, as_stream(stream)) != hipSuccess) {
+            (void)hipGetLastError();
+            return PC_E_HIP;
+        }
+    }
+    if (it == table.end()) {
+        table.emplace(module_id, e);
+        ctx->pool_used = e.v_offset + bytes;
+    }
+    return PC_OK;
+}
+
+int pc_assemble_kv(pc_ctx *ctx, int layer, const int *module_ids, int n_modules, void *out_K, void *out_V,
+                   int32_t *out_pos, int capacity_tokens, int *out_n_tokens, void *stream)
+{
+    if (!ctx || n_modules < 0 || capacity_tokens < 0 || (n_modules > 0 && !module_ids)) return PC_E_BADARG;
+    if (layer < 0 || layer >= ctx->cfg.n_layers) return PC_E_LAYER;
+    if (!out_K || !out_V || !out_pos || !aligned16(out_K) || !aligned16(out_V)) return PC_E_BADARG;
+    std::vector<GatherSeg> segs;
+    int rows = 0;
+    int rc = plan_prompt(ctx, layer, module_ids, n_modules, 0, capacity_tokens, segs, &rows);
+    if (rc != PC_OK) return rc;
+    rc = run_gather(ctx, segs, out_K, out_V, out_pos, as_stream(stream));
+    if (rc == PC_OK && out_n_tokens) *out_n_tokens = rows;
+    return rc;
+}
+
+int pc_assemble_kv_batched(pc_ctx *ctx, int layer, const int *module_ids_flat, const int *mod_offsets, int n_prompts,
+                           void *out_K, void *out_V, int32_t *out_pos, const int *kv_offsets, int *out_n_tokens,
+                           void *stream)
+{
+    if (!ctx || n_prompts < 0 || !mod_offsets || !kv_offsets) return PC_E_BADARG;
+    if (layer < 0 || layer >= ctx->cfg.n_layers) return PC_E_LAYER;
+    if (!out_K || !out_V || !out_pos || !aligned16(out_K) || !aligned16(out_V)) return PC_E_BADARG;
+    std::vector<GatherSeg> segs;
+    std::vector<int> rows(n_prompts, 0);
+    for (int b = 0; b < n_prompts; ++b) {
+        const int n = mod_offsets[b + 1] - mod_offsets[b];
+        const int cap = kv_offsets[b + 1] - kv_offsets[b];
+        if (n < 0 || cap < 0 || kv_offsets[b] < 0 || (n > 0 && !module_ids_flat)) return PC_E_BADARG;
+        int rc = plan_prompt(ctx, layer, module_ids_flat + mod_offsets[b], n, kv_offsets[b], cap, segs, &rows[b]);
+        if (rc != PC_OK) return rc;
+    }
+    int rc = run_gather(ctx, segs, out_K, out_V, out_pos, as_stream(stream));
+    if (rc == PC_OK && out_n_tokens)
+        for (int b = 0; b < n_prompts; ++b) out_n_tokens[b] = rows[b];
+    return rc;
+}
+
+int pc_rope(pc_ctx *ctx, void *x, int n_tokens, int n_heads, const int32_t *pos, void *stream)
+{
+    if (!ctx || n_tokens < 0 || n_heads <= 0) return PC_E_BADARG;
+    if (n_tokens == 0) return PC_OK;
+    if (!x || !pos) return PC_E_BADARG;
+    return launch_rope(ctx, x, n_tokens, n_heads, pos, as_stream(stream));
+}
+
+int pc_append_kv_batched(pc_ctx *ctx, int layer, const void *K_new_raw, const void *V_new, const int32_t *q_pos,
+                         const int *q_offsets, int n_prompts, void *asm_K, void *asm_V, int32_t *asm_pos,
+                         const int *kv_offsets, const int *kv_lens, void *stream)
+{
+    if (!ctx || n_prompts < 0 || !q_offsets || !kv_offsets || !kv_lens) return PC_E_BADARG;
+    if (layer < 0 || layer >= ctx->cfg.n_layers) return PC_E_LAYER;
+    for (int b = 0; b < n_prompts; ++b) {
+        const int n = q_offsets[b + 1] - q_offsets[b];
+        if (n < 0 || kv_lens[b] < 0 || q_offsets[b] < 0 || kv_offsets[b] < 0) return PC_E_BADARG;
+        if ((long)kv_offsets[b] + kv_lens[b] + n > (long)kv_offsets[b + 1]) return PC_E_CAPACITY;
+    }
+    if (n_prompts > 0 && q_offsets[n_prompts] > q_offsets[0] && (!K_new_raw || !V_new || !q_pos || !asm_K || !asm_V || !asm_pos))
+        return PC_E_BADARG;
+    for (int base = 0; base < n_prompts; base += kMaxAppendSegs) {
+        AppendArgs a;
+        a.n_segs = std::min(kMaxAppendSegs, n_prompts - base);
+        a.total_rows = 0;
+        for (int i = 0; i < a.n_segs; ++i) {
+            const int b = base + i;
+            a.seg[i].q_begin = q_offsets[b];
+            a.seg[i].n = q_offsets[b + 1] - q_offsets[b];
+            a.seg[i].dst_row = kv_offsets[b] + kv_lens[b];
+            a.total_rows += a.seg[i].n;
+        }
+        int rc = launch_append(ctx, a, K_new_raw, V_new, q_pos, asm_K, asm_V, asm_pos, as_stream(stream));
+        if (rc != PC_OK) return rc;
+    }
+    return PC_OK;
+}
+
+int pc_append_kv(pc_ctx *ctx, int layer, const void *K_new_raw, const void *V_new, const int32_t *q_pos, int n_q,
+                 void *asm_K, void *asm_V, int32_t *asm_pos, int n_kv_before, int capacity_tokens, void *stream)
+{
+    if (n_q < 0 || n_kv_before < 0 || capacity_tokens < 0) return PC_E_BADARG;
+    const int q_offsets[2] = {0, n_q};
+    const int kv_offsets[2] = {0, capacity_tokens};
+    const int kv_lens[1] = {n_kv_before};
+    return pc_append_kv_batched(ctx, layer, K_new_raw, V_new, q_pos, q_offsets, 1, asm_K, asm_V, asm_pos, kv_offsets,
+                                kv_lens, stream);
+}
+
+int pc_prefill_attn_batched(pc_ctx *ctx, int layer, const void *Q_new, const int32_t *q_pos, const int *q_offsets,
+                            int n_prompts, const void *asm_K, const void *asm_V, const int32_t *asm_pos,
+                            const int *kv_offsets, const int *kv_lens, void *out, void *stream)
+{
+    if (!ctx || n_prompts < 0 || !q_offsets || !kv_offsets || !kv_lens) return PC_E_BADARG;
+    if (layer < 0 || layer >= ctx->cfg.n_layers) return PC_E_LAYER;
+    long total_q = 0;
+    for (int b = 0; b < n_prompts; ++b) {
+        const int n = q_offsets[b + 1] - q_offsets[b];
+        if (n < 0 || kv_lens[b] < 0 || q_offsets[b] < 0 || kv_offsets[b] < 0) return PC_E_BADARG;
+        total_q += n;
+    }
+    if (total_q == 0) return PC_OK;
+    if (!Q_new || !q_pos || !out || !aligned16(Q_new) || !aligned16(out)) return PC_E_BADARG;
+    bool any_kv = false;
+    for (int b = 0; b < n_prompts; ++b) any_kv |= kv_lens[b] > 0;
+    if (any_kv && (!asm_K || !asm_V || !asm_pos || !aligned16(asm_K) || !aligned16(asm_V))) return PC_E_BADARG;
+
+    for (int base = 0; base < n_prompts; base += kMaxAttnSeqs) {
+        AttnBatch ab;
+        ab.n_seqs = std::min(kMaxAttnSeqs, n_prompts - base);
+        for (int i = 0; i < ab.n_seqs; ++i) {
+            const int b = base + i;
+            ab.seq[i].q_begin = q_offsets[b];
+            ab.seq[i].n_q = q_offsets[b + 1] - q_offsets[b];
+            ab.seq[i].kv_begin = kv_offsets[b];
+            ab.seq[i].n_kv = kv_lens[b];
+        }
+        int rc = run_attn(ctx, ab, Q_new, q_pos, asm_K, asm_V, asm_pos, out, as_stream(stream));
+        if (rc != PC_OK) return rc;
+    }
+    return PC_OK;
+}
+
+int pc_prefill_attn(pc_ctx *ctx, int layer, const void *Q_new, const int32_t *q_pos, int n_q, const void *asm_K,
+                    const void *asm_V, const int32_t *asm_pos, int n_kv, void *out, void *stream)
+{
+    if (n_q < 0 || n_kv < 0) return PC_E_BADARG;
+    const int q_offsets[2] = {0, n_q};
+    const int kv_offsets[2] = {0, n_kv};
+    const int kv_lens[1] = {n_kv};
+    return pc_prefill_attn_batched(ctx, layer, Q_new, q_pos, q_offsets, 1, asm_K, asm_V, asm_pos, kv_offsets, kv_lens,
+                                   out, stream);
+}
+
+/* ------------------------------------------------------------ host integers */
+
+long pc_schema_layout(int n, const int *sizes, const int *union_ids, int *starts)
+{
+    if (n < 0 || (n > 0 && (!sizes || !union_ids || !starts))) return PC_E_SCHEMA;
+    // a union's children must form one contiguous run
+    std::vector<int> closed;
+    for (int i = 0; i < n; ++i) {
+        if (sizes[i] < 0) return PC_E_SCHEMA;
+        const int u = union_ids[i];
+        if (u < 0) continue;
+        const bool continues = i > 0 && union_ids[i - 1] == u;
+        if (!continues) {
+            if (std::find(closed.begin(), closed.end(), u) != closed.end()) return PC_E_SCHEMA;
+            closed.push_back(u);
+        }
+    }
+    long next_free = 0;       // first position ID after everything laid out so far
+    long union_start = 0;     // start shared by the children of the union being laid out
+    for (int i = 0; i < n; ++i) {
+        const int u = union_ids[i];
+        const bool in_union = u >= 0;
+        const bool continues = in_union && i > 0 && union_ids[i - 1] == u;
+        if (!continues) union_start = next_free;
+        const long begin = in_union ? union_start : next_free;
+        starts[i] = (int)begin;
+        next_free = std::max(next_free, begin + sizes[i]);
+    }
+    return next_free;
+}
+
+int pc_uncached_positions(int prev_start, int prev_len, int n_tokens, int32_t *pos)
+{
+    if (prev_start < 0 || prev_len < 0 || n_tokens < 0 || (n_tokens > 0 && !pos)) return PC_E_BADARG;
+    const int first = prev_start + prev_len;
+    for (int i = 0; i < n_tokens; ++i) pos[i] = first + i;
+    return PC_OK;
+}
+
+int pc_check_selection(int n, const int *starts, const int *lens, int max_pos)
+{
+    return check_ranges(n, starts, lens, max_pos);
+}
+
+long pc_bytes_per_token(int n_layers, int n_kv_heads, int head_dim, int dtype)
+{
+    const int es = elem_size(dtype);
+    if (n_layers <= 0 || n_kv_heads <= 0 || head_dim <= 0 || es == 0) return PC_E_BADARG;
+    return (long)n_layers * 2 /* K and V */ * n_kv_heads * head_dim * es;
+}
+
+int pc_module_info(const pc_ctx *ctx, int layer, int module_id, int *n_tokens, int *start_pos)
+{
+    if (!ctx) return PC_E_BADARG;
+    if (layer < 0 || layer >= ctx->cfg.n_layers) return PC_E_LAYER;
+    auto it = ctx->modules[layer].find(module_id);
+    if (it == ctx->modules[layer].end()) return PC_E_UNKNOWN_MODULE;
+    if (n_tokens) *n_tokens = it->second.n_tokens;
+    if (start_pos) *start_pos = it->second.start_pos;
+    return PC_OK;
+}
+
+int pc_pool_usage(const pc_ctx *ctx, size_t *used, size_t *total)
+{
+    if (!ctx) return PC_E_BADARG;
+    if (used) *used = ctx->pool_used;
+    if (total) *total = ctx->cfg.pool_bytes;
+    return PC_OK;
+}
+
+int pc_last_attn_launch(const pc_ctx *ctx, int *n_splits, int *n_workgroups, int *waves_per_wg)
+{
+    if (!ctx) return PC_E_BADARG;
+    if (n_splits) *n_splits = ctx->last_attn.n_splits;
+    if (n_workgroups) *n_workgroups = ctx->last_attn.n_workgroups;
+    if (waves_per_wg) *waves_per_wg = ctx->last_attn.waves_per_wg;
+    return PC_OK;
+}
+
+}  // extern "C"

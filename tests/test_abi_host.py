@@ -1,0 +1,126 @@
+"""CPU-only checks of the C-ABI library: it loads, exports what the header declares, and its
+host-side integer logic agrees with the oracle and the paper.  No kernel is launched here."""
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2311_04934_amd import binding as pcb
+from paper_2311_04934_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "promptcache.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pc_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = pcb.lib()
+    declared = _declared_symbols()
+    assert len(declared) >= 15
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert sorted(pcb.EXPORTS) == declared
+
+
+def test_strerror_names_every_status():
+    seen = set()
+    for code in range(0, -12, -1):
+        s = pcb.strerror(code)
+        assert s and s != "unknown status"
+        seen.add(s)
+    assert len(seen) == 12
+    assert pcb.strerror(-99) == "unknown status"
+
+
+def test_schema_layout_printed_example_and_union_rule():
+    starts, span = pcb.pc_schema_layout([50, 60, 7])
+    assert starts == [0, 50, 110] and span == 117          # Sec. 3.3 worked example
+    starts, span = pcb.pc_schema_layout([5, 7, 3, 9, 4], [-1, 0, 0, 0, -1])
+    assert starts == [0, 5, 5, 5, 14] and span == 18        # union: shared start, spans largest child
+
+
+def test_schema_layout_agrees_with_oracle_on_random_schemas():
+    rng = np.random.default_rng(100)
+    for _ in range(200):
+        sizes, uids = [], []
+        for g in range(int(rng.integers(1, 10))):
+            if rng.random() < 0.5:
+                sizes.append(int(rng.integers(0, 600))); uids.append(-1)
+            else:
+                for s in rng.integers(0, 600, size=int(rng.integers(1, 5))):
+                    sizes.append(int(s)); uids.append(g)
+        assert pcb.pc_schema_layout(sizes, uids) == oracle.layout(sizes, uids)
+
+
+def test_schema_layout_rejects_malformed_schemas():
+    with pytest.raises(pcb.PcError):
+        pcb.pc_schema_layout([1, 2, 3], [0, -1, 0])
+    with pytest.raises(pcb.PcError):
+        pcb.pc_schema_layout([1, -2], [-1, -1])
+    with pytest.raises(ValueError):
+        oracle.layout([1, 2, 3], [0, -1, 0])
+
+
+@pytest.mark.parametrize("make", [W.tiny_fp32, W.llama7b_doc, W.long_doc_8k, W.sparse_selection, W.batched_serving])
+def test_workload_layouts_agree_and_fit(make):
+    w = make()
+    a = pcb.pc_schema_layout(w.sizes, w.union_ids)
+    assert a == oracle.layout(w.sizes, w.union_ids)
+    starts, span = a
+    for p in w.prompts:
+        ends = [starts[m] + w.sizes[m] for m in p.module_ids]
+        assert max(ends) + p.n_new <= w.max_pos
+        assert pcb.pc_check_selection([starts[m] for m in p.module_ids], [w.sizes[m] for m in p.module_ids], w.max_pos) == 0
+
+
+def test_uncached_positions_agree_with_oracle():
+    for prev in [(0, 0), (110, 40), (8000, 192)]:
+        assert np.array_equal(pcb.pc_uncached_positions(prev[0], prev[1], 9), oracle.text_positions(prev[0], prev[1], 9))
+
+
+def test_check_selection():
+    assert pcb.pc_check_selection([0, 128, 256], [128, 128, 128], 1024) == 0
+    assert pcb.pc_check_selection([256, 0], [128, 128], 1024) == 0            # order irrelevant, gap fine
+    assert pcb.pc_check_selection([0, 100], [128, 10], 1024) == -4            # overlap
+    assert pcb.pc_check_selection([5, 5], [7, 9], 1024) == -4                 # two children of one union
+    assert pcb.pc_check_selection([5, 5], [0, 9], 1024) == 0                  # an empty module overlaps nothing
+    assert pcb.pc_check_selection([1000], [100], 1024) == -8                  # beyond max_pos
+    assert pcb.pc_check_selection([-1], [3], 1024) == -1
+
+
+def test_bytes_per_token_table2():
+    rows = [ln.split() for ln in open(os.path.join(GOLDEN, "table2_mb_per_token.txt")) if ln.strip() and ln[0] != "#"]
+    for name, layers, hidden, printed in rows:
+        b = pcb.pc_bytes_per_token(int(layers), 1, int(hidden), pcb.PC_BF16)
+        assert b == oracle.bytes_per_token(int(layers), 1, int(hidden), 2)
+        decimals = len(printed.split(".")[1])
+        assert abs(math.floor(b / 2 ** 20 * 10 ** decimals) / 10 ** decimals - float(printed)) < 1e-9, name
+    # with GQA the hidden size is replaced by kv_heads*head_dim
+    assert pcb.pc_bytes_per_token(32, 8, 128, pcb.PC_BF16) == 32 * 2 * 8 * 128 * 2
+
+
+def test_create_rejects_bad_configs_before_touching_the_gpu():
+    import ctypes
+    def create(**kw):
+        base = dict(n_layers=1, n_q_heads=8, n_kv_heads=8, head_dim=64, dtype=0, rope_base=10000.0, max_pos=64,
+                    pool_bytes=0, scratch_bytes=1 << 20)
+        base.update(kw)
+        cfg = pcb.PcConfig(**base)
+        ctx = ctypes.c_void_p()
+        rc = pcb.lib().pc_create(ctypes.byref(cfg), ctypes.byref(ctx))
+        if rc == 0:
+            pcb.lib().pc_destroy(ctx)
+        return rc
+    assert create(n_q_heads=6, n_kv_heads=4) == -1
+    assert create(dtype=1, head_dim=96) == -9
+    assert create(dtype=7) == -9
+    assert create(max_pos=0) == -1
+    assert create(n_layers=0) == -1
