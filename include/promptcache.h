@@ -255,11 +255,11 @@ int pc_last_attn_launch(const pc_ctx *ctx, int *n_splits, int *n_workgroups, int
 /*
  * Optional per-kernel timing for benchmarks.  pc_profile_enable(ctx, n) creates n HIP event
  * pairs per kernel kind (n = 0 turns profiling off and frees them; it synchronises the
- * device).  While enabled, every kernel launch of the library is bracketed by a pair of
- * events recorded on the stream the kernel is launched on, until the pairs of its kind are
- * used up.  pc_profile_read waits for the recorded events of one kind, returns how many
- * launches were timed and the sum of their durations in milliseconds, and resets that
- * kind's counter.  kind: 0 gather (pc_assemble_kv*), 1 append, 2 attention main kernel,
+ * device).  While enabled, every kernel the library launches carries one pair of its kind
+ * (until they are used up), which then holds that kernel's own begin and end timestamps on
+ * the stream it ran on.  pc_profile_read waits for the recorded events of one kind, returns
+ * how many launches were timed and the sum of their durations in milliseconds, and resets
+ * that kind's counter.  kind: 0 gather (pc_assemble_kv*), 1 append, 2 attention main kernel,
  * 3 split-KV merge, 4 pc_rope.
  */
 int pc_profile_enable(pc_ctx *ctx, int max_records_per_kind);

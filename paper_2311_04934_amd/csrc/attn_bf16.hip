@@ -31,21 +31,14 @@
 //   XCD        workgroups are handed out round-robin over the 8 XCDs, so the group
 //                index is laid out such that all row blocks of one (kv head, split)
 //                land on the same XCD and share its L2.
-#include "common.h"
+#include <stdlib.h>
+
+#include "attn_bf16.h"
 
 namespace pc {
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-
-constexpr int KT = 64;          // keys per LDS tile
-constexpr int RW = 32;          // query rows per wave
-constexpr int kPosInf = 0x7fffffff;
+using namespace attn;
 
 template <int D>
 struct Lds {
@@ -58,43 +51,6 @@ struct Lds {
     static constexpr int BUF_BYTES = K_BYTES + V_BYTES + POS_BYTES + META_BYTES;
     static constexpr int TOTAL = 2 * BUF_BYTES;
 };
-
-struct AttnParams {
-    const uint16_t *q;       // [total_q][Hq][D] bf16 bits
-    const int32_t *q_pos;
-    const uint16_t *k;       // [total_kv][Hkv][D]
-    const uint16_t *v;
-    const int32_t *kv_pos;
-    uint16_t *out;           // [total_q][Hq][D]
-    float *part_o;           // [n_splits][total_q][Hq][D]
-    float2 *part_ml;         // [n_splits][total_q][Hq]
-    const float2 *rope;      // [max_pos][D/2]
-    int max_pos;
-    int Hq, Hkv, G;
-    int n_splits;
-    int rb_max;              // row blocks per (prompt, kv head)
-    int n_groups;            // n_seqs * n_splits * Hkv
-    int total_q;
-    float q_scale;           // log2(e) / sqrt(D)
-    AttnBatch batch;
-};
-
-__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
-
-__device__ __forceinline__ float wave_xor32(float x) { return __shfl_xor(x, 32, 64); }
-
-__device__ __forceinline__ int wave_min_i32(int x)
-{
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) x = min(x, __shfl_xor(x, o, 64));
-    return x;
-}
-__device__ __forceinline__ int wave_max_i32(int x)
-{
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) x = max(x, __shfl_xor(x, o, 64));
-    return x;
-}
 
 // 4x4 transpose of 16-bit values held as four (lo,hi) dword pairs: in[e] = 4 dims of key e,
 // out[i] = 4 keys of dim i.
@@ -110,7 +66,18 @@ __device__ __forceinline__ void transpose4x4_b16(const u32x2 in[4], u32x2 out[4]
     out[3].y = (in[2].y >> 16) | (in[3].y & 0xffff0000u);
 }
 
+// Registers that carry one K/V tile from global memory to LDS.
 template <int D, int NW>
+struct TileRegs {
+    static constexpr int NT = NW * 64;
+    static constexpr int K_PER_T = (KT * D / 8 + NT - 1) / NT;
+    static constexpr int V_PER_T = (16 * (D / 4) + NT - 1) / NT;
+    u32x4 k[K_PER_T];
+    u32x2 v[V_PER_T][4];
+    int pos;
+};
+
+template <int D, int NW, int PF>
 __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p)
 {
     constexpr int NT = NW * 64;
@@ -118,9 +85,8 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p)
     constexpr int DB = D / 32;              // 32-row blocks of O^T
     constexpr int K_CHUNKS = KT * D / 8;    // 16-byte chunks in a K tile
     constexpr int V_BLOCKS = 16 * (D / 4);  // 4-key x 4-dim blocks in a V tile
-    constexpr int K_PER_T = (K_CHUNKS + NT - 1) / NT;
-    constexpr int V_PER_T = (V_BLOCKS + NT - 1) / NT;
     using L = Lds<D>;
+    using Regs = TileRegs<D, NW>;
 
     extern __shared__ __align__(16) uint8_t smem[];
 
@@ -136,17 +102,20 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p)
     const int g = (slot / p.rb_max) * 8 + xcd;
     const int rb = slot % p.rb_max;
     if (g >= p.n_groups) return;
-    const int kvh = g % p.Hkv;
-    const int split = (g / p.Hkv) % p.n_splits;
-    const int seq_i = g / (p.Hkv * p.n_splits);
+    const int split = g % p.n_splits;
+    const int seq_i = (g / p.n_splits) % p.batch.n_seqs;
+    const int kvh = g / (p.n_splits * p.batch.n_seqs);
     const AttnSeq seq = p.batch.seq[seq_i];
 
     const int tiles_q = (seq.n_q + RW - 1) / RW;
     const int row_tiles = p.G * tiles_q;
     if (rb * NW >= row_tiles) return;   // whole workgroup has nothing to do
-    const int n_tiles = (seq.n_kv + KT - 1) / KT;
-    const int t0 = (int)(((long)split * n_tiles) / p.n_splits);
-    const int t1 = (int)(((long)(split + 1) * n_tiles) / p.n_splits);
+
+    // this split's key range: equal shares rounded up to a multiple of 32 keys
+    const int share = (((seq.n_kv + p.n_splits - 1) / p.n_splits) + 31) & ~31;
+    const int k_begin = split * share < seq.n_kv ? split * share : seq.n_kv;
+    const int k_end = k_begin + share < seq.n_kv ? k_begin + share : seq.n_kv;
+    const int n_tiles = (k_end - k_begin + KT - 1) / KT;
 
     // ---- this wave's row tile
     const int rt = rb * NW + wave;
@@ -198,61 +167,70 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p)
     float m_run = -INFINITY;  // running max (log2 domain), identical in both halves of the wave
     float l_run = 0.f;        // this lane's share of the running sum (halves added at the end)
 
-    // ---- staging registers for the next K/V tile
-    u32x4 k_reg[K_PER_T];
-    u32x2 v_reg[V_PER_T][4];
-    int pos_reg = kPosInf;
-
     const size_t kv_row_stride = (size_t)p.Hkv * D;  // elements
     const uint16_t *k_base = p.k + (size_t)seq.kv_begin * kv_row_stride + (size_t)kvh * D;
     const uint16_t *v_base = p.v + (size_t)seq.kv_begin * kv_row_stride + (size_t)kvh * D;
     const int32_t *pos_base = p.kv_pos + seq.kv_begin;
 
-    auto load_tile = [&](int t) {
-        const int row0 = t * KT;
+    // global -> registers.  Branch-free: rows at or past k_end are read from the last valid row
+    // and then zeroed (position +inf), so all loads of a tile are in flight together.
+    auto load_tile = [&](int t, Regs &r) {
+        if (p.debug == 2 && t > 1) return;
+        const int row0 = k_begin + t * KT;
+        const int last = k_end - 1;
 #pragma unroll
-        for (int it = 0; it < K_PER_T; ++it) {
+        for (int it = 0; it < Regs::K_PER_T; ++it) {
             const int c = tid + it * NT;
-            const int r = c / (D / 8), ch = c % (D / 8);
-            u32x4 val = {0u, 0u, 0u, 0u};
-            if (c < K_CHUNKS && row0 + r < seq.n_kv)
-                val = *reinterpret_cast<const u32x4 *>(k_base + (size_t)(row0 + r) * kv_row_stride + ch * 8);
-            k_reg[it] = val;
-        }
-#pragma unroll
-        for (int it = 0; it < V_PER_T; ++it) {
-            const int c = tid + it * NT;
-            const int dc = c % (D / 4), kg = c / (D / 4);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int r = kg * 4 + e;
-                u32x2 val = {0u, 0u};
-                if (c < V_BLOCKS && row0 + r < seq.n_kv)
-                    val = *reinterpret_cast<const u32x2 *>(v_base + (size_t)(row0 + r) * kv_row_stride + dc * 4);
-                v_reg[it][e] = val;
+            if (K_CHUNKS % NT == 0 || c < K_CHUNKS) {
+                const int row = row0 + c / (D / 8), ch = c % (D / 8);
+                const int rc = row < last ? row : last;
+                u32x4 val = *reinterpret_cast<const u32x4 *>(k_base + (size_t)rc * kv_row_stride + ch * 8);
+                if (row > last) val = u32x4{0u, 0u, 0u, 0u};
+                r.k[it] = val;
             }
         }
-        if (tid < KT) pos_reg = (row0 + tid < seq.n_kv) ? pos_base[row0 + tid] : kPosInf;
+#pragma unroll
+        for (int it = 0; it < Regs::V_PER_T; ++it) {
+            const int c = tid + it * NT;
+            if (V_BLOCKS % NT == 0 || c < V_BLOCKS) {
+                const int dc = c % (D / 4), kg = c / (D / 4);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int row = row0 + kg * 4 + e;
+                    const int rc = row < last ? row : last;
+                    u32x2 val = *reinterpret_cast<const u32x2 *>(v_base + (size_t)rc * kv_row_stride + dc * 4);
+                    if (row > last) val = u32x2{0u, 0u};
+                    r.v[it][e] = val;
+                }
+            }
+        }
+        {   // every wave reads the tile's 64 position IDs (one per lane); wave 0's copy is the one stored
+            const int row = row0 + lane;
+            const int rc = row < last ? row : last;
+            const int pv = pos_base[rc];
+            r.pos = row > last ? kPosInf : pv;
+        }
     };
 
-    auto store_tile = [&](int buf) {
+    // registers -> LDS (K as is, V transposed, positions and their range)
+    auto store_tile = [&](int buf, const Regs &r) {
         uint8_t *sK = smem + buf * L::BUF_BYTES;
         uint8_t *sV = sK + L::K_BYTES;
         int32_t *sPos = reinterpret_cast<int32_t *>(sV + L::V_BYTES);
         int32_t *sMeta = sPos + KT;
 #pragma unroll
-        for (int it = 0; it < K_PER_T; ++it) {
+        for (int it = 0; it < Regs::K_PER_T; ++it) {
             const int c = tid + it * NT;
-            const int r = c / (D / 8), ch = c % (D / 8);
-            if (c < K_CHUNKS) *reinterpret_cast<u32x4 *>(sK + r * L::K_STRIDE + ch * 16) = k_reg[it];
+            const int rr = c / (D / 8), ch = c % (D / 8);
+            if (K_CHUNKS % NT == 0 || c < K_CHUNKS) *reinterpret_cast<u32x4 *>(sK + rr * L::K_STRIDE + ch * 16) = r.k[it];
         }
 #pragma unroll
-        for (int it = 0; it < V_PER_T; ++it) {
+        for (int it = 0; it < Regs::V_PER_T; ++it) {
             const int c = tid + it * NT;
             const int dc = c % (D / 4), kg = c / (D / 4);
-            if (c < V_BLOCKS) {
+            if (V_BLOCKS % NT == 0 || c < V_BLOCKS) {
                 u32x2 tr[4];
-                transpose4x4_b16(v_reg[it], tr);
+                transpose4x4_b16(r.v[it], tr);
                 // keys 4*kg .. 4*kg+3 of the tile; inside each block of 16 keys the four
                 // 4-key groups are stored in the order 0,2,1,3 so that the 8 keys a lane
                 // needs for one PV MFMA are contiguous
@@ -265,15 +243,80 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p)
             }
         }
         if (tid < KT) {
-            sPos[tid] = pos_reg;
+            sPos[tid] = r.pos;
             // wave 0 holds all 64 position IDs of the tile: publish their range
-            const int real_min = wave_min_i32(pos_reg);                         // padding is +inf
-            const int real_max = wave_max_i32(pos_reg);                         // +inf if any padding
+            const int real_min = wave_min_i32(r.pos);  // padding is +inf
+            const int real_max = wave_max_i32(r.pos);  // +inf if any padding
             if (tid == 0) { sMeta[0] = real_min; sMeta[1] = real_max; }
         }
     };
 
-    auto compute_tile = [&](int buf) {
+    // S^T (32 keys x 32 queries) = K_sub . Q^T for one 32-key half of the tile
+    auto qk = [&](const uint8_t *sK, int sub) -> f32x16 {
+        f32x16 s;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s[i] = 0.f;
+        const uint8_t *krow = sK + (sub * 32 + col) * L::K_STRIDE + hh * 16;
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+            u32x4 raw = *reinterpret_cast<const u32x4 *>(krow + kb * 32);
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, raw), qf[kb], s, 0, 0, 0);
+        }
+        return s;
+    };
+
+    // mask (if needed) + online softmax of one score tile; rescales O when the running max moved
+    auto softmax = [&](f32x16 &s, const int32_t *sPos, int sub, bool need_mask, bf16x8 pf[2]) {
+        if (need_mask) {
+            // accumulator register i holds key 8*(i/4) + 4*hh + i%4 of the sub-tile
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+                const u32x4 kp = *reinterpret_cast<const u32x4 *>(sPos + sub * 32 + 8 * i4 + 4 * hh);
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if ((int)kp[e] > my_qpos) s[i4 * 4 + e] = -INFINITY;
+            }
+        }
+        float mx = s[0];
+#pragma unroll
+        for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[i]);
+        mx = max_across_halves(mx);
+        const float m_new = mx > m_run + kMaxSlack ? mx : m_run;
+        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
+        m_run = m_new;
+        float psum = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const float pv = __builtin_amdgcn_exp2f(s[i] - m_use);
+            psum += pv;
+            pf[i >> 3][i & 7] = (__bf16)pv;
+        }
+        l_run = l_run * alpha + psum;
+        if (__any(alpha != 1.f)) {
+#pragma unroll
+            for (int b = 0; b < DB; ++b)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) o_acc[b][i] *= alpha;
+        }
+    };
+
+    // O^T (D x 32 queries) += V^T_sub . P^T
+    auto pv_mma = [&](const uint8_t *sV, int sub, const bf16x8 pf[2]) {
+        const uint8_t *vrow = sV + col * L::V_STRIDE + (sub * 2) * 32 + hh * 16;
+#pragma unroll
+        for (int b = 0; b < DB; ++b) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                u32x4 raw = *reinterpret_cast<const u32x4 *>(vrow + b * 32 * L::V_STRIDE + j * 32);
+                o_acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, raw), pf[j], o_acc[b], 0, 0, 0);
+            }
+        }
+    };
+
+    // One 64-key tile.  Both score tiles are issued before the first softmax so that the matrix
+    // pipe works on the second while the vector ALU runs the first one's softmax.
+    auto compute_tile = [&](int buf, int t) {
         const uint8_t *sK = smem + buf * L::BUF_BYTES;
         const uint8_t *sV = sK + L::K_BYTES;
         const int32_t *sPos = reinterpret_cast<const int32_t *>(sV + L::V_BYTES);
@@ -282,84 +325,59 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p)
         const int tile_max = __builtin_amdgcn_readfirstlane(sMeta[1]);
         if (tile_min > wave_max_qpos) return;             // nothing in this tile is visible to this wave
         const bool need_mask = tile_max > wave_min_qpos;  // some (query, key) pair is hidden
-
-#pragma unroll
-        for (int sub = 0; sub < KT / 32; ++sub) {
-            // S^T (32 keys x 32 queries) = K_sub . Q^T
-            f32x16 s;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) s[i] = 0.f;
-            const uint8_t *krow = sK + (sub * 32 + col) * L::K_STRIDE + hh * 16;
-#pragma unroll
-            for (int kb = 0; kb < KB; ++kb) {
-                u32x4 raw = *reinterpret_cast<const u32x4 *>(krow + kb * 32);
-                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, raw), qf[kb], s, 0, 0, 0);
-            }
-            if (need_mask) {
-                // accumulator register i holds key 8*(i/4) + 4*hh + i%4 of the sub-tile
-#pragma unroll
-                for (int i4 = 0; i4 < 4; ++i4) {
-                    const u32x4 kp = *reinterpret_cast<const u32x4 *>(sPos + sub * 32 + 8 * i4 + 4 * hh);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if ((int)kp[e] > my_qpos) s[i4 * 4 + e] = -INFINITY;
-                }
-            }
-            // online softmax for the lane's query column
-            float mx = s[0];
-#pragma unroll
-            for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[i]);
-            mx = fmaxf(mx, wave_xor32(mx));
-            const float m_new = fmaxf(m_run, mx);
-            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
-            m_run = m_new;
-            float psum = 0.f;
-            bf16x8 pf[2];
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const float pv = __builtin_amdgcn_exp2f(s[i] - m_use);
-                psum += pv;
-                pf[i >> 3][i & 7] = (__bf16)pv;
-            }
-            l_run = l_run * alpha + psum;
-            if (__any(alpha != 1.f)) {
-#pragma unroll
-                for (int b = 0; b < DB; ++b)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) o_acc[b][i] *= alpha;
-            }
-            // O^T (D x 32 queries) += V^T_sub . P^T
-            const uint8_t *vrow = sV + col * L::V_STRIDE + (sub * 2) * 32 + hh * 16;
-#pragma unroll
-            for (int b = 0; b < DB; ++b) {
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    u32x4 raw = *reinterpret_cast<const u32x4 *>(vrow + b * 32 * L::V_STRIDE + j * 32);
-                    o_acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, raw), pf[j], o_acc[b], 0, 0, 0);
-                }
-            }
+        const bool second = k_begin + t * KT + 32 < k_end;  // the tile's second half holds real keys
+        bf16x8 pf[2];
+        f32x16 s0 = qk(sK, 0);
+        if (second) {
+            f32x16 s1 = qk(sK, 1);
+            softmax(s0, sPos, 0, need_mask, pf);
+            pv_mma(sV, 0, pf);
+            softmax(s1, sPos, 1, need_mask, pf);
+            pv_mma(sV, 1, pf);
+        } else {
+            softmax(s0, sPos, 0, need_mask, pf);
+            pv_mma(sV, 0, pf);
         }
     };
 
-    // ---- main loop over this split's key tiles (double-buffered LDS)
-    if (t0 < t1) {
-        load_tile(t0);
-        store_tile(0);
-        __syncthreads();
-        for (int t = t0; t < t1; ++t) {
-            const int buf = (t - t0) & 1;
-            const bool more = t + 1 < t1;
-            if (more) load_tile(t + 1);
-            if (wave_active) compute_tile(buf);
-            if (more) store_tile(buf ^ 1);
+    // ---- main loop: LDS double buffer; global loads run PF tiles ahead of their use
+    if (n_tiles > 0 && p.debug < 3) {
+        if constexpr (PF == 2) {
+            Regs ra, rb_;
+            load_tile(0, ra);
+            if (n_tiles > 1) load_tile(1, rb_);
+            store_tile(0, ra);
             __syncthreads();
+            if (n_tiles > 2) load_tile(2, ra);
+            for (int t = 0; t < n_tiles; t += 2) {
+                if (wave_active && p.debug != 1) compute_tile(0, t);
+                if (t + 1 < n_tiles) store_tile(1, rb_);
+                __syncthreads();
+                if (t + 1 >= n_tiles) break;
+                if (t + 3 < n_tiles) load_tile(t + 3, rb_);
+                if (wave_active && p.debug != 1) compute_tile(1, t + 1);
+                if (t + 2 < n_tiles) store_tile(0, ra);
+                __syncthreads();
+                if (t + 4 < n_tiles) load_tile(t + 4, ra);
+            }
+        } else {
+            Regs ra;
+            load_tile(0, ra);
+            store_tile(0, ra);
+            __syncthreads();
+            for (int t = 0; t < n_tiles; ++t) {
+                const bool more = t + 1 < n_tiles;
+                if (more) load_tile(t + 1, ra);
+                if (wave_active && p.debug != 1) compute_tile(t & 1, t);
+                if (more) store_tile((t + 1) & 1, ra);
+                __syncthreads();
+            }
         }
     }
 
     // ---- epilogue
-    if (!q_valid) return;
-    const float l_tot = l_run + wave_xor32(l_run);
+    if (!q_valid || p.debug == 4) return;
+    const float l_tot = sum_across_halves(l_run);
     const size_t out_row = (size_t)(seq.q_begin + qi) * p.Hq + head;
     if (p.n_splits == 1) {
         const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
@@ -421,20 +439,18 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float *part_o, 
     *reinterpret_cast<bf16x4 *>(out + (size_t)row * D + ch * 4) = w4;
 }
 
-template <int D, int NW>
+template <int D, int NW, int PF>
 int launch_variant(pc_ctx *ctx, AttnParams &p, int n_blocks, hipStream_t stream)
 {
     static bool attr_set[16] = {false};
-    auto kern = attn_bf16_kernel<D, NW>;
+    auto kern = attn_bf16_kernel<D, NW, PF>;
     const int smem = Lds<D>::TOTAL;
     if (!attr_set[ctx->device & 15]) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
             return PC_E_HIP;
         attr_set[ctx->device & 15] = true;
     }
-    ProfScope prof(ctx, kProfAttn, stream);
-    hipLaunchKernelGGL(kern, dim3(n_blocks), dim3(NW * 64), smem, stream, p);
-    return hip_status(hipGetLastError());
+    return launch_kernel(ctx, kProfAttn, kern, dim3(n_blocks), dim3(NW * 64), smem, stream, p);
 }
 
 }  // namespace
@@ -445,28 +461,34 @@ int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const i
     const int D = ctx->cfg.head_dim, Hq = ctx->cfg.n_q_heads, Hkv = ctx->cfg.n_kv_heads, G = Hq / Hkv;
     if (D != 64 && D != 128) return PC_E_UNSUPPORTED;
 
-    int total_q = 0, q_lo = 1 << 30, max_row_tiles = 0, min_kv_tiles = 1 << 30;
+    int total_q = 0, q_lo = 1 << 30, max_row_tiles = 0, min_kv = 1 << 30;
     for (int s = 0; s < batch.n_seqs; ++s) {
         const AttnSeq &sq = batch.seq[s];
         total_q = sq.q_begin + sq.n_q > total_q ? sq.q_begin + sq.n_q : total_q;
         q_lo = sq.q_begin < q_lo ? sq.q_begin : q_lo;
         const int rt = G * ((sq.n_q + RW - 1) / RW);
         if (rt > max_row_tiles) max_row_tiles = rt;
-        const int kt = (sq.n_kv + KT - 1) / KT;
-        if (kt < min_kv_tiles) min_kv_tiles = kt;
+        if (sq.n_q > 0 && sq.n_kv < min_kv) min_kv = sq.n_kv;
     }
     if (total_q == 0 || max_row_tiles == 0) return PC_OK;
 
-    const int NW = max_row_tiles <= 4 ? 4 : 8;
-    const int rb_max = (max_row_tiles + NW - 1) / NW;
+    // wide kernel: head_dim 128 and enough stacked query rows per kv head to fill 64-row waves
+    long max_kv = 0;
+    for (int s = 0; s < batch.n_seqs; ++s) max_kv = batch.seq[s].n_kv > max_kv ? batch.seq[s].n_kv : max_kv;
+    const bool fits_u32 = max_kv * (long)Hkv * D * 2 < (1L << 32);   // the wide kernel uses 32-bit row offsets
+    bool wide = D == 128 && max_row_tiles >= kWideRowTilesPerWg && fits_u32;
+    if (getenv("PC_ATTN_WIDE")) wide = D == 128 && fits_u32 && atoi(getenv("PC_ATTN_WIDE")) != 0;
+    const int NW = wide ? 4 : (max_row_tiles <= 4 ? 4 : 8);
+    const int tiles_per_wg = wide ? kWideRowTilesPerWg : NW;
+    const int rb_max = (max_row_tiles + tiles_per_wg - 1) / tiles_per_wg;
     const long base_wgs = (long)batch.n_seqs * Hkv * rb_max;
-    const long target = (long)ctx->n_cu * (8 / NW);
+    const long target = wide ? (long)ctx->n_cu : (long)ctx->n_cu * (8 / NW);
 
-    // KV splits: enough workgroups to fill the GPU, at least 2 key tiles per split,
+    // KV splits: enough workgroups to fill the GPU, at least 128 keys per split,
     // and the partials must fit the scratch.
     int n_splits = (int)((target + base_wgs - 1) / base_wgs);
-    const int max_by_tiles = min_kv_tiles / 2 > 1 ? min_kv_tiles / 2 : 1;
-    if (n_splits > max_by_tiles) n_splits = max_by_tiles;
+    const int max_by_keys = min_kv / 128 > 1 ? min_kv / 128 : 1;
+    if (n_splits > max_by_keys) n_splits = max_by_keys;
     if (n_splits > 32) n_splits = 32;
     if (n_splits < 1) n_splits = 1;
     const size_t per_split = (size_t)total_q * Hq * (D * sizeof(float) + sizeof(float2));
@@ -495,12 +517,20 @@ int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const i
     p.n_groups = batch.n_seqs * n_splits * Hkv;
     p.total_q = total_q;
     p.q_scale = 1.4426950408889634f / sqrtf((float)D);
+    p.debug = getenv("PC_ATTN_DEBUG") ? atoi(getenv("PC_ATTN_DEBUG")) : 0;
     p.batch = batch;
 
     const int n_blocks = 8 * ((p.n_groups + 7) / 8) * rb_max;
     int rc;
-    if (D == 128) rc = NW == 8 ? launch_variant<128, 8>(ctx, p, n_blocks, stream) : launch_variant<128, 4>(ctx, p, n_blocks, stream);
-    else rc = NW == 8 ? launch_variant<64, 8>(ctx, p, n_blocks, stream) : launch_variant<64, 4>(ctx, p, n_blocks, stream);
+    const int pf = getenv("PC_ATTN_PF") ? atoi(getenv("PC_ATTN_PF")) : 1;
+    if (wide) {
+        rc = launch_attn_bf16_wide(ctx, p, n_blocks, stream);
+    } else if (D == 128) {
+        if (pf == 2) rc = NW == 8 ? launch_variant<128, 8, 2>(ctx, p, n_blocks, stream) : launch_variant<128, 4, 2>(ctx, p, n_blocks, stream);
+        else rc = NW == 8 ? launch_variant<128, 8, 1>(ctx, p, n_blocks, stream) : launch_variant<128, 4, 1>(ctx, p, n_blocks, stream);
+    } else {
+        rc = NW == 8 ? launch_variant<64, 8, 1>(ctx, p, n_blocks, stream) : launch_variant<64, 4, 1>(ctx, p, n_blocks, stream);
+    }
     if (rc != PC_OK) return rc;
 
     if (n_splits > 1) {
@@ -509,12 +539,14 @@ int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const i
         const long row_lo = (long)q_lo * Hq;
         const long n_thr = (n_rows - row_lo) * (D / 4);
         const int blocks = (int)((n_thr + 255) / 256);
-        ProfScope prof(ctx, kProfCombine, stream);
+        const float *po = p.part_o;
+        const float2 *pml = p.part_ml;
         if (D == 128)
-            hipLaunchKernelGGL(attn_combine_kernel<128>, dim3(blocks), dim3(256), 0, stream, p.part_o, p.part_ml, p.out, n_splits, n_rows, row_lo, n_rows);
+            rc = launch_kernel(ctx, kProfCombine, attn_combine_kernel<128>, dim3(blocks), dim3(256), 0, stream, po, pml,
+                               p.out, n_splits, n_rows, row_lo, n_rows);
         else
-            hipLaunchKernelGGL(attn_combine_kernel<64>, dim3(blocks), dim3(256), 0, stream, p.part_o, p.part_ml, p.out, n_splits, n_rows, row_lo, n_rows);
-        rc = hip_status(hipGetLastError());
+            rc = launch_kernel(ctx, kProfCombine, attn_combine_kernel<64>, dim3(blocks), dim3(256), 0, stream, po, pml,
+                               p.out, n_splits, n_rows, row_lo, n_rows);
     }
     ctx->last_attn.n_splits = n_splits;
     ctx->last_attn.n_workgroups = n_blocks;

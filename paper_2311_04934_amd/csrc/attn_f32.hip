@@ -149,12 +149,10 @@ int launch_attn_f32(pc_ctx *ctx, const AttnBatch &batch, const float *q, const i
     p.batch = batch;
     const long n_pairs = (long)(q_hi - q_lo) * p.Hq;
     const int blocks = (int)((n_pairs + kWaves - 1) / kWaves);
-    ProfScope prof(ctx, kProfAttn, stream);
-    hipLaunchKernelGGL(attn_f32_kernel, dim3(blocks), dim3(kWaves * 64), 0, stream, p);
     ctx->last_attn.n_splits = 1;
     ctx->last_attn.n_workgroups = blocks;
     ctx->last_attn.waves_per_wg = kWaves;
-    return hip_status(hipGetLastError());
+    return launch_kernel(ctx, kProfAttn, attn_f32_kernel, dim3(blocks), dim3(kWaves * 64), 0, stream, p);
 }
 
 }  // namespace pc

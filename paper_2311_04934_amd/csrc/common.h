@@ -3,6 +3,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -127,24 +128,21 @@ int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const i
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? PC_OK : PC_E_HIP; }
 
-// Records a start event now and a stop event when it goes out of scope, both on `stream`,
-// if profiling is on and a free event pair is left for `kind`.
-struct ProfScope {
-    pc_ctx *ctx;
-    int kind, slot;
-    hipStream_t stream;
-    ProfScope(pc_ctx *c, int k, hipStream_t s) : ctx(c), kind(k), slot(-1), stream(s)
-    {
-        Profiler &p = ctx->prof;
-        if (p.capacity > 0 && p.used[kind] < p.capacity) {
-            slot = p.used[kind]++;
-            (void)hipEventRecord(p.start[kind][slot], stream);
-        }
+// Launch a kernel on `stream`.  When profiling is on and an event pair of `kind` is free, the
+// launch carries the pair (hipExtLaunchKernelGGL), so the pair reads the kernel's own begin and
+// end timestamps rather than the time between two stream markers.
+template <typename... Args, typename F = void (*)(Args...)>
+inline int launch_kernel(pc_ctx *ctx, int kind, F kernel, dim3 grid, dim3 block, unsigned smem, hipStream_t stream,
+                         Args... args)
+{
+    Profiler &p = ctx->prof;
+    if (p.capacity > 0 && p.used[kind] < p.capacity) {
+        const int slot = p.used[kind]++;
+        hipExtLaunchKernelGGL(kernel, grid, block, smem, stream, p.start[kind][slot], p.stop[kind][slot], 0, args...);
+    } else {
+        hipLaunchKernelGGL(kernel, grid, block, smem, stream, args...);
     }
-    ~ProfScope()
-    {
-        if (slot >= 0) (void)hipEventRecord(ctx->prof.stop[kind][slot], stream);
-    }
-};
+    return hip_status(hipGetLastError());
+}
 
 }  // namespace pc

@@ -75,10 +75,8 @@ int launch_gather(pc_ctx *ctx, const GatherArgs &args, uint8_t *out_k, uint8_t *
                   hipStream_t stream)
 {
     if (args.total_tiles <= 0) return PC_OK;
-    ProfScope prof(ctx, kProfGather, stream);
-    hipLaunchKernelGGL(gather_kv_kernel, dim3(args.total_tiles), dim3(kGatherThreads), 0, stream, args, out_k, out_v,
-                       out_pos);
-    return hip_status(hipGetLastError());
+    return launch_kernel(ctx, kProfGather, gather_kv_kernel, dim3(args.total_tiles), dim3(kGatherThreads), 0, stream,
+                         args, out_k, out_v, out_pos);
 }
 
 }  // namespace pc

@@ -90,14 +90,11 @@ int launch_rope(pc_ctx *ctx, void *x, int n_tokens, int n_heads, const int32_t *
     const long total = (long)n_tokens * n_heads * (head_dim / 2);
     if (total <= 0) return PC_OK;
     const int blocks = (int)((total + 255) / 256);
-    ProfScope prof(ctx, kProfRope, stream);
     if (ctx->cfg.dtype == PC_F32)
-        hipLaunchKernelGGL(rope_kernel<float>, dim3(blocks), dim3(256), 0, stream, static_cast<float *>(x), n_tokens,
-                           n_heads, head_dim, pos, table, max_pos);
-    else
-        hipLaunchKernelGGL(rope_kernel<uint16_t>, dim3(blocks), dim3(256), 0, stream, static_cast<uint16_t *>(x),
-                           n_tokens, n_heads, head_dim, pos, table, max_pos);
-    return hip_status(hipGetLastError());
+        return launch_kernel(ctx, kProfRope, rope_kernel<float>, dim3(blocks), dim3(256), 0, stream,
+                             static_cast<float *>(x), n_tokens, n_heads, head_dim, pos, table, max_pos);
+    return launch_kernel(ctx, kProfRope, rope_kernel<uint16_t>, dim3(blocks), dim3(256), 0, stream,
+                         static_cast<uint16_t *>(x), n_tokens, n_heads, head_dim, pos, table, max_pos);
 }
 
 int launch_append(pc_ctx *ctx, const AppendArgs &args, const void *k_new, const void *v_new, const int32_t *q_pos,
@@ -106,18 +103,15 @@ int launch_append(pc_ctx *ctx, const AppendArgs &args, const void *k_new, const 
     if (args.total_rows <= 0) return PC_OK;
     const int n_kv_heads = ctx->cfg.n_kv_heads, head_dim = ctx->cfg.head_dim, max_pos = ctx->cfg.max_pos;
     const float2 *table = ctx->rope_table;
-    ProfScope prof(ctx, kProfAppend, stream);
     if (ctx->cfg.dtype == PC_F32)
-        hipLaunchKernelGGL(append_kernel<float>, dim3(args.total_rows), dim3(256), 0, stream, args,
-                           static_cast<const float *>(k_new), static_cast<const float *>(v_new), q_pos,
-                           static_cast<float *>(asm_k), static_cast<float *>(asm_v), asm_pos, n_kv_heads, head_dim,
-                           table, max_pos);
-    else
-        hipLaunchKernelGGL(append_kernel<uint16_t>, dim3(args.total_rows), dim3(256), 0, stream, args,
-                           static_cast<const uint16_t *>(k_new), static_cast<const uint16_t *>(v_new), q_pos,
-                           static_cast<uint16_t *>(asm_k), static_cast<uint16_t *>(asm_v), asm_pos, n_kv_heads,
-                           head_dim, table, max_pos);
-    return hip_status(hipGetLastError());
+        return launch_kernel(ctx, kProfAppend, append_kernel<float>, dim3(args.total_rows), dim3(256), 0, stream, args,
+                             static_cast<const float *>(k_new), static_cast<const float *>(v_new), q_pos,
+                             static_cast<float *>(asm_k), static_cast<float *>(asm_v), asm_pos, n_kv_heads, head_dim,
+                             table, max_pos);
+    return launch_kernel(ctx, kProfAppend, append_kernel<uint16_t>, dim3(args.total_rows), dim3(256), 0, stream, args,
+                         static_cast<const uint16_t *>(k_new), static_cast<const uint16_t *>(v_new), q_pos,
+                         static_cast<uint16_t *>(asm_k), static_cast<uint16_t *>(asm_v), asm_pos, n_kv_heads, head_dim,
+                         table, max_pos);
 }
 
 }  // namespace pc
