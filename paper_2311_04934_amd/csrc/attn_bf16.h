@@ -40,6 +40,7 @@ struct AttnParams {
     int total_q;
     float q_scale;           // log2(e) / sqrt(D)
     int debug;               // experiments only: 1 = skip compute, 2 = skip global loads
+    long long *trace;        // experiments only: per-workgroup timestamps (debug == 7)
     AttnBatch batch;
 };
 
@@ -79,8 +80,8 @@ __device__ __forceinline__ float sum_across_halves(float x)
 
 }  // namespace attn
 
-// wide kernel (attn_bf16_wide.hip): D = 128, 4 waves x 64 query rows
-int launch_attn_bf16_wide(pc_ctx *ctx, attn::AttnParams &p, int n_blocks, hipStream_t stream);
+// DMA-staged kernel (attn_bf16_wide.hip): D = 128, 8 row tiles per workgroup, 1 or 2 row tiles per wave
+int launch_attn_bf16_wide(pc_ctx *ctx, attn::AttnParams &p, int n_blocks, int q_tiles_per_wave, hipStream_t stream);
 constexpr int kWideRowTilesPerWg = 8;
 
 }  // namespace pc

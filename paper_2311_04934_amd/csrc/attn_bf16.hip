@@ -518,13 +518,14 @@ int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const i
     p.total_q = total_q;
     p.q_scale = 1.4426950408889634f / sqrtf((float)D);
     p.debug = getenv("PC_ATTN_DEBUG") ? atoi(getenv("PC_ATTN_DEBUG")) : 0;
+    p.trace = reinterpret_cast<long long *>(reinterpret_cast<uint8_t *>(ctx->scratch) + ctx->scratch_bytes - (1 << 20));
     p.batch = batch;
 
     const int n_blocks = 8 * ((p.n_groups + 7) / 8) * rb_max;
     int rc;
     const int pf = getenv("PC_ATTN_PF") ? atoi(getenv("PC_ATTN_PF")) : 1;
     if (wide) {
-        rc = launch_attn_bf16_wide(ctx, p, n_blocks, stream);
+        rc = launch_attn_bf16_wide(ctx, p, n_blocks, getenv("PC_ATTN_NQT") ? atoi(getenv("PC_ATTN_NQT")) : 1, stream);
     } else if (D == 128) {
         if (pf == 2) rc = NW == 8 ? launch_variant<128, 8, 2>(ctx, p, n_blocks, stream) : launch_variant<128, 4, 2>(ctx, p, n_blocks, stream);
         else rc = NW == 8 ? launch_variant<128, 8, 1>(ctx, p, n_blocks, stream) : launch_variant<128, 4, 1>(ctx, p, n_blocks, stream);

@@ -42,11 +42,10 @@ constexpr int LDS_V = NBUF * TILE_BYTES;         // 64 KiB
 constexpr int LDS_POS = 2 * NBUF * TILE_BYTES;   // 128 KiB
 constexpr int LDS_MAIN = LDS_POS + NBUF * KT * 4;
 constexpr int EPI_STRIDE = D * 4 + 16;           // fp32 row of O plus a 16-byte pad
-constexpr int LDS_EPI = 4 * 64 * EPI_STRIDE;     // 4 waves x 64 rows
+constexpr int LDS_EPI = 256 * EPI_STRIDE;        // 256 query rows per workgroup
 constexpr int LDS_TOTAL = LDS_MAIN > LDS_EPI ? LDS_MAIN : LDS_EPI;
 
 typedef __attribute__((address_space(3))) uint8_t lds_u8;
-typedef __attribute__((address_space(1))) const void gptr_t;
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
@@ -74,8 +73,13 @@ struct QTile {        // one 32-query row tile of a wave
     int qpos;         // its position ID (+inf when the lane has no query)
 };
 
-__global__ __launch_bounds__(256) void attn_bf16_wide_kernel(const AttnParams p)
+template <int NQT, int NW>
+__global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams p)
 {
+    static_assert(NQT * NW == kWideRowTilesPerWg, "a workgroup covers 8 row tiles");
+    constexpr int GRP_PER_WAVE = 16 / NW;                // 1-KiB (4-row) groups of a tile each wave copies, per tensor
+    constexpr int DMA_PER_TILE = 2 * GRP_PER_WAVE + 1;   // loads a wave issues per tile (K, V, positions)
+
     extern __shared__ __align__(16) uint8_t smem[];
     lds_u8 *lds = (lds_u8 *)smem;
     const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
@@ -107,10 +111,10 @@ __global__ __launch_bounds__(256) void attn_bf16_wide_kernel(const AttnParams p)
     const int n_tiles = (k_end - k_begin + KT - 1) / KT;
 
     // ---- this wave's two row tiles
-    QTile qt[2];
+    QTile qt[NQT];
 #pragma unroll
-    for (int x = 0; x < 2; ++x) {
-        const int rt = rb * kWideRowTilesPerWg + wave * 2 + x;
+    for (int x = 0; x < NQT; ++x) {
+        const int rt = rb * kWideRowTilesPerWg + wave * NQT + x;
         const bool act = rt < row_tiles;
         const int g_head = act ? rt / tiles_q : 0;
         const int tq = act ? rt % tiles_q : 0;
@@ -135,10 +139,10 @@ __global__ __launch_bounds__(256) void attn_bf16_wide_kernel(const AttnParams p)
     const uint32_t row_bytes_g = (uint32_t)kv_row_stride * 2u;   // bytes between consecutive keys in global memory
     const uint8_t *k_bytes = reinterpret_cast<const uint8_t *>(k_base);
     const uint8_t *v_bytes = reinterpret_cast<const uint8_t *>(v_base);
-    uint32_t dma_r[4], dma_ck[4], dma_cv[4];
+    uint32_t dma_r[GRP_PER_WAVE], dma_ck[GRP_PER_WAVE], dma_cv[GRP_PER_WAVE];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int r = (j * 4 + wave) * 4 + st_row;                // row of the tile this lane fetches in step j
+    for (int j = 0; j < GRP_PER_WAVE; ++j) {
+        const int r = (j * NW + wave) * 4 + st_row;                // row of the tile this lane fetches in step j
         dma_r[j] = (uint32_t)r;
         dma_ck[j] = (uint32_t)((st_chunk ^ (r & 15)) << 4);       // byte offset of the chunk inside the row
         dma_cv[j] = (uint32_t)((st_chunk ^ ((r & 7) << 1)) << 4);
@@ -148,12 +152,12 @@ __global__ __launch_bounds__(256) void attn_bf16_wide_kernel(const AttnParams p)
         const uint32_t row0 = (uint32_t)(k_begin + t * KT);
         const uint32_t dst0 = __builtin_amdgcn_readfirstlane(lds_base + buf * TILE_BYTES + wave * 1024);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < GRP_PER_WAVE; ++j) {
             uint32_t grow = row0 + dma_r[j];
             grow = grow < (uint32_t)last_row ? grow : (uint32_t)last_row;
             const uint32_t off = grow * row_bytes_g;               // < 4 GiB, checked by the launcher
-            dma_b128(k_bytes + off + dma_ck[j], dst0 + LDS_K + j * 4096);
-            dma_b128(v_bytes + off + dma_cv[j], dst0 + LDS_V + j * 4096);
+            dma_b128(k_bytes + off + dma_ck[j], dst0 + LDS_K + j * NW * 1024);
+            dma_b128(v_bytes + off + dma_cv[j], dst0 + LDS_V + j * NW * 1024);
         }
         uint32_t prow = row0 + (uint32_t)lane;
         prow = prow < (uint32_t)last_row ? prow : (uint32_t)last_row;
@@ -161,9 +165,9 @@ __global__ __launch_bounds__(256) void attn_bf16_wide_kernel(const AttnParams p)
     };
 
     // ---- prologue: Q of both row tiles, rotated at the queries' position IDs, scaled, bf16
-    bf16x8 qf[2][KB];
+    bf16x8 qf[NQT][KB];
 #pragma unroll
-    for (int x = 0; x < 2; ++x) {
+    for (int x = 0; x < NQT; ++x) {
         const int q_row = seq.q_begin + (qt[x].valid ? qt[x].qi : 0);
         const uint16_t *qrow = p.q + ((size_t)q_row * p.Hq + qt[x].head) * D;
         int tpos = qt[x].qpos;
@@ -189,7 +193,10 @@ __global__ __launch_bounds__(256) void attn_bf16_wide_kernel(const AttnParams p)
         }
     }
     // smallest query position in the wave: a key tile whose largest position exceeds it needs the mask
-    const int wave_min_qpos = wave_min_i32(pc_imin(qt[0].qpos, qt[1].qpos));
+    int min_qpos = qt[0].qpos;
+#pragma unroll
+    for (int x = 1; x < NQT; ++x) min_qpos = pc_imin(min_qpos, qt[x].qpos);
+    const int wave_min_qpos = wave_min_i32(min_qpos);
 
     // first three tiles on their way (after the Q loads, so that waiting for Q does not wait for them)
     if (n_tiles > 0) issue_tile(0);
@@ -216,45 +223,45 @@ __global__ __launch_bounds__(256) void attn_bf16_wide_kernel(const AttnParams p)
     }
 
     // ---- state
-    f32x16 o_acc[2][DB];
+    f32x16 o_acc[NQT][DB];
+    float m_run[NQT], l_run[NQT], alpha[NQT];   // running max / sum; alpha = pending rescale of O
+    bf16x8 pf[2][NQT][2];          // [sub-tile parity][row tile][16-key half]
+    f32x16 sc[2][NQT];             // [sub-tile parity][row tile] scores
 #pragma unroll
-    for (int x = 0; x < 2; ++x)
+    for (int x = 0; x < NQT; ++x) {
+        m_run[x] = -INFINITY;
+        l_run[x] = 0.f;
+        alpha[x] = 1.f;
 #pragma unroll
         for (int b = 0; b < DB; ++b)
 #pragma unroll
             for (int i = 0; i < 16; ++i) o_acc[x][b][i] = 0.f;
-    float m_run[2] = {-INFINITY, -INFINITY};
-    float l_run[2] = {0.f, 0.f};
-    float alpha[2] = {1.f, 1.f};   // pending rescale of O
-    bf16x8 pf[2][2][2];            // [sub-tile parity][row tile][16-key half]
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int x = 0; x < 2; ++x)
+        for (int a = 0; a < 2; ++a)
 #pragma unroll
             for (int j = 0; j < 2; ++j)
 #pragma unroll
                 for (int e = 0; e < 8; ++e) pf[a][x][j][e] = (__bf16)0.f;
-    f32x16 sc[2][2];               // [sub-tile parity][row tile] scores
+    }
 
-    // K.Q for both row tiles of one 32-key sub-tile: every K fragment is read once, used twice
-    auto qk = [&](int buf, int sub, f32x16 &sa, f32x16 &sb) {
-        if (p.debug == 1 || p.debug == 6) return;
+    // K.Q for the wave's row tiles on one 32-key sub-tile: every K fragment is read once
+    auto qk = [&](int buf, int sub, f32x16 (&s)[NQT]) {
         const lds_u8 *base = lds + LDS_K + buf * TILE_BYTES + sub * 32 * ROW_BYTES;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) { sa[i] = 0.f; sb[i] = 0.f; }
+        for (int x = 0; x < NQT; ++x)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) s[x][i] = 0.f;
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
             const u32x4 raw = *reinterpret_cast<const __attribute__((address_space(3))) u32x4 *>(base + koff[kb]);
             const bf16x8 kf = __builtin_bit_cast(bf16x8, raw);
-            sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[0][kb], sa, 0, 0, 0);
-            sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[1][kb], sb, 0, 0, 0);
+#pragma unroll
+            for (int x = 0; x < NQT; ++x) s[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[x][kb], s[x], 0, 0, 0);
         }
     };
 
-    // O^T += V^T.P^T for both row tiles of one sub-tile: every V fragment is read once, used twice
-    auto pv = [&](int buf, int sub, const bf16x8 (&pa)[2], const bf16x8 (&pb)[2]) {
-        if (p.debug == 1 || p.debug == 6) return;
+    // O^T += V^T.P^T for the wave's row tiles on one sub-tile: every V fragment is read once
+    auto pv = [&](int buf, int sub, const bf16x8 (&pp)[NQT][2]) {
         const lds_u8 *base = lds + LDS_V + buf * TILE_BYTES + sub * 32 * ROW_BYTES;
 #pragma unroll
         for (int b = 0; b < DB; ++b) {
@@ -265,15 +272,15 @@ __global__ __launch_bounds__(256) void attn_bf16_wide_kernel(const AttnParams p)
                 const s16x4 t1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(a0 + 8 * ROW_BYTES));
                 const s16x8 t = __builtin_shufflevector(t0, t1, 0, 1, 2, 3, 4, 5, 6, 7);
                 const bf16x8 vf = __builtin_bit_cast(bf16x8, t);
-                o_acc[0][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pa[j], o_acc[0][b], 0, 0, 0);
-                o_acc[1][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb[j], o_acc[1][b], 0, 0, 0);
+#pragma unroll
+                for (int x = 0; x < NQT; ++x)
+                    o_acc[x][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pp[x][j], o_acc[x][b], 0, 0, 0);
             }
         }
     };
 
     // online softmax of one score tile (row tile x); O is NOT rescaled here (see rescale())
     auto softmax = [&](bool masked, f32x16 &s, int x, int buf, int sub, int n_valid, bf16x8 (&pout)[2]) {
-        if (p.debug == 1 || p.debug == 5) return;
         if (masked) {
             const lds_u8 *pp = lds + LDS_POS + buf * KT * 4;
 #pragma unroll
@@ -305,9 +312,12 @@ __global__ __launch_bounds__(256) void attn_bf16_wide_kernel(const AttnParams p)
     };
 
     auto rescale = [&]() {
-        if (__any(alpha[0] != 1.f || alpha[1] != 1.f)) {
+        bool need = false;
 #pragma unroll
-            for (int x = 0; x < 2; ++x)
+        for (int x = 0; x < NQT; ++x) need |= alpha[x] != 1.f;
+        if (__any(need)) {
+#pragma unroll
+            for (int x = 0; x < NQT; ++x)
 #pragma unroll
                 for (int b = 0; b < DB; ++b)
 #pragma unroll
@@ -325,14 +335,14 @@ __global__ __launch_bounds__(256) void attn_bf16_wide_kernel(const AttnParams p)
     };
 
     // ---- main loop
-    if (n_tiles > 0 && p.debug < 3) {
+    if (n_tiles > 0) {
         // tile 0 visible
-        if (n_tiles > 2) PC_WAIT_VMCNT(18);
-        else if (n_tiles > 1) PC_WAIT_VMCNT(9);
+        if (n_tiles > 2) PC_WAIT_VMCNT(2 * DMA_PER_TILE);
+        else if (n_tiles > 1) PC_WAIT_VMCNT(DMA_PER_TILE);
         else PC_WAIT_VMCNT(0);
         __syncthreads();
         bool mask_cur = tile_needs_mask(0);
-        qk(0, 0, sc[0][0], sc[0][1]);
+        qk(0, 0, sc[0]);
 
         for (int t = 0; t < n_tiles; ++t) {
             const int buf = t & (NBUF - 1);
@@ -344,13 +354,13 @@ __global__ __launch_bounds__(256) void attn_bf16_wide_kernel(const AttnParams p)
 
             // ===== sub-tile 0 of tile t: scores in sc[0]
             rescale();
-            softmax(mask_cur, sc[0][0], 0, buf, 0, n_valid, pf[0][0]);     // phase 1: softmax a ...
-            pv(pbuf, psub, pf[1][0], pf[1][1]);                             // ... with P.V of the previous sub-tile
-            softmax(mask_cur, sc[0][1], 1, buf, 0, n_valid, pf[0][1]);     // phase 2: softmax b ...
-            qk(buf, 1, sc[1][0], sc[1][1]);                                 // ... with K.Q of this tile's second half
+            pv(pbuf, psub, pf[1]);
+#pragma unroll
+            for (int x = 0; x < NQT; ++x) softmax(mask_cur, sc[0][x], x, buf, 0, n_valid, pf[0][x]);
+            qk(buf, 1, sc[1]);
 
             // make tile t+1 visible; its loads were issued two tiles ago.  Loads of tile t+2 may stay in flight.
-            if (t + 2 < n_tiles) PC_WAIT_VMCNT(9);
+            if (t + 2 < n_tiles) PC_WAIT_VMCNT(DMA_PER_TILE);
             else PC_WAIT_VMCNT(0);
             __syncthreads();
             if (t + 3 < n_tiles) issue_tile(t + 3);   // into the buffer tile t-1 used; everyone is past it now
@@ -358,30 +368,29 @@ __global__ __launch_bounds__(256) void attn_bf16_wide_kernel(const AttnParams p)
 
             // ===== sub-tile 1 of tile t: scores in sc[1]
             rescale();
-            softmax(mask_cur, sc[1][0], 0, buf, 1, n_valid, pf[1][0]);     // phase 1
-            pv(buf, 0, pf[0][0], pf[0][1]);
-            softmax(mask_cur, sc[1][1], 1, buf, 1, n_valid, pf[1][1]);     // phase 2
-            // K.Q of the next tile's first half (past the last tile: recompute on this tile, result unused)
-            qk(has_next ? (t + 1) & (NBUF - 1) : buf, 0, sc[0][0], sc[0][1]);
+            pv(buf, 0, pf[0]);
+#pragma unroll
+            for (int x = 0; x < NQT; ++x) softmax(mask_cur, sc[1][x], x, buf, 1, n_valid, pf[1][x]);
+            // K.Q of the next tile's first half (past the last tile: recomputed on this tile, result unused)
+            qk(has_next ? (t + 1) & (NBUF - 1) : buf, 0, sc[0]);
             mask_cur = mask_next;
         }
         // drain: P.V of the very last sub-tile
         rescale();
-        pv((n_tiles - 1) & (NBUF - 1), 1, pf[1][0], pf[1][1]);
+        pv((n_tiles - 1) & (NBUF - 1), 1, pf[1]);
     }
 
     // ---- epilogue: O^T -> LDS -> whole rows to global
-    if (p.debug == 4) return;
     __syncthreads();   // every wave is done with the K/V buffers
-    float l_tot[2], inv[2];
+    float l_tot[NQT], inv[NQT];
 #pragma unroll
-    for (int x = 0; x < 2; ++x) {
+    for (int x = 0; x < NQT; ++x) {
         l_tot[x] = sum_across_halves(l_run[x]);
         inv[x] = p.n_splits == 1 ? (l_tot[x] > 0.f ? 1.f / l_tot[x] : 0.f) : 1.f;
     }
-    lds_u8 *epi = lds + wave * 64 * EPI_STRIDE;
+    lds_u8 *epi = lds + wave * NQT * 32 * EPI_STRIDE;
 #pragma unroll
-    for (int x = 0; x < 2; ++x)
+    for (int x = 0; x < NQT; ++x)
 #pragma unroll
         for (int b = 0; b < DB; ++b)
 #pragma unroll
@@ -394,7 +403,7 @@ __global__ __launch_bounds__(256) void attn_bf16_wide_kernel(const AttnParams p)
     // (m, l) of the partial, one lane per query
     if (p.n_splits > 1 && hh == 0) {
 #pragma unroll
-        for (int x = 0; x < 2; ++x)
+        for (int x = 0; x < NQT; ++x)
             if (qt[x].valid) {
                 const size_t out_row = (size_t)(seq.q_begin + qt[x].qi) * p.Hq + qt[x].head;
                 p.part_ml[(size_t)split * p.total_q * p.Hq + out_row] = make_float2(m_run[x], l_tot[x]);
@@ -404,9 +413,9 @@ __global__ __launch_bounds__(256) void attn_bf16_wide_kernel(const AttnParams p)
     __builtin_amdgcn_wave_barrier();
     // a wave instruction moves 2 rows of 512 bytes (fp32) or 4 rows of 256 bytes (bf16)
 #pragma unroll
-    for (int x = 0; x < 2; ++x) {
+    for (int x = 0; x < NQT; ++x) {
         // row of the row tile handled by each lane's query index: broadcast through the tile descriptor
-        const int rt = rb * kWideRowTilesPerWg + wave * 2 + x;
+        const int rt = rb * kWideRowTilesPerWg + wave * NQT + x;
         if (rt >= row_tiles) continue;
         const int g_head = rt / tiles_q, tq = rt % tiles_q;
         const int head = kvh * p.G + g_head;
@@ -442,18 +451,25 @@ __global__ __launch_bounds__(256) void attn_bf16_wide_kernel(const AttnParams p)
     }
 }
 
-}  // namespace
-
-int launch_attn_bf16_wide(pc_ctx *ctx, attn::AttnParams &p, int n_blocks, hipStream_t stream)
+template <int NQT, int NW>
+int launch_one(pc_ctx *ctx, AttnParams &p, int n_blocks, hipStream_t stream)
 {
     static bool attr_set[16] = {false};
+    auto kern = attn_bf16_dma_kernel<NQT, NW>;
     if (!attr_set[ctx->device & 15]) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(attn_bf16_wide_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_TOTAL) != hipSuccess)
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                LDS_TOTAL) != hipSuccess)
             return PC_E_HIP;
         attr_set[ctx->device & 15] = true;
     }
-    return launch_kernel(ctx, kProfAttn, attn_bf16_wide_kernel, dim3(n_blocks), dim3(256), LDS_TOTAL, stream, p);
+    return launch_kernel(ctx, kProfAttn, kern, dim3(n_blocks), dim3(NW * 64), LDS_TOTAL, stream, p);
+}
+
+}  // namespace
+
+int launch_attn_bf16_wide(pc_ctx *ctx, attn::AttnParams &p, int n_blocks, int q_tiles_per_wave, hipStream_t stream)
+{
+    return q_tiles_per_wave == 2 ? launch_one<2, 4>(ctx, p, n_blocks, stream) : launch_one<1, 8>(ctx, p, n_blocks, stream);
 }
 
 }  // namespace pc
