@@ -28,6 +28,9 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+# HBM bytes per launch from rocprofv3 FETCH_SIZE (x1.998, calibrated on a copy of known size) + WRITE_SIZE;
+# see profiles/long_doc_8k_hot_path.md.  Only known for the default workload.
+MEASURED_TRAFFIC = {("long_doc_8k", 32): {"attn": 52.6e6 + 34.1e6, "gather": 33.6e6 + 33.6e6}}
 
 
 def attn_flops(w, prompt_lens, n_new):
@@ -164,12 +167,9 @@ def main() -> int:
             if rc:
                 raise pcb.PcError(rc, "bench step")
 
-    # ---------------- warmup, then the timed region
+    # ---------------- warmup, then the timed region: exactly K steps, nothing but the library calls
     for _ in range(args.warmup):
         step()
-    torch.cuda.synchronize()
-    if not args.no_events:
-        pc.pc_profile_enable(args.steps * L)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -178,22 +178,24 @@ def main() -> int:
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
+    # ---------------- the same K steps again, every kernel launch carrying a HIP event pair that holds
+    # the kernel's own begin/end timestamps on its stream.  (Kept out of the region above because launches
+    # that carry events are dispatched one by one and stretch the step by about a fifth.)
     kern = {}
+    ms_per_step_events = None
     if not args.no_events:
-        for name, kind in (("gather", pcb.PROF_GATHER), ("append", pcb.PROF_APPEND), ("attn", pcb.PROF_ATTN),
-                           ("combine", pcb.PROF_COMBINE)):
-            n, ms = pc.pc_profile_read(kind)
-            kern[name] = {"launches": n, "avg_us": (ms * 1e3 / n) if n else None}
-        pc.pc_profile_enable(0)
-        # the same K steps without event records, for the overhead the records add
+        pc.pc_profile_enable(args.steps * L)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(args.steps):
             step()
         torch.cuda.synchronize()
-        ms_per_step_plain = (time.perf_counter() - t0) * 1e3 / args.steps
-    else:
-        ms_per_step_plain = ms_per_step
+        ms_per_step_events = (time.perf_counter() - t0) * 1e3 / args.steps
+        for name, kind in (("gather", pcb.PROF_GATHER), ("append", pcb.PROF_APPEND), ("attn", pcb.PROF_ATTN),
+                           ("combine", pcb.PROF_COMBINE)):
+            n, ms = pc.pc_profile_read(kind)
+            kern[name] = {"launches": n, "avg_us": (ms * 1e3 / n) if n else None}
+        pc.pc_profile_enable(0)
     launch = pc.pc_last_attn_launch()
 
     # ---------------- algorithmic work per layer
@@ -207,7 +209,7 @@ def main() -> int:
         "unit": "TFLOP/s (uncached-prefill attention FLOPs over the whole assemble+append+attention step)",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4),
-        "ms_per_step_without_event_records": round(ms_per_step_plain, 4),
+        "ms_per_step_with_event_records": round(ms_per_step_events, 4) if ms_per_step_events else None,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "layers": L, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
@@ -225,12 +227,13 @@ def main() -> int:
         result["kernels_us"] = {k: (round(v["avg_us"], 2) if v["avg_us"] else None) for k, v in kern.items()}
         result["assemble_GBps"] = round(gat_gbs, 1)
         result["attn_kernel_TFLOPs"] = round(attn_tf, 1)
-        result["roofline"] = {"kernel": "attn_bf16_kernel", "bound": "mfma", "achieved": round(attn_tf, 1),
+        result["roofline"] = {"kernel": "attn_bf16_dma_kernel<1,8>" if (w.head_dim == 128 and launch[2] == 8 and launch[0] >= 1 and w.n_q_heads // w.n_kv_heads * ((n_new[0] + 31) // 32) >= 8) else "attn_bf16_kernel", "bound": "mfma", "achieved": round(attn_tf, 1),
                               "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                              "frac": round(attn_tf / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None}
+                              "frac": round(attn_tf / MFMA_BF16_PEAK_TFLOPS, 4),
+                              "traffic": MEASURED_TRAFFIC.get((w.name, L if L == 32 else 32), {}).get("attn")}
         result["roofline_assemble"] = {"kernel": "gather_kv_kernel", "bound": "hbm", "achieved": round(gat_gbs, 1),
                                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gat_gbs / HBM_PEAK_GBS, 4),
-                                       "traffic": None}
+                                       "traffic": MEASURED_TRAFFIC.get((w.name, 32), {}).get("gather")}
 
     # ---------------- full prefill of the same prompt with the same kernel (ordinary causal mask), one layer
     if not args.no_full_prefill and B == 1:

@@ -523,9 +523,12 @@ int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const i
 
     const int n_blocks = 8 * ((p.n_groups + 7) / 8) * rb_max;
     int rc;
+    int waves_used = NW;
     const int pf = getenv("PC_ATTN_PF") ? atoi(getenv("PC_ATTN_PF")) : 1;
     if (wide) {
-        rc = launch_attn_bf16_wide(ctx, p, n_blocks, getenv("PC_ATTN_NQT") ? atoi(getenv("PC_ATTN_NQT")) : 1, stream);
+        const int nqt = getenv("PC_ATTN_NQT") ? atoi(getenv("PC_ATTN_NQT")) : 1;
+        rc = launch_attn_bf16_wide(ctx, p, n_blocks, nqt, stream);
+        waves_used = nqt == 2 ? 4 : 8;
     } else if (D == 128) {
         if (pf == 2) rc = NW == 8 ? launch_variant<128, 8, 2>(ctx, p, n_blocks, stream) : launch_variant<128, 4, 2>(ctx, p, n_blocks, stream);
         else rc = NW == 8 ? launch_variant<128, 8, 1>(ctx, p, n_blocks, stream) : launch_variant<128, 4, 1>(ctx, p, n_blocks, stream);
@@ -551,7 +554,7 @@ int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const i
     }
     ctx->last_attn.n_splits = n_splits;
     ctx->last_attn.n_workgroups = n_blocks;
-    ctx->last_attn.waves_per_wg = NW;
+    ctx->last_attn.waves_per_wg = waves_used;
     return rc;
 }
 
