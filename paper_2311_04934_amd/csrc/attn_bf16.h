@@ -29,7 +29,7 @@ struct AttnParams {
     const uint16_t *v;
     const int32_t *kv_pos;
     uint16_t *out;           // [total_q][Hq][D]
-    float *part_o;           // [n_splits][total_q][Hq][D]
+    uint16_t *part_o;        // bf16 [n_splits][total_q][Hq][D]: un-normalised partial O of every KV split
     float2 *part_ml;         // [n_splits][total_q][Hq]
     const float2 *rope;      // [max_pos][D/2]
     int max_pos;
@@ -81,7 +81,7 @@ __device__ __forceinline__ float sum_across_halves(float x)
 }  // namespace attn
 
 // DMA-staged kernel (attn_bf16_wide.hip): D = 128, 8 row tiles per workgroup, 1 or 2 row tiles per wave
-int launch_attn_bf16_wide(pc_ctx *ctx, attn::AttnParams &p, int n_blocks, int q_tiles_per_wave, hipStream_t stream);
+int launch_attn_bf16_wide(pc_ctx *ctx, attn::AttnParams &p, int n_blocks, hipStream_t stream);
 constexpr int kWideRowTilesPerWg = 8;
 
 }  // namespace pc

@@ -393,50 +393,76 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p)
             }
     } else {
         const size_t prow = (size_t)split * p.total_q * p.Hq + out_row;
-        float *orow = p.part_o + prow * D;
+        uint16_t *orow = p.part_o + prow * D;
 #pragma unroll
         for (int b = 0; b < DB; ++b)
 #pragma unroll
             for (int i4 = 0; i4 < 4; ++i4) {
-                f32x4 w;
+                bf16x4 w;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) w[e] = o_acc[b][i4 * 4 + e];
-                *reinterpret_cast<f32x4 *>(orow + b * 32 + i4 * 8 + hh * 4) = w;
+                for (int e = 0; e < 4; ++e) w[e] = (__bf16)o_acc[b][i4 * 4 + e];
+                *reinterpret_cast<bf16x4 *>(orow + b * 32 + i4 * 8 + hh * 4) = w;
             }
         if (hh == 0) p.part_ml[prow] = make_float2(m_run, l_tot);
     }
 }
 
-// Merge the split-KV partials: out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
+// Merge the split-KV partials: out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.  The partial O_s are
+// stored in bf16 (they are rounded to bf16 at the output anyway, and the merge is a convex
+// combination); m_s and l_s are fp32.  One thread owns 8 elements of a row.
 template <int D>
-__global__ __launch_bounds__(256) void attn_combine_kernel(const float *part_o, const float2 *part_ml, uint16_t *out,
+__global__ __launch_bounds__(256) void attn_combine_kernel(const uint16_t *part_o, const float2 *part_ml, uint16_t *out,
                                                            int n_splits, long n_rows /* total_q * Hq */,
                                                            long row_lo, long row_hi /* rows this launch owns */)
 {
-    constexpr int CH = D / 4;  // 4-element chunks per row
+    constexpr int CH = D / 8;  // 8-element chunks per row
+    constexpr int U = 8;       // splits fetched together: all their loads are in flight at once
     const long idx = (long)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (row_hi - row_lo) * CH) return;
     const long row = row_lo + idx / CH;
     const int ch = (int)(idx % CH);
-    float M = -INFINITY;
-    for (int s = 0; s < n_splits; ++s) M = fmaxf(M, part_ml[(size_t)s * n_rows + row].x);
-    float Lsum = 0.f;
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    if (M != -INFINITY) {
-        for (int s = 0; s < n_splits; ++s) {
-            const float2 ml = part_ml[(size_t)s * n_rows + row];
-            if (ml.x == -INFINITY) continue;   // that split saw no visible key (its O may be unset)
-            const float w = __builtin_amdgcn_exp2f(ml.x - M);
-            Lsum += w * ml.y;
-            const f32x4 o = *reinterpret_cast<const f32x4 *>(part_o + ((size_t)s * n_rows + row) * D + ch * 4);
-            acc += o * w;
+    float M = -INFINITY, Lsum = 0.f;
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+    for (int s0 = 0; s0 < n_splits; s0 += U) {
+        float2 ml[U];
+        u32x4 o[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int s = s0 + u < n_splits ? s0 + u : n_splits - 1;   // clamped: a repeated split gets weight 0 below
+            ml[u] = part_ml[(size_t)s * n_rows + row];
+            o[u] = *reinterpret_cast<const u32x4 *>(part_o + ((size_t)s * n_rows + row) * D + ch * 8);
+        }
+        float Mg = M;
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (s0 + u < n_splits) Mg = fmaxf(Mg, ml[u].x);
+        if (Mg == -INFINITY) continue;            // nothing visible so far
+        const float r = __builtin_amdgcn_exp2f(M - Mg);   // M = -inf gives 0, and acc and Lsum are 0 then
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] *= r;
+        Lsum *= r;
+        M = Mg;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            // a split that saw no visible key has m = -inf and an O that may be unset: it is skipped
+            const bool use = s0 + u < n_splits && ml[u].x != -INFINITY;
+            const float w = use ? __builtin_amdgcn_exp2f(ml[u].x - M) : 0.f;
+            Lsum += use ? w * ml[u].y : 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t word = o[u][e >> 1];
+                const float x = bf16_bits_to_f32((e & 1) ? (word >> 16) : (word & 0xffffu));
+                acc[e] += use ? x * w : 0.f;
+            }
         }
     }
     const float inv = Lsum > 0.f ? 1.f / Lsum : 0.f;
-    bf16x4 w4;
+    bf16x8 w8;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) w4[e] = (__bf16)(acc[e] * inv);
-    *reinterpret_cast<bf16x4 *>(out + (size_t)row * D + ch * 4) = w4;
+    for (int e = 0; e < 8; ++e) w8[e] = (__bf16)(acc[e] * inv);
+    *reinterpret_cast<bf16x8 *>(out + (size_t)row * D + ch * 8) = w8;
 }
 
 template <int D, int NW, int PF>
@@ -491,7 +517,7 @@ int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const i
     if (n_splits > max_by_keys) n_splits = max_by_keys;
     if (n_splits > 32) n_splits = 32;
     if (n_splits < 1) n_splits = 1;
-    const size_t per_split = (size_t)total_q * Hq * (D * sizeof(float) + sizeof(float2));
+    const size_t per_split = (size_t)total_q * Hq * (D * sizeof(uint16_t) + sizeof(float2));
     if (n_splits > 1) {
         const size_t fit = ctx->scratch_bytes / per_split;
         if (fit < 2) n_splits = 1;
@@ -505,8 +531,8 @@ int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const i
     p.v = static_cast<const uint16_t *>(v);
     p.kv_pos = kv_pos;
     p.out = static_cast<uint16_t *>(out);
-    p.part_o = ctx->scratch;
-    p.part_ml = reinterpret_cast<float2 *>(ctx->scratch + (size_t)n_splits * total_q * Hq * D);
+    p.part_o = reinterpret_cast<uint16_t *>(ctx->scratch);
+    p.part_ml = reinterpret_cast<float2 *>(reinterpret_cast<uint8_t *>(ctx->scratch) + (((size_t)n_splits * total_q * Hq * D * sizeof(uint16_t) + 255) & ~(size_t)255));
     p.rope = ctx->rope_table;
     p.max_pos = ctx->cfg.max_pos;
     p.Hq = Hq;
@@ -526,9 +552,8 @@ int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const i
     int waves_used = NW;
     const int pf = getenv("PC_ATTN_PF") ? atoi(getenv("PC_ATTN_PF")) : 1;
     if (wide) {
-        const int nqt = getenv("PC_ATTN_NQT") ? atoi(getenv("PC_ATTN_NQT")) : 1;
-        rc = launch_attn_bf16_wide(ctx, p, n_blocks, nqt, stream);
-        waves_used = nqt == 2 ? 4 : 8;
+        rc = launch_attn_bf16_wide(ctx, p, n_blocks, stream);
+        waves_used = 8;
     } else if (D == 128) {
         if (pf == 2) rc = NW == 8 ? launch_variant<128, 8, 2>(ctx, p, n_blocks, stream) : launch_variant<128, 4, 2>(ctx, p, n_blocks, stream);
         else rc = NW == 8 ? launch_variant<128, 8, 1>(ctx, p, n_blocks, stream) : launch_variant<128, 4, 1>(ctx, p, n_blocks, stream);
@@ -541,9 +566,9 @@ int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const i
         // the prompts of one launch own the contiguous query rows [q_lo, total_q)
         const long n_rows = (long)total_q * Hq;
         const long row_lo = (long)q_lo * Hq;
-        const long n_thr = (n_rows - row_lo) * (D / 4);
+        const long n_thr = (n_rows - row_lo) * (D / 8);
         const int blocks = (int)((n_thr + 255) / 256);
-        const float *po = p.part_o;
+        const uint16_t *po = p.part_o;
         const float2 *pml = p.part_ml;
         if (D == 128)
             rc = launch_kernel(ctx, kProfCombine, attn_combine_kernel<128>, dim3(blocks), dim3(256), 0, stream, po, pml,

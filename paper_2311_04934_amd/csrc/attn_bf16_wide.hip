@@ -1,27 +1,31 @@
 // Uncached-token prefill attention over the assembled KV (Sec. 3.4 of the paper), bf16 MFMA,
-// "wide" variant for head_dim 128: 4 wavefronts per workgroup, 64 query rows per wavefront.
+// head_dim 128: 8 wavefronts per workgroup (two per SIMD), one 32-query row tile per wavefront.
 //
-// Same contract and the same S^T = K.Q^T / O^T += V^T.P^T formulation as the narrow kernel
-// (attn_bf16.hip); what differs is how the work is fed:
+// Same contract and the same S^T = K.Q^T / O^T += V^T.P^T formulation as the register-staged
+// kernel (attn_bf16.hip); what differs is how the work is fed:
 //
-//   rows      a wave owns TWO 32-query row tiles (a, b).  Every K and V fragment read from LDS
-//             feeds two MFMAs, which halves the LDS traffic per FLOP (the narrow kernel is
-//             bound by LDS bandwidth at head_dim 128).
 //   staging   K, V and position IDs of a 64-key tile go from global memory straight into LDS
 //             (global_load_lds, 16 bytes per lane): no registers, no LDS-write instructions.
-//             Four tile buffers; the loads of tile T+3 are issued while tile T is computed.
-//             Rows are stored unpadded with their 16-byte chunks XOR-swizzled by the key index
-//             so that both the K reads (one key per lane) and the transposing V reads are
-//             bank-conflict free.
-//   V         stays row-major [key][d] in LDS; the MFMA A operand V^T is fetched with
-//             ds_read_b64_tr_b16, which hands every lane four keys of one d column.
-//   pipeline  one wave per SIMD, so matrix and vector work of the SAME wave are interleaved:
-//               phase 1(i):  softmax of tile a, sub-tile i   ||  P.V MFMAs of sub-tile i-1 (a and b)
-//               phase 2(i):  softmax of tile b, sub-tile i   ||  K.Q MFMAs of sub-tile i+1 (a and b)
-//             each phase is one straight-line block of 16 MFMAs and ~100 vector instructions.
-//             Rescaling O when a running maximum moved is deferred to the start of the next
-//             phase 1 and skipped when no lane needs it.
+//             The copies of tile T+3 are issued while tile T is computed.  Rows are stored
+//             unpadded with their 16-byte chunks XOR-swizzled by the key index so that both the
+//             K reads (one key per lane) and the transposing V reads are bank-conflict free.
+//   V         lands row-major [key][d].  Once per tile the workgroup re-lays it out as MFMA A
+//             fragments of V^T: each wave fetches two of the 16 fragments with ds_read_b64_tr_b16
+//             and stores them lane-major, so that all 8 waves then read a fragment with a single
+//             16-byte LDS load.
+//   pipeline  a step handles three independent pieces of work on three 32-key sub-tiles: P.V of
+//             the previous one, K.Q of the next one and the online softmax of the current one.
+//             Matrix and vector instructions of the same wave overlap when they alternate, so a
+//             step is written as 16 slots of one matrix instruction followed by one softmax
+//             element (see step()).  The copies of the next tile and the V re-layout ride in
+//             the same slots.  One workgroup barrier per 64-key tile.
+//   rescale   O is rescaled only when the reference maximum of the online softmax moved, which
+//             it does rarely: the reference follows the running maximum lazily (see kMaxSlack).
 //   epilogue  O^T goes through LDS so that partial results / outputs are written as whole rows.
+//
+// The kernel is a template over the number of row tiles per wave; only <1 tile, 8 waves> is
+// instantiated (two tiles per wave need all 512 registers, which leaves one wave per SIMD, and
+// measured slower).
 #include <stdlib.h>
 
 #include "attn_bf16.h"
@@ -37,13 +41,20 @@ constexpr int DB = D / 32;       // 32-row blocks of O^T
 constexpr int NBUF = 4;
 constexpr int ROW_BYTES = D * 2;                 // one K or V row of one head
 constexpr int TILE_BYTES = KT * ROW_BYTES;       // 16 KiB
+constexpr int NVRAW = 3;                         // landing buffers of V as it is in global memory
+constexpr int NVT = 2;                           // buffers of V re-laid out as MFMA fragments
 constexpr int LDS_K = 0;
-constexpr int LDS_V = NBUF * TILE_BYTES;         // 64 KiB
-constexpr int LDS_POS = 2 * NBUF * TILE_BYTES;   // 128 KiB
+constexpr int LDS_V = NBUF * TILE_BYTES;                     // 64 KiB: raw V, [key][d], swizzled chunks
+constexpr int LDS_VT = LDS_V + NVRAW * TILE_BYTES;           // 112 KiB: V^T fragments, 16 x 1 KiB per tile
+constexpr int LDS_POS = LDS_VT + NVT * TILE_BYTES;           // 144 KiB
 constexpr int LDS_MAIN = LDS_POS + NBUF * KT * 4;
 constexpr int EPI_STRIDE = D * 4 + 16;           // fp32 row of O plus a 16-byte pad
 constexpr int LDS_EPI = 256 * EPI_STRIDE;        // 256 query rows per workgroup
-constexpr int LDS_TOTAL = LDS_MAIN > LDS_EPI ? LDS_MAIN : LDS_EPI;
+#ifndef PC_TRACE
+#define PC_TRACE 0
+#endif
+constexpr int LDS_TRACE = LDS_MAIN > LDS_EPI ? LDS_MAIN : LDS_EPI;
+constexpr int LDS_TOTAL = LDS_TRACE + (PC_TRACE ? 4096 : 0);
 
 typedef __attribute__((address_space(3))) uint8_t lds_u8;
 typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -87,6 +98,19 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
+#if PC_TRACE
+    int n_stamps = 0;
+    auto stamp = [&]() {
+        if ((wave & 3) == 0 && n_stamps < 255) {
+            const long long tck = clock64();
+            if (lane == 0) *reinterpret_cast<__attribute__((address_space(3))) long long *>(lds + LDS_TRACE + ((wave >> 2) * 256 + 1 + n_stamps) * 8) = tck;
+            ++n_stamps;
+        }
+    };
+#define PC_STAMP() stamp()
+#else
+#define PC_STAMP()
+#endif
     const int col = lane & 31;
     const int hh = lane >> 5;
 
@@ -105,6 +129,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
     const int row_tiles = p.G * tiles_q;
     if (rb * kWideRowTilesPerWg >= row_tiles) return;
 
+    PC_STAMP();
     const int share = (((seq.n_kv + p.n_splits - 1) / p.n_splits) + 31) & ~31;
     const int k_begin = split * share < seq.n_kv ? split * share : seq.n_kv;
     const int k_end = k_begin + share < seq.n_kv ? k_begin + share : seq.n_kv;
@@ -151,40 +176,61 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
         const int buf = t & (NBUF - 1);
         const uint32_t row0 = (uint32_t)(k_begin + t * KT);
         const uint32_t dst0 = __builtin_amdgcn_readfirstlane(lds_base + buf * TILE_BYTES + wave * 1024);
+        const uint32_t dstv = __builtin_amdgcn_readfirstlane(lds_base + LDS_V + (t % NVRAW) * TILE_BYTES + wave * 1024);
 #pragma unroll
         for (int j = 0; j < GRP_PER_WAVE; ++j) {
             uint32_t grow = row0 + dma_r[j];
             grow = grow < (uint32_t)last_row ? grow : (uint32_t)last_row;
             const uint32_t off = grow * row_bytes_g;               // < 4 GiB, checked by the launcher
             dma_b128(k_bytes + off + dma_ck[j], dst0 + LDS_K + j * NW * 1024);
-            dma_b128(v_bytes + off + dma_cv[j], dst0 + LDS_V + j * NW * 1024);
+            dma_b128(v_bytes + off + dma_cv[j], dstv + j * NW * 1024);
         }
         uint32_t prow = row0 + (uint32_t)lane;
         prow = prow < (uint32_t)last_row ? prow : (uint32_t)last_row;
         dma_b32(pos_base + prow, __builtin_amdgcn_readfirstlane(lds_base + LDS_POS + buf * KT * 4));
     };
 
-    // ---- prologue: Q of both row tiles, rotated at the queries' position IDs, scaled, bf16
-    bf16x8 qf[NQT][KB];
+    // ---- prologue.  Order matters for latency: the raw Q rows and the first K/V tile are requested
+    // first; the rotation table rows (their addresses depend on the queries' position IDs) next;
+    // tiles 1 and 2 only after Q is in registers, because vector-memory results are counted in
+    // order and waiting for the table rows would otherwise wait for those tiles as well.
+    u32x4 q_lo[NQT][KB / 2], q_hi[NQT][KB / 2];
 #pragma unroll
     for (int x = 0; x < NQT; ++x) {
         const int q_row = seq.q_begin + (qt[x].valid ? qt[x].qi : 0);
         const uint16_t *qrow = p.q + ((size_t)q_row * p.Hq + qt[x].head) * D;
+#pragma unroll
+        for (int kb = 0; kb < KB / 2; ++kb) {
+            const int d0 = kb * 16 + hh * 8;
+            q_lo[x][kb] = *reinterpret_cast<const u32x4 *>(qrow + d0);
+            q_hi[x][kb] = *reinterpret_cast<const u32x4 *>(qrow + d0 + D / 2);
+        }
+    }
+#if PC_TRACE
+    { int qq = qt[0].qpos; asm volatile("" : "+v"(qq)); qt[0].qpos = qq; }
+    PC_STAMP();   // position IDs have arrived
+    { u32x4 w = q_hi[NQT - 1][KB / 2 - 1]; asm volatile("" : "+v"(w)); q_hi[NQT - 1][KB / 2 - 1] = w; }
+    PC_STAMP();   // raw Q has arrived
+#endif
+    if (n_tiles > 0) issue_tile(0);
+    PC_STAMP();
+    // Q rotated at the queries' position IDs, scaled by log2(e)/sqrt(d), bf16: B operand of K.Q
+    bf16x8 qf[NQT][KB];
+#pragma unroll
+    for (int x = 0; x < NQT; ++x) {
         int tpos = qt[x].qpos;
         tpos = tpos < 0 ? 0 : (tpos >= p.max_pos ? p.max_pos - 1 : tpos);
         const float2 *trow = p.rope + (size_t)tpos * (D / 2);
 #pragma unroll
         for (int kb = 0; kb < KB / 2; ++kb) {
             const int d0 = kb * 16 + hh * 8;
-            u32x4 lo = *reinterpret_cast<const u32x4 *>(qrow + d0);
-            u32x4 hi = *reinterpret_cast<const u32x4 *>(qrow + d0 + D / 2);
             bf16x8 olo, ohi;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                uint32_t wl = lo[e >> 1], wh = hi[e >> 1];
-                float xl = bf16_bits_to_f32((e & 1) ? (wl >> 16) : (wl & 0xffffu));
-                float xh = bf16_bits_to_f32((e & 1) ? (wh >> 16) : (wh & 0xffffu));
-                float2 cs = trow[d0 + e];
+                const uint32_t wl = q_lo[x][kb][e >> 1], wh = q_hi[x][kb][e >> 1];
+                const float xl = bf16_bits_to_f32((e & 1) ? (wl >> 16) : (wl & 0xffffu));
+                const float xh = bf16_bits_to_f32((e & 1) ? (wh >> 16) : (wh & 0xffffu));
+                const float2 cs = trow[d0 + e];
                 olo[e] = (__bf16)((xl * cs.x - xh * cs.y) * p.q_scale);
                 ohi[e] = (__bf16)((xh * cs.x + xl * cs.y) * p.q_scale);
             }
@@ -192,16 +238,26 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
             qf[x][kb + KB / 2] = ohi;
         }
     }
+    // pin Q here: the two remaining tiles must not be requested before the table rows have arrived
+#pragma unroll
+    for (int x = 0; x < NQT; ++x)
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+            u32x4 w = __builtin_bit_cast(u32x4, qf[x][kb]);
+            asm volatile("" : "+v"(w));
+            qf[x][kb] = __builtin_bit_cast(bf16x8, w);
+        }
+    PC_STAMP();   // Q rotated
+    if (n_tiles > 0) {
+        issue_tile(1);
+        issue_tile(2);
+    }
     // smallest query position in the wave: a key tile whose largest position exceeds it needs the mask
     int min_qpos = qt[0].qpos;
 #pragma unroll
     for (int x = 1; x < NQT; ++x) min_qpos = pc_imin(min_qpos, qt[x].qpos);
     const int wave_min_qpos = wave_min_i32(min_qpos);
-
-    // first three tiles on their way (after the Q loads, so that waiting for Q does not wait for them)
-    if (n_tiles > 0) issue_tile(0);
-    if (n_tiles > 1) issue_tile(1);
-    if (n_tiles > 2) issue_tile(2);
+    PC_STAMP();
 
     // ---- per-lane LDS offsets of the MFMA operand fragments
     // K (A operand of K.Q): key = col of the sub-tile, chunk 2*kb+hh, swizzled by key & 15
@@ -244,71 +300,180 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
                 for (int e = 0; e < 8; ++e) pf[a][x][j][e] = (__bf16)0.f;
     }
 
-    // K.Q for the wave's row tiles on one 32-key sub-tile: every K fragment is read once
-    auto qk = [&](int buf, int sub, f32x16 (&s)[NQT]) {
-        const lds_u8 *base = lds + LDS_K + buf * TILE_BYTES + sub * 32 * ROW_BYTES;
-#pragma unroll
-        for (int x = 0; x < NQT; ++x)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) s[x][i] = 0.f;
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb) {
-            const u32x4 raw = *reinterpret_cast<const __attribute__((address_space(3))) u32x4 *>(base + koff[kb]);
-            const bf16x8 kf = __builtin_bit_cast(bf16x8, raw);
-#pragma unroll
-            for (int x = 0; x < NQT; ++x) s[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[x][kb], s[x], 0, 0, 0);
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
+#define PC_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+    // V fragments (A operand of O^T += V^T.P^T) of one 32-key sub-tile, group g of 8 (two
+    // transposing reads each): g = 4*j + b covers keys 16*j.., d rows 32*b..
+    bf16x8 vf[2 * DB];
+    auto read_v = [&](const lds_u8 *vbase, int g) {
+        vf[g] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const lds_u32x4 *>(vbase + g * 1024 + lane * 16));
+    };
+    // Re-layout of V: fragment f = 8*sub + 4*j + b of a tile (keys 32*sub + 16*j .., d rows 32*b ..) is
+    // fetched from the raw tile with two transposing reads, exactly the 16 bytes per lane the MFMA
+    // wants, and stored lane-major, 1 KiB per fragment.  Each wave converts NW-th of the tile; all
+    // waves then fetch a fragment with one 16-byte read instead of two transposing 8-byte ones.
+    constexpr int FRAG_PER_WAVE = 16 / NW;
+    s16x4 tr_lo[FRAG_PER_WAVE], tr_hi[FRAG_PER_WAVE];
+    auto transpose_read = [&](int t, int k) {
+        const int f = wave * FRAG_PER_WAVE + k;
+        const int sub = f >> 3, j = (f >> 2) & 1, b = f & 3;
+        const lds_u8 *a0 = lds + LDS_V + (t % NVRAW) * TILE_BYTES + (32 * sub + 16 * j) * ROW_BYTES + voff[b];
+        tr_lo[k] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)a0);
+        tr_hi[k] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(a0 + 8 * ROW_BYTES));
+    };
+    auto transpose_write = [&](int t, int k) {
+        const int f = wave * FRAG_PER_WAVE + k;
+        typedef short s16x8 __attribute__((ext_vector_type(8)));
+        const s16x8 w = __builtin_shufflevector(tr_lo[k], tr_hi[k], 0, 1, 2, 3, 4, 5, 6, 7);
+        *reinterpret_cast<__attribute__((address_space(3))) u32x4 *>(lds + LDS_VT + (t & (NVT - 1)) * TILE_BYTES + f * 1024 + lane * 16) = __builtin_bit_cast(u32x4, w);
+    };
+
+    // One asynchronous copy of tile t's staging: piece k < 2*GRP_PER_WAVE is a K (even) or V (odd)
+    // group, the last piece is the position IDs.  Tiles past the split's end copy its last row into a
+    // buffer nobody reads again, which keeps the count of outstanding copies the same in every iteration.
+    auto issue_piece = [&](int t, int k) {
+        const int buf = t & (NBUF - 1);
+        const uint32_t row0 = (uint32_t)(k_begin + t * KT);
+        if (k < 2 * GRP_PER_WAVE) {
+            const int j = k >> 1;
+            const uint32_t dst0 = __builtin_amdgcn_readfirstlane(lds_base + buf * TILE_BYTES + wave * 1024 + j * NW * 1024);
+            uint32_t grow = row0 + dma_r[j];
+            grow = grow < (uint32_t)last_row ? grow : (uint32_t)last_row;
+            const uint32_t off = grow * row_bytes_g;               // < 4 GiB, checked by the launcher
+            if (k & 1) dma_b128(v_bytes + off + dma_cv[j], __builtin_amdgcn_readfirstlane(lds_base + LDS_V + (t % NVRAW) * TILE_BYTES + wave * 1024 + j * NW * 1024));
+            else dma_b128(k_bytes + off + dma_ck[j], dst0 + LDS_K);
+        } else {
+            uint32_t prow = row0 + (uint32_t)lane;
+            prow = prow < (uint32_t)last_row ? prow : (uint32_t)last_row;
+            dma_b32(pos_base + prow, __builtin_amdgcn_readfirstlane(lds_base + LDS_POS + buf * KT * 4));
         }
     };
 
-    // O^T += V^T.P^T for the wave's row tiles on one sub-tile: every V fragment is read once
-    auto pv = [&](int buf, int sub, const bf16x8 (&pp)[NQT][2]) {
-        const lds_u8 *base = lds + LDS_V + buf * TILE_BYTES + sub * 32 * ROW_BYTES;
+    // One step.  Three independent pieces of work on three different 32-key sub-tiles:
+    //   O += V^T.P of the previous sub-tile (fragments vf were read during the previous step),
+    //   S(next) = K.Q of the sub-tile after the current one (fragments read at the top),
+    //   online softmax of the current scores s into pout (O is not rescaled here, see rescale()).
+    // The code is laid out as 16 slots: NQT matrix instructions, then a share of the softmax's
+    // vector instructions, the LDS reads that refill vf for the next step (second half) and, when
+    // do_dma, one asynchronous copy of that tile.  The compiler's scheduler is fenced
+    // between slots so that this order survives; the empty asm statements keep each value's
+    // computation in its slot.
+    auto step = [&](const bf16x8 (&pp)[NQT][2], const lds_u8 *kbase, f32x16 (&snext)[NQT], const f32x16 (&s)[NQT],
+                    bf16x8 (&pout)[NQT][2], const lds_u8 *vnext, bool do_dma, int dma_tile) {
+        bf16x8 kf[KB];
 #pragma unroll
-        for (int b = 0; b < DB; ++b) {
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const lds_u8 *a0 = base + voff[b] + (16 * j) * ROW_BYTES;
-                const s16x4 t0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)a0);
-                const s16x4 t1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(a0 + 8 * ROW_BYTES));
-                const s16x8 t = __builtin_shufflevector(t0, t1, 0, 1, 2, 3, 4, 5, 6, 7);
-                const bf16x8 vf = __builtin_bit_cast(bf16x8, t);
-#pragma unroll
-                for (int x = 0; x < NQT; ++x)
-                    o_acc[x][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pp[x][j], o_acc[x][b], 0, 0, 0);
-            }
-        }
-    };
-
-    // online softmax of one score tile (row tile x); O is NOT rescaled here (see rescale())
-    auto softmax = [&](bool masked, f32x16 &s, int x, int buf, int sub, int n_valid, bf16x8 (&pout)[2]) {
-        if (masked) {
-            const lds_u8 *pp = lds + LDS_POS + buf * KT * 4;
-#pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
-                const int key0 = sub * 32 + 8 * i4 + 4 * hh;
-                const u32x4 kp = *reinterpret_cast<const __attribute__((address_space(3))) u32x4 *>(pp + key0 * 4);
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if ((int)kp[e] > qt[x].qpos || key0 + e >= n_valid) s[i4 * 4 + e] = -INFINITY;
-            }
-        }
-        float mx = s[0];
-#pragma unroll
-        for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[i]);
-        mx = max_across_halves(mx);
-        const float m_new = mx > m_run[x] + kMaxSlack ? mx : m_run[x];
-        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-        const float a = __builtin_amdgcn_exp2f(m_run[x] - m_use);
-        m_run[x] = m_new;
-        float psum = 0.f;
+        for (int kb = 0; kb < KB; ++kb) kf[kb] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const lds_u32x4 *>(kbase + koff[kb]));
+        PC_FENCE();
+        float m_use[NQT], psum[NQT], pe_even[NQT], dnext[NQT], mxa[NQT][5], mx[NQT], m_new[NQT];
+        u32x4 pw[NQT][2];
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        int e_done = 0;   // softmax elements finished so far (compile-time after unrolling)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            const float pe = __builtin_amdgcn_exp2f(s[i] - m_use);
-            psum += pe;
-            pout[i >> 3][i & 7] = (__bf16)pe;
+#pragma unroll
+            for (int x = 0; x < NQT; ++x) {
+                if (i < 2 * DB) {
+                    o_acc[x][i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i], pp[x][i / DB], o_acc[x][i % DB], 0, 0, 0);
+                } else {
+                    const int kb = i - 2 * DB;
+                    snext[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb], qf[x][kb], kb == 0 ? zero : snext[x], 0, 0, 0);
+                }
+            }
+            // ---- softmax share of this slot
+            if (i == 0) {
+#pragma unroll
+                for (int x = 0; x < NQT; ++x) {
+#pragma unroll
+                    for (int c = 0; c < 5; ++c) {
+                        mxa[x][c] = fmaxf(fmaxf(s[x][3 * c], s[x][3 * c + 1]), s[x][3 * c + 2]);
+                        asm volatile("" : "+v"(mxa[x][c]));
+                    }
+                }
+            } else if (i == 1) {
+#pragma unroll
+                for (int x = 0; x < NQT; ++x) {
+                    mx[x] = fmaxf(fmaxf(fmaxf(mxa[x][0], mxa[x][1]), mxa[x][2]), fmaxf(fmaxf(mxa[x][3], mxa[x][4]), s[x][15]));
+                    mx[x] = max_across_halves(mx[x]);
+                    asm volatile("" : "+v"(mx[x]));
+                }
+            } else if (i == 2) {
+#pragma unroll
+                for (int x = 0; x < NQT; ++x) {
+                    m_new[x] = mx[x] > m_run[x] + kMaxSlack ? mx[x] : m_run[x];
+                    m_use[x] = (m_new[x] == -INFINITY) ? 0.f : m_new[x];
+                    asm volatile("" : "+v"(m_use[x]));
+                }
+            } else if (i == 3) {
+#pragma unroll
+                for (int x = 0; x < NQT; ++x) {
+                    alpha[x] = __builtin_amdgcn_exp2f(m_run[x] - m_use[x]);
+                    asm volatile("" : "+v"(alpha[x]));
+                    m_run[x] = m_new[x];
+                    psum[x] = 0.f;
+                    dnext[x] = s[x][0] - m_use[x];
+                    asm volatile("" : "+v"(dnext[x]));
+                }
+            } else {
+                const int n_e = i < 8 ? 2 : 1;   // slots 4..7 take two elements, slots 8..15 one
+#pragma unroll
+                for (int r = 0; r < n_e; ++r) {
+                    const int e = e_done + r;
+#pragma unroll
+                    for (int x = 0; x < NQT; ++x) {
+                        float pe = __builtin_amdgcn_exp2f(dnext[x]);
+                        asm volatile("" : "+v"(pe));
+                        if (e < 15) {
+                            dnext[x] = s[x][e + 1] - m_use[x];
+                            asm volatile("" : "+v"(dnext[x]));
+                        }
+                        psum[x] += pe;
+                        asm volatile("" : "+v"(psum[x]));
+                        if (e & 1) {
+                            typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+                            bf16x2 pr;
+                            pr[0] = (__bf16)pe_even[x];
+                            pr[1] = (__bf16)pe;
+                            uint32_t w = __builtin_bit_cast(uint32_t, pr);
+                            asm volatile("" : "+v"(w));
+                            pw[x][e >> 3][(e & 7) >> 1] = w;
+                        } else {
+                            pe_even[x] = pe;
+                        }
+                    }
+                }
+                e_done += n_e;
+            }
+            // ---- refill vf for the next step once this step's P.V instructions have been issued
+            if (i >= 2 * DB) read_v(vnext, i - 2 * DB);
+            if (do_dma && i < DMA_PER_TILE) issue_piece(dma_tile, i);
+            // re-layout of the V tile that became visible at the last barrier (dma_tile - 2)
+            if (do_dma && i < FRAG_PER_WAVE) transpose_read(dma_tile - 2, i);
+            if (do_dma && i >= 4 && i < 4 + FRAG_PER_WAVE) transpose_write(dma_tile - 2, i - 4);
+            PC_FENCE();
         }
-        l_run[x] = l_run[x] * a + psum;
-        alpha[x] = a;
+#pragma unroll
+        for (int x = 0; x < NQT; ++x) {
+            l_run[x] = l_run[x] * alpha[x] + psum[x];
+            pout[x][0] = __builtin_bit_cast(bf16x8, pw[x][0]);
+            pout[x][1] = __builtin_bit_cast(bf16x8, pw[x][1]);
+        }
+        PC_FENCE();
+    };
+
+    auto apply_mask = [&](f32x16 (&s)[NQT], int buf, int sub, int n_valid) {
+        const lds_u8 *pp = lds + LDS_POS + buf * KT * 4;
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+            const int key0 = sub * 32 + 8 * i4 + 4 * hh;
+            const u32x4 kp = *reinterpret_cast<const lds_u32x4 *>(pp + key0 * 4);
+#pragma unroll
+            for (int x = 0; x < NQT; ++x)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if ((int)kp[e] > qt[x].qpos || key0 + e >= n_valid) s[x][i4 * 4 + e] = -INFINITY;
+        }
     };
 
     auto rescale = [&]() {
@@ -325,61 +490,83 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
         }
     };
 
-    // does tile t (already visible in LDS) need the per-element mask for this wave?
+    // does tile t (already visible in LDS) need the per-element mask for this wave?  Yes when it holds
+    // a position ID above the wave's smallest query position, or fewer than 64 real keys.
     auto tile_needs_mask = [&](int t) -> bool {
         const int buf = t & (NBUF - 1);
         const int n_valid = k_end - (k_begin + t * KT);
-        const int pv_ = *reinterpret_cast<const __attribute__((address_space(3))) int *>(lds + LDS_POS + buf * KT * 4 + lane * 4);
-        const int tmax = wave_max_i32(pv_);
-        return __builtin_amdgcn_readfirstlane(tmax > wave_min_qpos || n_valid < KT);
+        const int kpos = *reinterpret_cast<const __attribute__((address_space(3))) int *>(lds + LDS_POS + buf * KT * 4 + lane * 4);
+        return __any(kpos > wave_min_qpos) || n_valid < KT;
     };
 
     // ---- main loop
     if (n_tiles > 0) {
-        // tile 0 visible
-        if (n_tiles > 2) PC_WAIT_VMCNT(2 * DMA_PER_TILE);
-        else if (n_tiles > 1) PC_WAIT_VMCNT(DMA_PER_TILE);
-        else PC_WAIT_VMCNT(0);
+        // tiles 0 (and 1, 2 when they exist) were issued in the prologue; tile 0 visible:
+        PC_WAIT_VMCNT(2 * DMA_PER_TILE);
         __syncthreads();
         bool mask_cur = tile_needs_mask(0);
-        qk(0, 0, sc[0]);
+#pragma unroll
+        for (int k = 0; k < FRAG_PER_WAVE; ++k) transpose_read(0, k);
+#pragma unroll
+        for (int k = 0; k < FRAG_PER_WAVE; ++k) transpose_write(0, k);
+        __syncthreads();   // V^T fragments of tile 0 visible
+        {   // scores of sub-tile 0, and V fragments of sub-tile 0 as stand-in for "the previous sub-tile" (its P is 0)
+            const lds_u8 *kbase = lds + LDS_K;
+#pragma unroll
+            for (int x = 0; x < NQT; ++x)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) sc[0][x][i] = 0.f;
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) {
+                const bf16x8 kf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const lds_u32x4 *>(kbase + koff[kb]));
+#pragma unroll
+                for (int x = 0; x < NQT; ++x) sc[0][x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[x][kb], sc[0][x], 0, 0, 0);
+            }
+#pragma unroll
+            for (int g = 0; g < 2 * DB; ++g) read_v(lds + LDS_VT, g);
+        }
 
         for (int t = 0; t < n_tiles; ++t) {
             const int buf = t & (NBUF - 1);
             const int n_valid = k_end - (k_begin + t * KT);   // real keys in this tile (may exceed 64)
             const bool has_next = t + 1 < n_tiles;
-            // previous sub-tile (for P.V): sub 1 of tile t-1; for t == 0 any finite data times P = 0
-            const int pbuf = t > 0 ? (t - 1) & (NBUF - 1) : buf;
-            const int psub = t > 0 ? 1 : 0;
-
-            // ===== sub-tile 0 of tile t: scores in sc[0]
-            rescale();
-            pv(pbuf, psub, pf[1]);
-#pragma unroll
-            for (int x = 0; x < NQT; ++x) softmax(mask_cur, sc[0][x], x, buf, 0, n_valid, pf[0][x]);
-            qk(buf, 1, sc[1]);
-
-            // make tile t+1 visible; its loads were issued two tiles ago.  Loads of tile t+2 may stay in flight.
-            if (t + 2 < n_tiles) PC_WAIT_VMCNT(DMA_PER_TILE);
-            else PC_WAIT_VMCNT(0);
-            __syncthreads();
-            if (t + 3 < n_tiles) issue_tile(t + 3);   // into the buffer tile t-1 used; everyone is past it now
-            const bool mask_next = has_next ? tile_needs_mask(t + 1) : false;
-
-            // ===== sub-tile 1 of tile t: scores in sc[1]
-            rescale();
-            pv(buf, 0, pf[0]);
-#pragma unroll
-            for (int x = 0; x < NQT; ++x) softmax(mask_cur, sc[1][x], x, buf, 1, n_valid, pf[1][x]);
+            const lds_u8 *k_cur = lds + LDS_K + buf * TILE_BYTES;
+            const lds_u8 *v_cur = lds + LDS_VT + (t & (NVT - 1)) * TILE_BYTES;   // fragments 0..7: first 32 keys, 8..15: last 32
             // K.Q of the next tile's first half (past the last tile: recomputed on this tile, result unused)
-            qk(has_next ? (t + 1) & (NBUF - 1) : buf, 0, sc[0]);
+            const lds_u8 *k_nxt = lds + LDS_K + (has_next ? (t + 1) & (NBUF - 1) : buf) * TILE_BYTES;
+
+            PC_STAMP();
+            if (mask_cur) apply_mask(sc[0], buf, 0, n_valid);
+            rescale();
+            // P.V of tile t-1's second half | K.Q of this tile's second half | softmax of its first half
+            step(pf[1], k_cur + 32 * ROW_BYTES, sc[1], sc[0], pf[0], v_cur, false, 0);
+            PC_STAMP();
+
+            // make tile t+1 visible; its copies were issued two tiles ago, those of tile t+2 may stay in flight
+            PC_WAIT_VMCNT(DMA_PER_TILE);
+            __syncthreads();
+            PC_STAMP();
+            const bool mask_next = has_next ? tile_needs_mask(t + 1) : false;
+            PC_STAMP();
+
+            if (mask_cur) apply_mask(sc[1], buf, 1, n_valid);
+            rescale();
+            // P.V of this tile's first half | K.Q of tile t+1's first half | softmax of this tile's second half;
+            // tile t+3 is copied into the buffer tile t-1 used: every wave is past it since the barrier
+            step(pf[0], k_nxt, sc[0], sc[1], pf[1], v_cur + 8 * 1024, true, t + 3);
             mask_cur = mask_next;
         }
         // drain: P.V of the very last sub-tile
         rescale();
-        pv((n_tiles - 1) & (NBUF - 1), 1, pf[1]);
+#pragma unroll
+        for (int i = 0; i < 2 * DB; ++i)
+#pragma unroll
+            for (int x = 0; x < NQT; ++x)
+                o_acc[x][i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i], pf[1][x][i / DB], o_acc[x][i % DB], 0, 0, 0);
     }
+    PC_WAIT_VMCNT(0);   // copies past the split's end may still be landing in LDS
 
+    PC_STAMP();
     // ---- epilogue: O^T -> LDS -> whole rows to global
     __syncthreads();   // every wave is done with the K/V buffers
     float l_tot[NQT], inv[NQT];
@@ -419,36 +606,34 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
         if (rt >= row_tiles) continue;
         const int g_head = rt / tiles_q, tq = rt % tiles_q;
         const int head = kvh * p.G + g_head;
-        if (p.n_splits > 1) {
+        // a wave instruction moves 4 rows of 256 bytes (bf16): final output, or this split's partial
+        uint16_t *dst_base = p.n_splits > 1 ? p.part_o + (size_t)split * p.total_q * p.Hq * D : p.out;
 #pragma unroll 4
-            for (int it = 0; it < 16; ++it) {
-                const int q = it * 2 + (lane >> 5);
-                const int qi = tq * RW + q;
-                const f32x4 w = *reinterpret_cast<const __attribute__((address_space(3))) f32x4 *>(epi + (x * 32 + q) * EPI_STRIDE + (lane & 31) * 16);
-                if (qi < seq.n_q) {
-                    const size_t out_row = (size_t)(seq.q_begin + qi) * p.Hq + head;
-                    float *dst = p.part_o + ((size_t)split * p.total_q * p.Hq + out_row) * D;
-                    *reinterpret_cast<f32x4 *>(dst + (lane & 31) * 4) = w;
-                }
-            }
-        } else {
-#pragma unroll 4
-            for (int it = 0; it < 8; ++it) {
-                const int q = it * 4 + (lane >> 4);
-                const int qi = tq * RW + q;
-                const lds_u8 *src = epi + (x * 32 + q) * EPI_STRIDE + (lane & 15) * 32;
-                const f32x4 w0 = *reinterpret_cast<const __attribute__((address_space(3))) f32x4 *>(src);
-                const f32x4 w1 = *reinterpret_cast<const __attribute__((address_space(3))) f32x4 *>(src + 16);
-                if (qi < seq.n_q) {
-                    bf16x8 o;
+        for (int it = 0; it < 8; ++it) {
+            const int q = it * 4 + (lane >> 4);
+            const int qi = tq * RW + q;
+            const lds_u8 *src = epi + (x * 32 + q) * EPI_STRIDE + (lane & 15) * 32;
+            const f32x4 w0 = *reinterpret_cast<const __attribute__((address_space(3))) f32x4 *>(src);
+            const f32x4 w1 = *reinterpret_cast<const __attribute__((address_space(3))) f32x4 *>(src + 16);
+            if (qi < seq.n_q) {
+                bf16x8 o;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) { o[e] = (__bf16)w0[e]; o[4 + e] = (__bf16)w1[e]; }
-                    const size_t out_row = (size_t)(seq.q_begin + qi) * p.Hq + head;
-                    *reinterpret_cast<bf16x8 *>(p.out + out_row * D + (lane & 15) * 8) = o;
-                }
+                for (int e = 0; e < 4; ++e) { o[e] = (__bf16)w0[e]; o[4 + e] = (__bf16)w1[e]; }
+                const size_t out_row = (size_t)(seq.q_begin + qi) * p.Hq + head;
+                *reinterpret_cast<bf16x8 *>(dst_base + out_row * D + (lane & 15) * 8) = o;
             }
         }
     }
+#if PC_TRACE
+    PC_STAMP();
+    if (lane == 0 && (wave & 3) == 0)
+        *reinterpret_cast<__attribute__((address_space(3))) long long *>(lds + LDS_TRACE + (wave >> 2) * 256 * 8) = n_stamps;
+    __builtin_amdgcn_s_waitcnt(0xc07f);
+    __syncthreads();
+    if (p.trace && blockIdx.x < 256)
+        for (int i = tid; i < 512; i += NW * 64)
+            p.trace[blockIdx.x * 512 + i] = *reinterpret_cast<const __attribute__((address_space(3))) long long *>(lds + LDS_TRACE + i * 8);
+#endif
 }
 
 template <int NQT, int NW>
@@ -467,9 +652,9 @@ int launch_one(pc_ctx *ctx, AttnParams &p, int n_blocks, hipStream_t stream)
 
 }  // namespace
 
-int launch_attn_bf16_wide(pc_ctx *ctx, attn::AttnParams &p, int n_blocks, int q_tiles_per_wave, hipStream_t stream)
+int launch_attn_bf16_wide(pc_ctx *ctx, attn::AttnParams &p, int n_blocks, hipStream_t stream)
 {
-    return q_tiles_per_wave == 2 ? launch_one<2, 4>(ctx, p, n_blocks, stream) : launch_one<1, 8>(ctx, p, n_blocks, stream);
+    return launch_one<1, 8>(ctx, p, n_blocks, stream);
 }
 
 }  // namespace pc
