@@ -39,8 +39,6 @@ struct AttnParams {
     int n_groups;            // n_seqs * n_splits * Hkv
     int total_q;
     float q_scale;           // log2(e) / sqrt(D)
-    int debug;               // experiments only: 1 = skip compute, 2 = skip global loads
-    long long *trace;        // experiments only: per-workgroup timestamps (debug == 7)
     AttnBatch batch;
 };
 

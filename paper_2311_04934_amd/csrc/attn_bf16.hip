@@ -26,12 +26,11 @@
 //   mask       per key tile the min/max position ID decides "all visible",
 //                "none visible" (tile skipped) or "mixed" (per-element compare).
 //   split-KV   when one pass would not fill the GPU, the key range is cut into
-//                n_splits pieces; partial (m, l, O) go to scratch and a merge kernel
-//                combines them by log-sum-exp.
+//                n_splits pieces; partial (m, l) in fp32 and O in bf16 go to scratch and
+//                a merge kernel combines them by log-sum-exp.
 //   XCD        workgroups are handed out round-robin over the 8 XCDs, so the group
 //                index is laid out such that all row blocks of one (kv head, split)
 //                land on the same XCD and share its L2.
-#include <stdlib.h>
 
 #include "attn_bf16.h"
 
@@ -77,7 +76,7 @@ struct TileRegs {
     int pos;
 };
 
-template <int D, int NW, int PF>
+template <int D, int NW>
 __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p)
 {
     constexpr int NT = NW * 64;
@@ -175,7 +174,6 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p)
     // global -> registers.  Branch-free: rows at or past k_end are read from the last valid row
     // and then zeroed (position +inf), so all loads of a tile are in flight together.
     auto load_tile = [&](int t, Regs &r) {
-        if (p.debug == 2 && t > 1) return;
         const int row0 = k_begin + t * KT;
         const int last = k_end - 1;
 #pragma unroll
@@ -340,43 +338,23 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p)
         }
     };
 
-    // ---- main loop: LDS double buffer; global loads run PF tiles ahead of their use
-    if (n_tiles > 0 && p.debug < 3) {
-        if constexpr (PF == 2) {
-            Regs ra, rb_;
-            load_tile(0, ra);
-            if (n_tiles > 1) load_tile(1, rb_);
-            store_tile(0, ra);
+    // ---- main loop: LDS double buffer; the global loads of tile t+1 are in flight while tile t is computed
+    if (n_tiles > 0) {
+        Regs ra;
+        load_tile(0, ra);
+        store_tile(0, ra);
+        __syncthreads();
+        for (int t = 0; t < n_tiles; ++t) {
+            const bool more = t + 1 < n_tiles;
+            if (more) load_tile(t + 1, ra);
+            if (wave_active) compute_tile(t & 1, t);
+            if (more) store_tile((t + 1) & 1, ra);
             __syncthreads();
-            if (n_tiles > 2) load_tile(2, ra);
-            for (int t = 0; t < n_tiles; t += 2) {
-                if (wave_active && p.debug != 1) compute_tile(0, t);
-                if (t + 1 < n_tiles) store_tile(1, rb_);
-                __syncthreads();
-                if (t + 1 >= n_tiles) break;
-                if (t + 3 < n_tiles) load_tile(t + 3, rb_);
-                if (wave_active && p.debug != 1) compute_tile(1, t + 1);
-                if (t + 2 < n_tiles) store_tile(0, ra);
-                __syncthreads();
-                if (t + 4 < n_tiles) load_tile(t + 4, ra);
-            }
-        } else {
-            Regs ra;
-            load_tile(0, ra);
-            store_tile(0, ra);
-            __syncthreads();
-            for (int t = 0; t < n_tiles; ++t) {
-                const bool more = t + 1 < n_tiles;
-                if (more) load_tile(t + 1, ra);
-                if (wave_active && p.debug != 1) compute_tile(t & 1, t);
-                if (more) store_tile((t + 1) & 1, ra);
-                __syncthreads();
-            }
         }
     }
 
     // ---- epilogue
-    if (!q_valid || p.debug == 4) return;
+    if (!q_valid) return;
     const float l_tot = sum_across_halves(l_run);
     const size_t out_row = (size_t)(seq.q_begin + qi) * p.Hq + head;
     if (p.n_splits == 1) {
@@ -465,11 +443,11 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const uint16_t *part_
     *reinterpret_cast<bf16x8 *>(out + (size_t)row * D + ch * 8) = w8;
 }
 
-template <int D, int NW, int PF>
+template <int D, int NW>
 int launch_variant(pc_ctx *ctx, AttnParams &p, int n_blocks, hipStream_t stream)
 {
     static bool attr_set[16] = {false};
-    auto kern = attn_bf16_kernel<D, NW, PF>;
+    auto kern = attn_bf16_kernel<D, NW>;
     const int smem = Lds<D>::TOTAL;
     if (!attr_set[ctx->device & 15]) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
@@ -503,7 +481,6 @@ int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const i
     for (int s = 0; s < batch.n_seqs; ++s) max_kv = batch.seq[s].n_kv > max_kv ? batch.seq[s].n_kv : max_kv;
     const bool fits_u32 = max_kv * (long)Hkv * D * 2 < (1L << 32);   // the wide kernel uses 32-bit row offsets
     bool wide = D == 128 && max_row_tiles >= kWideRowTilesPerWg && fits_u32;
-    if (getenv("PC_ATTN_WIDE")) wide = D == 128 && fits_u32 && atoi(getenv("PC_ATTN_WIDE")) != 0;
     const int NW = wide ? 4 : (max_row_tiles <= 4 ? 4 : 8);
     const int tiles_per_wg = wide ? kWideRowTilesPerWg : NW;
     const int rb_max = (max_row_tiles + tiles_per_wg - 1) / tiles_per_wg;
@@ -543,22 +520,18 @@ int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const i
     p.n_groups = batch.n_seqs * n_splits * Hkv;
     p.total_q = total_q;
     p.q_scale = 1.4426950408889634f / sqrtf((float)D);
-    p.debug = getenv("PC_ATTN_DEBUG") ? atoi(getenv("PC_ATTN_DEBUG")) : 0;
-    p.trace = reinterpret_cast<long long *>(reinterpret_cast<uint8_t *>(ctx->scratch) + ctx->scratch_bytes - (1 << 20));
     p.batch = batch;
 
     const int n_blocks = 8 * ((p.n_groups + 7) / 8) * rb_max;
     int rc;
     int waves_used = NW;
-    const int pf = getenv("PC_ATTN_PF") ? atoi(getenv("PC_ATTN_PF")) : 1;
     if (wide) {
         rc = launch_attn_bf16_wide(ctx, p, n_blocks, stream);
         waves_used = 8;
     } else if (D == 128) {
-        if (pf == 2) rc = NW == 8 ? launch_variant<128, 8, 2>(ctx, p, n_blocks, stream) : launch_variant<128, 4, 2>(ctx, p, n_blocks, stream);
-        else rc = NW == 8 ? launch_variant<128, 8, 1>(ctx, p, n_blocks, stream) : launch_variant<128, 4, 1>(ctx, p, n_blocks, stream);
+        rc = NW == 8 ? launch_variant<128, 8>(ctx, p, n_blocks, stream) : launch_variant<128, 4>(ctx, p, n_blocks, stream);
     } else {
-        rc = NW == 8 ? launch_variant<64, 8, 1>(ctx, p, n_blocks, stream) : launch_variant<64, 4, 1>(ctx, p, n_blocks, stream);
+        rc = NW == 8 ? launch_variant<64, 8>(ctx, p, n_blocks, stream) : launch_variant<64, 4>(ctx, p, n_blocks, stream);
     }
     if (rc != PC_OK) return rc;
 

@@ -26,7 +26,6 @@
 // The kernel is a template over the number of row tiles per wave; only <1 tile, 8 waves> is
 // instantiated (two tiles per wave need all 512 registers, which leaves one wave per SIMD, and
 // measured slower).
-#include <stdlib.h>
 
 #include "attn_bf16.h"
 
@@ -50,11 +49,7 @@ constexpr int LDS_POS = LDS_VT + NVT * TILE_BYTES;           // 144 KiB
 constexpr int LDS_MAIN = LDS_POS + NBUF * KT * 4;
 constexpr int EPI_STRIDE = D * 4 + 16;           // fp32 row of O plus a 16-byte pad
 constexpr int LDS_EPI = 256 * EPI_STRIDE;        // 256 query rows per workgroup
-#ifndef PC_TRACE
-#define PC_TRACE 0
-#endif
-constexpr int LDS_TRACE = LDS_MAIN > LDS_EPI ? LDS_MAIN : LDS_EPI;
-constexpr int LDS_TOTAL = LDS_TRACE + (PC_TRACE ? 4096 : 0);
+constexpr int LDS_TOTAL = LDS_MAIN > LDS_EPI ? LDS_MAIN : LDS_EPI;
 
 typedef __attribute__((address_space(3))) uint8_t lds_u8;
 typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -98,19 +93,6 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-#if PC_TRACE
-    int n_stamps = 0;
-    auto stamp = [&]() {
-        if ((wave & 3) == 0 && n_stamps < 255) {
-            const long long tck = clock64();
-            if (lane == 0) *reinterpret_cast<__attribute__((address_space(3))) long long *>(lds + LDS_TRACE + ((wave >> 2) * 256 + 1 + n_stamps) * 8) = tck;
-            ++n_stamps;
-        }
-    };
-#define PC_STAMP() stamp()
-#else
-#define PC_STAMP()
-#endif
     const int col = lane & 31;
     const int hh = lane >> 5;
 
@@ -129,7 +111,6 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
     const int row_tiles = p.G * tiles_q;
     if (rb * kWideRowTilesPerWg >= row_tiles) return;
 
-    PC_STAMP();
     const int share = (((seq.n_kv + p.n_splits - 1) / p.n_splits) + 31) & ~31;
     const int k_begin = split * share < seq.n_kv ? split * share : seq.n_kv;
     const int k_end = k_begin + share < seq.n_kv ? k_begin + share : seq.n_kv;
@@ -190,44 +171,37 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
         dma_b32(pos_base + prow, __builtin_amdgcn_readfirstlane(lds_base + LDS_POS + buf * KT * 4));
     };
 
-    // ---- prologue.  Order matters for latency: the raw Q rows and the first K/V tile are requested
-    // first; the rotation table rows (their addresses depend on the queries' position IDs) next;
-    // tiles 1 and 2 only after Q is in registers, because vector-memory results are counted in
-    // order and waiting for the table rows would otherwise wait for those tiles as well.
-    u32x4 q_lo[NQT][KB / 2], q_hi[NQT][KB / 2];
-#pragma unroll
-    for (int x = 0; x < NQT; ++x) {
-        const int q_row = seq.q_begin + (qt[x].valid ? qt[x].qi : 0);
-        const uint16_t *qrow = p.q + ((size_t)q_row * p.Hq + qt[x].head) * D;
-#pragma unroll
-        for (int kb = 0; kb < KB / 2; ++kb) {
-            const int d0 = kb * 16 + hh * 8;
-            q_lo[x][kb] = *reinterpret_cast<const u32x4 *>(qrow + d0);
-            q_hi[x][kb] = *reinterpret_cast<const u32x4 *>(qrow + d0 + D / 2);
-        }
+    // ---- prologue.  Order matters for latency.  The position IDs come first (the rotation-table
+    // addresses depend on them); then the first two K/V tiles are requested, and only then the raw
+    // Q rows and the table rows.  The compiler does not see the asynchronous copies: when it waits
+    // for "its" loads, older copies that are still in flight simply make that wait longer (the first
+    // tile is needed at that point anyway), while younger copies could let the count drop early.
+    // So no copy is issued between a load and its use: tile 2 follows once Q is in registers.
+    if (n_tiles > 0) {
+        int qq = qt[0].qpos;
+        asm volatile("" : "+v"(qq));   // the position IDs have arrived
+        qt[0].qpos = qq;
+        issue_tile(0);
+        issue_tile(1);
     }
-#if PC_TRACE
-    { int qq = qt[0].qpos; asm volatile("" : "+v"(qq)); qt[0].qpos = qq; }
-    PC_STAMP();   // position IDs have arrived
-    { u32x4 w = q_hi[NQT - 1][KB / 2 - 1]; asm volatile("" : "+v"(w)); q_hi[NQT - 1][KB / 2 - 1] = w; }
-    PC_STAMP();   // raw Q has arrived
-#endif
-    if (n_tiles > 0) issue_tile(0);
-    PC_STAMP();
     // Q rotated at the queries' position IDs, scaled by log2(e)/sqrt(d), bf16: B operand of K.Q
     bf16x8 qf[NQT][KB];
 #pragma unroll
     for (int x = 0; x < NQT; ++x) {
+        const int q_row = seq.q_begin + (qt[x].valid ? qt[x].qi : 0);
+        const uint16_t *qrow = p.q + ((size_t)q_row * p.Hq + qt[x].head) * D;
         int tpos = qt[x].qpos;
         tpos = tpos < 0 ? 0 : (tpos >= p.max_pos ? p.max_pos - 1 : tpos);
         const float2 *trow = p.rope + (size_t)tpos * (D / 2);
 #pragma unroll
         for (int kb = 0; kb < KB / 2; ++kb) {
             const int d0 = kb * 16 + hh * 8;
+            const u32x4 lo = *reinterpret_cast<const u32x4 *>(qrow + d0);
+            const u32x4 hi = *reinterpret_cast<const u32x4 *>(qrow + d0 + D / 2);
             bf16x8 olo, ohi;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const uint32_t wl = q_lo[x][kb][e >> 1], wh = q_hi[x][kb][e >> 1];
+                const uint32_t wl = lo[e >> 1], wh = hi[e >> 1];
                 const float xl = bf16_bits_to_f32((e & 1) ? (wl >> 16) : (wl & 0xffffu));
                 const float xh = bf16_bits_to_f32((e & 1) ? (wh >> 16) : (wh & 0xffffu));
                 const float2 cs = trow[d0 + e];
@@ -238,7 +212,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
             qf[x][kb + KB / 2] = ohi;
         }
     }
-    // pin Q here: the two remaining tiles must not be requested before the table rows have arrived
+    // pin Q here: the third tile must not be requested before the loads above have been consumed
 #pragma unroll
     for (int x = 0; x < NQT; ++x)
 #pragma unroll
@@ -247,17 +221,12 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
             asm volatile("" : "+v"(w));
             qf[x][kb] = __builtin_bit_cast(bf16x8, w);
         }
-    PC_STAMP();   // Q rotated
-    if (n_tiles > 0) {
-        issue_tile(1);
-        issue_tile(2);
-    }
+    if (n_tiles > 0) issue_tile(2);
     // smallest query position in the wave: a key tile whose largest position exceeds it needs the mask
     int min_qpos = qt[0].qpos;
 #pragma unroll
     for (int x = 1; x < NQT; ++x) min_qpos = pc_imin(min_qpos, qt[x].qpos);
     const int wave_min_qpos = wave_min_i32(min_qpos);
-    PC_STAMP();
 
     // ---- per-lane LDS offsets of the MFMA operand fragments
     // K (A operand of K.Q): key = col of the sub-tile, chunk 2*kb+hh, swizzled by key & 15
@@ -535,19 +504,15 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
             // K.Q of the next tile's first half (past the last tile: recomputed on this tile, result unused)
             const lds_u8 *k_nxt = lds + LDS_K + (has_next ? (t + 1) & (NBUF - 1) : buf) * TILE_BYTES;
 
-            PC_STAMP();
             if (mask_cur) apply_mask(sc[0], buf, 0, n_valid);
             rescale();
             // P.V of tile t-1's second half | K.Q of this tile's second half | softmax of its first half
             step(pf[1], k_cur + 32 * ROW_BYTES, sc[1], sc[0], pf[0], v_cur, false, 0);
-            PC_STAMP();
 
             // make tile t+1 visible; its copies were issued two tiles ago, those of tile t+2 may stay in flight
             PC_WAIT_VMCNT(DMA_PER_TILE);
             __syncthreads();
-            PC_STAMP();
             const bool mask_next = has_next ? tile_needs_mask(t + 1) : false;
-            PC_STAMP();
 
             if (mask_cur) apply_mask(sc[1], buf, 1, n_valid);
             rescale();
@@ -566,7 +531,6 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
     }
     PC_WAIT_VMCNT(0);   // copies past the split's end may still be landing in LDS
 
-    PC_STAMP();
     // ---- epilogue: O^T -> LDS -> whole rows to global
     __syncthreads();   // every wave is done with the K/V buffers
     float l_tot[NQT], inv[NQT];
@@ -624,16 +588,6 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
             }
         }
     }
-#if PC_TRACE
-    PC_STAMP();
-    if (lane == 0 && (wave & 3) == 0)
-        *reinterpret_cast<__attribute__((address_space(3))) long long *>(lds + LDS_TRACE + (wave >> 2) * 256 * 8) = n_stamps;
-    __builtin_amdgcn_s_waitcnt(0xc07f);
-    __syncthreads();
-    if (p.trace && blockIdx.x < 256)
-        for (int i = tid; i < 512; i += NW * 64)
-            p.trace[blockIdx.x * 512 + i] = *reinterpret_cast<const __attribute__((address_space(3))) long long *>(lds + LDS_TRACE + i * 8);
-#endif
 }
 
 template <int NQT, int NW>

@@ -247,14 +247,6 @@ int pc_profile_read(pc_ctx *ctx, int kind, int *n_records, double *total_ms)
     return PC_OK;
 }
 
-/* experiments only: copy the tail of the scratch buffer (kernel timestamps) to the host */
-int pc_debug_read_trace(pc_ctx *ctx, void *dst, size_t bytes)
-{
-    if (!ctx || bytes > (1u << 20)) return PC_E_BADARG;
-    (void)hipDeviceSynchronize();
-    return hip_status(hipMemcpy(dst, reinterpret_cast<uint8_t *>(ctx->scratch) + ctx->scratch_bytes - (1 << 20), bytes, hipMemcpyDeviceToHost));
-}
-
 int pc_destroy(pc_ctx *ctx)
 {
     if (!ctx) return PC_E_BADARG;
