@@ -2,9 +2,10 @@
 """Benchmark of the Prompt Cache hot path on one MI355X.
 
 A step is one pass of the whole path over all layers of one synthetic workload:
-for every layer, assemble the prompt's KV from the module pool (pc_assemble_kv),
-append the uncached tokens' rotated K and V (pc_append_kv) and run the uncached
-tokens' attention over the result (pc_prefill_attn).  Inputs are resident in HBM
+for every layer, assemble the prompt's KV from the module pool and append the
+uncached tokens' rotated K and V (one launch: pc_assemble_append_kv_batched; with
+--separate-launches: pc_assemble_kv_batched then pc_append_kv_batched) and run the
+uncached tokens' attention over the result (pc_prefill_attn_batched).  Inputs are resident in HBM
 before the timed region starts; every layer has its own buffers so that the
 working set (pool + assembled KV, > 2 GB) cannot be served from cache.
 
@@ -85,6 +86,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="do not record per-kernel HIP events in the timed region")
     ap.add_argument("--no-full-prefill", action="store_true")
+    ap.add_argument("--separate-launches", action="store_true",
+                    help="assemble and append with two calls (two launches) instead of the fused one")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -158,12 +161,16 @@ def main() -> int:
                  P(asm_pos[layer]), hp(kv_off_c), hp(n_mod_c), stream)
         a_att = (ctx, layer, P(Q[layer]), P(q_pos), hp(q_off_c), B, P(asm_K[layer]), P(asm_V[layer]), P(asm_pos[layer]),
                  hp(kv_off_c), hp(kv_len_c), P(out[layer]), stream)
-        calls.append((a_asm, a_app, a_att))
+        a_fus = (ctx, layer, hp(ids_flat), hp(mod_offs), B, P(Kn[layer]), P(Vn[layer]), P(q_pos), hp(q_off_c),
+                 P(asm_K[layer]), P(asm_V[layer]), P(asm_pos[layer]), hp(kv_off_c), hp(n_out), stream)
+        calls.append((a_asm, a_app, a_att, a_fus))
     f_asm, f_app, f_att = lib.pc_assemble_kv_batched, lib.pc_append_kv_batched, lib.pc_prefill_attn_batched
+    f_fus = lib.pc_assemble_append_kv_batched
+    fused = not args.separate_launches
 
     def step():
-        for a_asm, a_app, a_att in calls:
-            rc = f_asm(*a_asm) or f_app(*a_app) or f_att(*a_att)
+        for a_asm, a_app, a_att, a_fus in calls:
+            rc = (f_fus(*a_fus) if fused else (f_asm(*a_asm) or f_app(*a_app))) or f_att(*a_att)
             if rc:
                 raise pcb.PcError(rc, "bench step")
 
@@ -201,6 +208,8 @@ def main() -> int:
     # ---------------- algorithmic work per layer
     flops_layer = attn_flops(w, n_mod, n_new)
     gather_bytes_layer = sum(n_mod) * (2 * 2 * w.row_bytes + 4)       # K and V, read + write, + int32 position
+    if fused:   # the same launch also reads and writes the uncached tokens' rows (and reads/writes their position IDs)
+        gather_bytes_layer += sum(n_new) * (2 * 2 * w.row_bytes + 8)
     attn_tflops_step = flops_layer * L / (ms_per_step * 1e-3) / 1e12
 
     result = {
@@ -231,7 +240,7 @@ def main() -> int:
                               "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                               "frac": round(attn_tf / MFMA_BF16_PEAK_TFLOPS, 4),
                               "traffic": MEASURED_TRAFFIC.get((w.name, L if L == 32 else 32), {}).get("attn")}
-        result["roofline_assemble"] = {"kernel": "gather_kv_kernel", "bound": "hbm", "achieved": round(gat_gbs, 1),
+        result["roofline_assemble"] = {"kernel": "gather_append_kernel" if fused else "gather_kv_kernel", "bound": "hbm", "achieved": round(gat_gbs, 1),
                                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gat_gbs / HBM_PEAK_GBS, 4),
                                        "traffic": MEASURED_TRAFFIC.get((w.name, 32), {}).get("gather")}
 

@@ -209,6 +209,21 @@ int pc_append_kv_batched(pc_ctx *ctx, int layer, const void *K_new_raw, const vo
                          void *asm_V, int32_t *asm_pos, const int *kv_offsets, const int *kv_lens,
                          void *stream);
 
+/*
+ * Sec. 3.4: a prompt's KV cache is its imported modules followed by its own uncached
+ * tokens.  This call does pc_assemble_kv_batched and pc_append_kv_batched (with kv_lens =
+ * the assembled row counts) in ONE kernel launch: the two steps write disjoint rows of the
+ * same packed buffers, and the append alone is cheaper than a launch.  Arguments as in the
+ * two calls; out_n_tokens[b] (host) receives prompt b's total rows, modules plus new
+ * tokens.  PC_E_CAPACITY if a prompt's span kv_offsets[b+1]-kv_offsets[b] cannot hold both.
+ * Falls back to two launches when the batch has more than 64 module segments or prompts.
+ */
+int pc_assemble_append_kv_batched(pc_ctx *ctx, int layer, const int *module_ids_flat,
+                                  const int *mod_offsets, int n_prompts, const void *K_new_raw,
+                                  const void *V_new, const int32_t *q_pos, const int *q_offsets,
+                                  void *out_K, void *out_V, int32_t *out_pos, const int *kv_offsets,
+                                  int *out_n_tokens, void *stream);
+
 /* Batched pc_prefill_attn.  Prompt b's queries are rows q_offsets[b] .. q_offsets[b+1]-1
  * of Q_new/q_pos/out and see rows kv_offsets[b] .. kv_offsets[b]+kv_lens[b]-1 of the
  * packed KV.  q_offsets host int[B+1]; kv_offsets host int[B+1]; kv_lens host int[B]. */

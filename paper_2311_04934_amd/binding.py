@@ -20,7 +20,8 @@ PC_F32, PC_BF16 = 0, 1
 
 EXPORTS = [
     "pc_create", "pc_destroy", "pc_strerror", "pc_store_module", "pc_assemble_kv", "pc_prefill_attn",
-    "pc_rope", "pc_append_kv", "pc_assemble_kv_batched", "pc_append_kv_batched", "pc_prefill_attn_batched",
+    "pc_rope", "pc_append_kv", "pc_assemble_kv_batched", "pc_append_kv_batched", "pc_assemble_append_kv_batched",
+    "pc_prefill_attn_batched",
     "pc_schema_layout", "pc_uncached_positions", "pc_check_selection", "pc_bytes_per_token",
     "pc_module_info", "pc_pool_usage", "pc_last_attn_launch", "pc_profile_enable", "pc_profile_read",
 ]
@@ -65,6 +66,7 @@ def lib() -> ctypes.CDLL:
     L.pc_append_kv.argtypes = [vp, i, vp, vp, vp, i, vp, vp, vp, i, i, vp]
     L.pc_assemble_kv_batched.argtypes = [vp, i, vp, vp, i, vp, vp, vp, vp, vp, vp]
     L.pc_append_kv_batched.argtypes = [vp, i, vp, vp, vp, vp, i, vp, vp, vp, vp, vp, vp]
+    L.pc_assemble_append_kv_batched.argtypes = [vp, i, vp, vp, i, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     L.pc_prefill_attn_batched.argtypes = [vp, i, vp, vp, vp, i, vp, vp, vp, vp, vp, vp, vp]
     L.pc_schema_layout.argtypes = [i, vp, vp, vp]
     L.pc_schema_layout.restype = ctypes.c_long
@@ -231,6 +233,21 @@ class PromptCache:
         _check(lib().pc_append_kv_batched(self._ctx, layer, _dev(K_new_raw), _dev(V_new), _dev(q_pos), _np_ptr(qo), B,
                                           _dev(asm_K), _dev(asm_V), _dev(asm_pos), _np_ptr(kvo), _np_ptr(kvl),
                                           _stream(stream)), "pc_append_kv_batched")
+
+    def pc_assemble_append_kv_batched(self, layer: int, module_ids: Sequence[Sequence[int]], K_new_raw, V_new, q_pos,
+                                      q_offsets: Sequence[int], out_K, out_V, out_pos, kv_offsets: Sequence[int],
+                                      stream=None) -> List[int]:
+        flat = _ints([m for ids in module_ids for m in ids])
+        offs = _ints(np.concatenate([[0], np.cumsum([len(ids) for ids in module_ids])]))
+        qo, kvo = _ints(q_offsets), _ints(kv_offsets)
+        B = len(module_ids)
+        assert len(kvo) == B + 1 and len(qo) == B + 1
+        n_out = np.zeros(max(B, 1), dtype=np.intc)
+        _check(lib().pc_assemble_append_kv_batched(self._ctx, layer, _np_ptr(flat), _np_ptr(offs), B, _dev(K_new_raw),
+                                                   _dev(V_new), _dev(q_pos), _np_ptr(qo), _dev(out_K), _dev(out_V),
+                                                   _dev(out_pos), _np_ptr(kvo), _np_ptr(n_out), _stream(stream)),
+               "pc_assemble_append_kv_batched")
+        return [int(x) for x in n_out[:B]]
 
     def pc_prefill_attn_batched(self, layer: int, Q_new, q_pos, q_offsets: Sequence[int], asm_K, asm_V, asm_pos,
                                 kv_offsets: Sequence[int], kv_lens: Sequence[int], out, stream=None) -> None:

@@ -103,6 +103,17 @@ struct AppendArgs {
     int total_rows;
     AppendSeg seg[kMaxAppendSegs];
 };
+// Assembly and append of a batch in one launch (at most kMaxFusedAppendSegs prompts).
+constexpr int kMaxFusedAppendSegs = 64;
+struct FusedKvArgs {
+    GatherArgs g;
+    int n_app;
+    int app_rows;
+    AppendSeg app[kMaxFusedAppendSegs];
+};
+int launch_gather_append(pc_ctx *ctx, const FusedKvArgs &args, uint8_t *out_k, uint8_t *out_v, int32_t *out_pos,
+                         const void *k_new, const void *v_new, const int32_t *q_pos, hipStream_t stream);
+
 int launch_append(pc_ctx *ctx, const AppendArgs &args, const void *k_new, const void *v_new, const int32_t *q_pos,
                   void *asm_k, void *asm_v, int32_t *asm_pos, hipStream_t stream);
 

@@ -10,63 +10,36 @@
 // a call needs no host->device copy and no synchronisation.  Each lane moves
 // 16 bytes per access and issues all of its loads (K and V) before the first
 // store, which keeps ~32 KiB in flight per workgroup.
-#include "common.h"
+#include "kv_ops.h"
 
 namespace pc {
 namespace {
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-constexpr int kGatherThreads = 256;
-constexpr int kUnroll = 4;  // 16-byte accesses per lane per tensor per pass
-
-__global__ __launch_bounds__(kGatherThreads) void gather_kv_kernel(const GatherArgs a, uint8_t *__restrict__ out_k,
-                                                                    uint8_t *__restrict__ out_v,
-                                                                    int32_t *__restrict__ out_pos)
+__global__ __launch_bounds__(kv::kThreads) void gather_kv_kernel(const GatherArgs a, uint8_t *__restrict__ out_k,
+                                                                  uint8_t *__restrict__ out_v,
+                                                                  int32_t *__restrict__ out_pos)
 {
-    const int tile = blockIdx.x;
-    // segment lookup: last segment whose first_tile <= tile (uniform across the workgroup)
-    int lo = 0, hi = a.n_segs - 1;
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (a.seg[mid].first_tile <= tile) lo = mid;
-        else hi = mid - 1;
-    }
-    const GatherSeg sg = a.seg[lo];
-    const int r0 = (tile - sg.first_tile) * a.rows_per_tile;
-    int n_rows = sg.n_rows - r0;
-    if (n_rows > a.rows_per_tile) n_rows = a.rows_per_tile;
-    if (n_rows <= 0) return;
+    kv::gather_tile(a, blockIdx.x, out_k, out_v, out_pos);
+}
 
-    const size_t src_off = (size_t)r0 * a.row_bytes;
-    const size_t dst_off = (size_t)(sg.dst_row + r0) * a.row_bytes;
-    const u32x4 *__restrict__ sk = reinterpret_cast<const u32x4 *>(sg.src_k + src_off);
-    const u32x4 *__restrict__ sv = reinterpret_cast<const u32x4 *>(sg.src_v + src_off);
-    u32x4 *__restrict__ dk = reinterpret_cast<u32x4 *>(out_k + dst_off);
-    u32x4 *__restrict__ dv = reinterpret_cast<u32x4 *>(out_v + dst_off);
-    const int n_vec = (int)(((size_t)n_rows * a.row_bytes) >> 4);
-
-    for (int base = 0; base < n_vec; base += kGatherThreads * kUnroll) {
-        u32x4 rk[kUnroll], rv[kUnroll];
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int i = base + u * kGatherThreads + threadIdx.x;
-            if (i < n_vec) {
-                rk[u] = __builtin_nontemporal_load(sk + i);
-                rv[u] = __builtin_nontemporal_load(sv + i);
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int i = base + u * kGatherThreads + threadIdx.x;
-            if (i < n_vec) {
-                dk[i] = rk[u];
-                dv[i] = rv[u];
-            }
-        }
-    }
-    for (int r = threadIdx.x; r < n_rows; r += kGatherThreads)
-        out_pos[sg.dst_row + r0 + r] = sg.start_pos + r0 + r;
+// Assembly and append in one launch: workgroups [0, total_tiles) gather module rows, the rest append
+// one uncached token's row each.  (Every workgroup of such a launch is resident at once; the append
+// rows, a chain of dependent loads, run fastest at the end of the grid, when the copy stream drains.)  The two write disjoint rows of the same packed buffers, and a kernel
+// launch costs more than the whole append, so a prompt's KV is complete after a single launch.
+template <typename T>
+__global__ __launch_bounds__(kv::kThreads) void gather_append_kernel(const FusedKvArgs a, uint8_t *__restrict__ out_k,
+                                                                      uint8_t *__restrict__ out_v,
+                                                                      int32_t *__restrict__ out_pos, const T *k_new,
+                                                                      const T *v_new, const int32_t *q_pos,
+                                                                      int n_kv_heads, int d, const float2 *table,
+                                                                      int max_pos)
+{
+    const int b = blockIdx.x;
+    if (b < a.g.total_tiles)
+        kv::gather_tile(a.g, b, out_k, out_v, out_pos);
+    else
+        kv::append_row<T>(a.app, a.n_app, b - a.g.total_tiles, k_new, v_new, q_pos, reinterpret_cast<T *>(out_k),
+                             reinterpret_cast<T *>(out_v), out_pos, n_kv_heads, d, table, max_pos);
 }
 
 }  // namespace
@@ -75,8 +48,23 @@ int launch_gather(pc_ctx *ctx, const GatherArgs &args, uint8_t *out_k, uint8_t *
                   hipStream_t stream)
 {
     if (args.total_tiles <= 0) return PC_OK;
-    return launch_kernel(ctx, kProfGather, gather_kv_kernel, dim3(args.total_tiles), dim3(kGatherThreads), 0, stream,
+    return launch_kernel(ctx, kProfGather, gather_kv_kernel, dim3(args.total_tiles), dim3(kv::kThreads), 0, stream,
                          args, out_k, out_v, out_pos);
+}
+
+int launch_gather_append(pc_ctx *ctx, const FusedKvArgs &args, uint8_t *out_k, uint8_t *out_v, int32_t *out_pos,
+                         const void *k_new, const void *v_new, const int32_t *q_pos, hipStream_t stream)
+{
+    const int blocks = args.g.total_tiles + args.app_rows;
+    if (blocks <= 0) return PC_OK;
+    const int n_kv_heads = ctx->cfg.n_kv_heads, head_dim = ctx->cfg.head_dim, max_pos = ctx->cfg.max_pos;
+    if (ctx->cfg.dtype == PC_F32)
+        return launch_kernel(ctx, kProfGather, gather_append_kernel<float>, dim3(blocks), dim3(kv::kThreads), 0, stream,
+                             args, out_k, out_v, out_pos, static_cast<const float *>(k_new),
+                             static_cast<const float *>(v_new), q_pos, n_kv_heads, head_dim, ctx->rope_table, max_pos);
+    return launch_kernel(ctx, kProfGather, gather_append_kernel<uint16_t>, dim3(blocks), dim3(kv::kThreads), 0, stream,
+                         args, out_k, out_v, out_pos, static_cast<const uint16_t *>(k_new),
+                         static_cast<const uint16_t *>(v_new), q_pos, n_kv_heads, head_dim, ctx->rope_table, max_pos);
 }
 
 }  // namespace pc

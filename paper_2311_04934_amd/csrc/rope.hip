@@ -7,25 +7,13 @@
 // rounded once to fp32, so the angle carries no fp32 range-reduction error even
 // at positions in the tens of thousands.  Pairing is half-split: element i rotates
 // with element i + d/2.
-#include "common.h"
+#include "kv_ops.h"
 
 namespace pc {
 namespace {
 
-template <typename T>
-struct Elem;
-template <>
-struct Elem<float> {
-    static __device__ __forceinline__ float load(const float *p) { return *p; }
-    static __device__ __forceinline__ void store(float *p, float x) { *p = x; }
-};
-template <>
-struct Elem<uint16_t> {  // bf16 bits
-    static __device__ __forceinline__ float load(const uint16_t *p) { return __uint_as_float((uint32_t)*p << 16); }
-    static __device__ __forceinline__ void store(uint16_t *p, float x) { *p = __builtin_bit_cast(uint16_t, (__bf16)x); }
-};
-
-__device__ __forceinline__ int clamp_pos(int pos, int max_pos) { return pos < 0 ? 0 : (pos >= max_pos ? max_pos - 1 : pos); }
+using kv::clamp_pos;
+using kv::Elem;
 
 // One thread per rotation pair.
 template <typename T>
@@ -46,39 +34,15 @@ __global__ __launch_bounds__(256) void rope_kernel(T *x, int n_tokens, int n_hea
     Elem<T>::store(row + i + half, hi * cs.x + lo * cs.y);
 }
 
-// One workgroup per appended row: rotate K_new at the row's position ID into the tail of
-// the assembled K, copy V_new, write the position ID.
+// One workgroup per appended row (see kv::append_row).
 template <typename T>
-__global__ __launch_bounds__(256) void append_kernel(const AppendArgs a, const T *k_new, const T *v_new,
-                                                     const int32_t *q_pos, T *asm_k, T *asm_v, int32_t *asm_pos,
-                                                     int n_kv_heads, int d, const float2 *table, int max_pos)
+__global__ __launch_bounds__(kv::kThreads) void append_kernel(const AppendArgs a, const T *k_new, const T *v_new,
+                                                              const int32_t *q_pos, T *asm_k, T *asm_v,
+                                                              int32_t *asm_pos, int n_kv_heads, int d,
+                                                              const float2 *table, int max_pos)
 {
-    // which prompt does this row belong to (uniform scan over at most kMaxAppendSegs entries)
-    int r = blockIdx.x, s = 0;
-    while (s < a.n_segs && r >= a.seg[s].n) {
-        r -= a.seg[s].n;
-        ++s;
-    }
-    if (s >= a.n_segs) return;
-    const int src = a.seg[s].q_begin + r;
-    const int dst = a.seg[s].dst_row + r;
-    const int half = d >> 1;
-    const int row_elems = n_kv_heads * d;
-    const int p = q_pos[src];
-    const float2 *trow = table + (size_t)clamp_pos(p, max_pos) * half;
-    const T *ks = k_new + (size_t)src * row_elems;
-    const T *vs = v_new + (size_t)src * row_elems;
-    T *kd = asm_k + (size_t)dst * row_elems;
-    T *vd = asm_v + (size_t)dst * row_elems;
-    for (int e = threadIdx.x; e < n_kv_heads * half; e += 256) {
-        const int h = e / half, i = e % half;
-        const float2 cs = trow[i];
-        const float lo = Elem<T>::load(ks + h * d + i), hi = Elem<T>::load(ks + h * d + i + half);
-        Elem<T>::store(kd + h * d + i, lo * cs.x - hi * cs.y);
-        Elem<T>::store(kd + h * d + i + half, hi * cs.x + lo * cs.y);
-    }
-    for (int e = threadIdx.x; e < row_elems; e += 256) vd[e] = vs[e];
-    if (threadIdx.x == 0) asm_pos[dst] = p;
+    kv::append_row<T>(a.seg, a.n_segs, blockIdx.x, k_new, v_new, q_pos, asm_k, asm_v, asm_pos, n_kv_heads, d, table,
+                      max_pos);
 }
 
 }  // namespace
@@ -104,11 +68,11 @@ int launch_append(pc_ctx *ctx, const AppendArgs &args, const void *k_new, const 
     const int n_kv_heads = ctx->cfg.n_kv_heads, head_dim = ctx->cfg.head_dim, max_pos = ctx->cfg.max_pos;
     const float2 *table = ctx->rope_table;
     if (ctx->cfg.dtype == PC_F32)
-        return launch_kernel(ctx, kProfAppend, append_kernel<float>, dim3(args.total_rows), dim3(256), 0, stream, args,
+        return launch_kernel(ctx, kProfAppend, append_kernel<float>, dim3(args.total_rows), dim3(kv::kThreads), 0, stream, args,
                              static_cast<const float *>(k_new), static_cast<const float *>(v_new), q_pos,
                              static_cast<float *>(asm_k), static_cast<float *>(asm_v), asm_pos, n_kv_heads, head_dim,
                              table, max_pos);
-    return launch_kernel(ctx, kProfAppend, append_kernel<uint16_t>, dim3(args.total_rows), dim3(256), 0, stream, args,
+    return launch_kernel(ctx, kProfAppend, append_kernel<uint16_t>, dim3(args.total_rows), dim3(kv::kThreads), 0, stream, args,
                          static_cast<const uint16_t *>(k_new), static_cast<const uint16_t *>(v_new), q_pos,
                          static_cast<uint16_t *>(asm_k), static_cast<uint16_t *>(asm_v), asm_pos, n_kv_heads, head_dim,
                          table, max_pos);

@@ -372,6 +372,66 @@ int pc_append_kv_batched(pc_ctx *ctx, int layer, const void *K_new_raw, const vo
     return PC_OK;
 }
 
+int pc_assemble_append_kv_batched(pc_ctx *ctx, int layer, const int *module_ids_flat, const int *mod_offsets,
+                                  int n_prompts, const void *K_new_raw, const void *V_new, const int32_t *q_pos,
+                                  const int *q_offsets, void *out_K, void *out_V, int32_t *out_pos,
+                                  const int *kv_offsets, int *out_n_tokens, void *stream)
+{
+    if (!ctx || n_prompts < 0 || !mod_offsets || !kv_offsets || !q_offsets) return PC_E_BADARG;
+    if (layer < 0 || layer >= ctx->cfg.n_layers) return PC_E_LAYER;
+    if (!out_K || !out_V || !out_pos || !aligned16(out_K) || !aligned16(out_V)) return PC_E_BADARG;
+    std::vector<GatherSeg> segs;
+    std::vector<int> rows(n_prompts, 0);
+    int new_rows = 0;
+    for (int b = 0; b < n_prompts; ++b) {
+        const int n = mod_offsets[b + 1] - mod_offsets[b];
+        const int cap = kv_offsets[b + 1] - kv_offsets[b];
+        const int nq = q_offsets[b + 1] - q_offsets[b];
+        if (n < 0 || cap < 0 || nq < 0 || kv_offsets[b] < 0 || q_offsets[b] < 0 || (n > 0 && !module_ids_flat))
+            return PC_E_BADARG;
+        int rc = plan_prompt(ctx, layer, module_ids_flat + mod_offsets[b], n, kv_offsets[b], cap, segs, &rows[b]);
+        if (rc != PC_OK) return rc;
+        if ((long)rows[b] + nq > (long)cap) return PC_E_CAPACITY;
+        new_rows += nq;
+    }
+    if (new_rows > 0 && (!K_new_raw || !V_new || !q_pos)) return PC_E_BADARG;
+
+    int rc = PC_OK;
+    if (segs.size() <= (size_t)kMaxGatherSegs && n_prompts <= kMaxFusedAppendSegs) {
+        FusedKvArgs a;
+        int rows_per_tile = (int)(16384 / ctx->row_bytes);
+        if (rows_per_tile < 1) rows_per_tile = 1;
+        a.g.n_segs = (int)segs.size();
+        a.g.rows_per_tile = rows_per_tile;
+        a.g.row_bytes = (int)ctx->row_bytes;
+        int tiles = 0;
+        for (int i = 0; i < a.g.n_segs; ++i) {
+            a.g.seg[i] = segs[i];
+            a.g.seg[i].first_tile = tiles;
+            tiles += (a.g.seg[i].n_rows + rows_per_tile - 1) / rows_per_tile;
+        }
+        a.g.total_tiles = tiles;
+        a.n_app = n_prompts;
+        a.app_rows = new_rows;
+        for (int b = 0; b < n_prompts; ++b) {
+            a.app[b].q_begin = q_offsets[b];
+            a.app[b].n = q_offsets[b + 1] - q_offsets[b];
+            a.app[b].dst_row = kv_offsets[b] + rows[b];
+        }
+        rc = launch_gather_append(ctx, a, static_cast<uint8_t *>(out_K), static_cast<uint8_t *>(out_V), out_pos,
+                                  K_new_raw, V_new, q_pos, as_stream(stream));
+    } else {
+        // too many segments for one argument block: the two steps one after the other
+        rc = run_gather(ctx, segs, out_K, out_V, out_pos, as_stream(stream));
+        if (rc == PC_OK)
+            rc = pc_append_kv_batched(ctx, layer, K_new_raw, V_new, q_pos, q_offsets, n_prompts, out_K, out_V, out_pos,
+                                      kv_offsets, rows.data(), stream);
+    }
+    if (rc == PC_OK && out_n_tokens)
+        for (int b = 0; b < n_prompts; ++b) out_n_tokens[b] = rows[b] + (q_offsets[b + 1] - q_offsets[b]);
+    return rc;
+}
+
 int pc_append_kv(pc_ctx *ctx, int layer, const void *K_new_raw, const void *V_new, const int32_t *q_pos, int n_q,
                  void *asm_K, void *asm_V, int32_t *asm_pos, int n_kv_before, int capacity_tokens, void *stream)
 {

@@ -266,7 +266,7 @@ def test_error_paths():
 
 
 # ------------------------------------------------------------------ batched (config 5 shape, reduced and full)
-def _batched_run(w, layer, q_sample):
+def _batched_run(w, layer, q_sample, fused=False):
     c = build_case(w, layer)
     r = GpuRunner(c)
     dev = r.dev
@@ -279,13 +279,18 @@ def _batched_run(w, layer, q_sample):
     asm_K = torch.full((total_kv, w.n_kv_heads, w.head_dim), float("nan"), dtype=w.torch_dtype, device=dev)
     asm_V = torch.full_like(asm_K, float("nan"))
     asm_pos = torch.full((total_kv,), -7, dtype=torch.int32, device=dev)
-    lens = r.pc.pc_assemble_kv_batched(layer, [p.module_ids for p in c.prompts], asm_K, asm_V, asm_pos, kv_off)
-    assert lens == n_mod
     Q = torch.cat([p.Q for p in c.prompts]).to(dev)
     Kn = torch.cat([p.K_new for p in c.prompts]).to(dev)
     Vn = torch.cat([p.V_new for p in c.prompts]).to(dev)
     qp = torch.from_numpy(np.concatenate([p.q_pos for p in c.prompts])).to(dev)
-    r.pc.pc_append_kv_batched(layer, Kn, Vn, qp, q_off, asm_K, asm_V, asm_pos, kv_off, lens)
+    if fused:   # assembly and append in one launch
+        totals = r.pc.pc_assemble_append_kv_batched(layer, [p.module_ids for p in c.prompts], Kn, Vn, qp, q_off,
+                                                    asm_K, asm_V, asm_pos, kv_off)
+        assert totals == [a + b for a, b in zip(n_mod, n_new)]
+    else:
+        lens = r.pc.pc_assemble_kv_batched(layer, [p.module_ids for p in c.prompts], asm_K, asm_V, asm_pos, kv_off)
+        assert lens == n_mod
+        r.pc.pc_append_kv_batched(layer, Kn, Vn, qp, q_off, asm_K, asm_V, asm_pos, kv_off, lens)
     out = torch.full((total_q, w.n_q_heads, w.head_dim), float("nan"), dtype=w.torch_dtype, device=dev)
     kv_lens = [a + b for a, b in zip(n_mod, n_new)]
     r.pc.pc_prefill_attn_batched(layer, Q, qp, q_off, asm_K, asm_V, asm_pos, kv_off, kv_lens, out)
@@ -304,13 +309,50 @@ def _batched_run(w, layer, q_sample):
         rows = None
         if q_sample and n_new[b] > q_sample:
             rows = np.unique(np.concatenate([[0, n_new[b] - 1], rng.choice(n_new[b], size=q_sample - 2, replace=False)]))
-        check_attention(c, b, res, rows, "/batched")
+        check_attention(c, b, res, rows, "/fused" if fused else "/batched")
 
 
 def test_batched_reduced_variable_lengths():
     w = W.custom("batched_small", "bf16", 8, 2, 128, [300, 64, 90, 70, 120, 33], [-1, 0, 0, 0, 1, 1],
                  [W.Prompt([0, 1, 4], 40), W.Prompt([0, 2], 17), W.Prompt([3, 0, 5], 64), W.Prompt([0], 1)], max_pos=1024)
     _batched_run(w, 0, None)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_fused_assemble_append_matches_oracle(dtype):
+    """One launch for assembly + append: same rows, bit for bit, as the oracle's concat and rotation."""
+    hq, hkv, d = (8, 2, 128) if dtype == "bf16" else (4, 2, 64)
+    w = W.custom("fused_small", dtype, hq, hkv, d, [300, 64, 90, 70, 120, 33], [-1, 0, 0, 0, 1, 1],
+                 [W.Prompt([0, 1, 4], 40), W.Prompt([0, 2], 17), W.Prompt([], 9), W.Prompt([3, 0, 5], 64),
+                  W.Prompt([0], 1)], max_pos=1024)
+    _batched_run(w, 0, None, fused=True)
+
+
+def test_fused_assemble_append_many_prompts_takes_two_launches():
+    """More prompts than one argument block holds: the call falls back to gather then append."""
+    sizes = [40, 24, 56]
+    prompts = [W.Prompt([i % 3], 1 + (i % 5)) for i in range(70)]
+    w = W.custom("fused_many", "bf16", 4, 2, 64, sizes, None, prompts, max_pos=512)
+    _batched_run(w, 0, None, fused=True)
+
+
+def test_fused_assemble_append_capacity_error_touches_nothing():
+    w = W.custom("fused_cap", "bf16", 8, 2, 128, [32], None, [W.Prompt([0], 8)], max_pos=256)
+    c = build_case(w, 0)
+    r = GpuRunner(c)
+    dev = r.dev
+    asm_K = torch.full((39, 2, 128), 3.0, dtype=torch.bfloat16, device=dev)   # one row short of 32 + 8
+    asm_V = torch.full_like(asm_K, 3.0)
+    asm_pos = torch.full((39,), -7, dtype=torch.int32, device=dev)
+    pcx = c.prompts[0]
+    qp = torch.from_numpy(pcx.q_pos).to(dev)
+    with pytest.raises(pcb.PcError) as ei:
+        r.pc.pc_assemble_append_kv_batched(0, [pcx.module_ids], pcx.K_new.to(dev), pcx.V_new.to(dev), qp, [0, 8],
+                                           asm_K, asm_V, asm_pos, [0, 39])
+    assert ei.value.status == -5
+    torch.cuda.synchronize()
+    assert torch.all(asm_K == 3.0) and torch.all(asm_pos == -7)
+    r.close()
 
 
 # ------------------------------------------------------------------ the benchmark's configurations at full size
@@ -327,6 +369,10 @@ def test_config3_long_doc_8k_full_size_sampled(layer):
 @pytest.mark.parametrize("seed", [0, 1])
 def test_config4_sparse_selection_full_size_sampled(seed):
     run_and_check(W.sparse_selection(seed=seed, n_prompts=2), layer=seed * 31, q_sample=8)
+
+
+def test_config3_long_doc_8k_fused_assembly_full_size_sampled():
+    _batched_run(W.long_doc_8k(), 0, 24, fused=True)
 
 
 def test_config5_batched_serving_full_size_sampled():
