@@ -32,6 +32,7 @@ struct AttnParams {
     uint16_t *part_o;        // bf16 [n_splits][total_q][Hq][D]: un-normalised partial O of every KV split
     float2 *part_ml;         // [n_splits][total_q][Hq]
     const float2 *rope;      // [max_pos][D/2]
+    const float2 *rope_t;    // [D/2][max_pos]
     int max_pos;
     int Hq, Hkv, G;
     int n_splits;

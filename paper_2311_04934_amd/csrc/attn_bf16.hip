@@ -511,6 +511,7 @@ int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const i
     p.part_o = reinterpret_cast<uint16_t *>(ctx->scratch);
     p.part_ml = reinterpret_cast<float2 *>(reinterpret_cast<uint8_t *>(ctx->scratch) + (((size_t)n_splits * total_q * Hq * D * sizeof(uint16_t) + 255) & ~(size_t)255));
     p.rope = ctx->rope_table;
+    p.rope_t = ctx->rope_table_t;
     p.max_pos = ctx->cfg.max_pos;
     p.Hq = Hq;
     p.Hkv = Hkv;

@@ -75,6 +75,7 @@ __device__ __forceinline__ void dma_b32(const void *gsrc, uint32_t lds_addr)
 struct QTile {        // one 32-query row tile of a wave
     bool valid;       // this lane's query exists
     int head;
+    int tq;           // index of the 32-query tile inside the prompt
     int qi;           // query index inside the prompt
     int qpos;         // its position ID (+inf when the lane has no query)
 };
@@ -125,6 +126,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
         const int g_head = act ? rt / tiles_q : 0;
         const int tq = act ? rt % tiles_q : 0;
         qt[x].head = kvh * p.G + g_head;
+        qt[x].tq = tq;
         qt[x].qi = tq * RW + col;
         qt[x].valid = act && qt[x].qi < seq.n_q;
         qt[x].qpos = qt[x].valid ? p.q_pos[seq.q_begin + qt[x].qi] : kPosInf;
@@ -172,56 +174,75 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
     };
 
     // ---- prologue.  Order matters for latency.  The position IDs come first (the rotation-table
-    // addresses depend on them); then the first two K/V tiles are requested, and only then the raw
-    // Q rows and the table rows.  The compiler does not see the asynchronous copies: when it waits
-    // for "its" loads, older copies that are still in flight simply make that wait longer (the first
-    // tile is needed at that point anyway), while younger copies could let the count drop early.
-    // So no copy is issued between a load and its use: tile 2 follows once Q is in registers.
+    // addresses depend on them).  Then three kinds of requests go out together: the raw Q rows, as
+    // asynchronous copies into LDS (whole 256-byte rows per 16 lanes, where a direct load into the
+    // MFMA operand layout would touch 32 cache lines per instruction); the first two K/V tiles; and
+    // the table values.  The compiler does not see the copies: when it waits for the table values,
+    // the older copies still in flight make that wait longer (all of them are needed now anyway),
+    // while younger copies could let the count drop early, so the third tile is issued later.
+    //
+    // Q staging space: row tile s = wave*NQT + x of the workgroup gets 8 KiB of tile buffers that stay
+    // unused until the first workgroup barrier: K buffers 2 and 3, raw-V buffer 2, V^T buffer 1.
+    auto q_region = [&](int s8) -> int {
+        return s8 < 4 ? LDS_K + 2 * TILE_BYTES + s8 * 8192
+                      : (s8 < 6 ? LDS_V + 2 * TILE_BYTES + (s8 - 4) * 8192 : LDS_VT + TILE_BYTES + (s8 - 6) * 8192);
+    };
+    static_assert(NVRAW == 3 && NVT == 2 && NBUF == 4 && NQT * NW == 8, "Q staging relies on this tile-buffer layout");
+    bf16x8 qf[NQT][KB];
     if (n_tiles > 0) {
         int qq = qt[0].qpos;
         asm volatile("" : "+v"(qq));   // the position IDs have arrived
         qt[0].qpos = qq;
+#pragma unroll
+        for (int x = 0; x < NQT; ++x) {
+            const uint8_t *qhead = reinterpret_cast<const uint8_t *>(p.q) + ((size_t)seq.q_begin * p.Hq + qt[x].head) * (D * 2);
+            const uint32_t dst0 = __builtin_amdgcn_readfirstlane(lds_base + q_region(wave * NQT + x));
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int r = 4 * j + (lane >> 4), c = lane & 15;   // row of the tile, 16-byte chunk of the row
+                int qi = qt[x].tq * RW + r;
+                qi = qi < seq.n_q ? qi : seq.n_q - 1;                // rows past the prompt's last query: any valid row
+                dma_b128(qhead + (size_t)qi * p.Hq * (D * 2) + ((c ^ (r & 15)) << 4), dst0 + j * 1024);
+            }
+        }
         issue_tile(0);
         issue_tile(1);
-    }
-    // Q rotated at the queries' position IDs, scaled by log2(e)/sqrt(d), bf16: B operand of K.Q
-    bf16x8 qf[NQT][KB];
+        // table values (position-minor table: the 32 lanes of a half-wave hold 32 queries, usually at
+        // consecutive positions, so one pair index is a contiguous 256-byte read for them)
+        float2 cs[NQT][KB / 2][8];
 #pragma unroll
-    for (int x = 0; x < NQT; ++x) {
-        const int q_row = seq.q_begin + (qt[x].valid ? qt[x].qi : 0);
-        const uint16_t *qrow = p.q + ((size_t)q_row * p.Hq + qt[x].head) * D;
-        int tpos = qt[x].qpos;
-        tpos = tpos < 0 ? 0 : (tpos >= p.max_pos ? p.max_pos - 1 : tpos);
-        const float2 *trow = p.rope + (size_t)tpos * (D / 2);
+        for (int x = 0; x < NQT; ++x) {
+            int tpos = qt[x].qpos;
+            tpos = tpos < 0 ? 0 : (tpos >= p.max_pos ? p.max_pos - 1 : tpos);
+            const float2 *tcol = p.rope_t + tpos;
 #pragma unroll
-        for (int kb = 0; kb < KB / 2; ++kb) {
-            const int d0 = kb * 16 + hh * 8;
-            const u32x4 lo = *reinterpret_cast<const u32x4 *>(qrow + d0);
-            const u32x4 hi = *reinterpret_cast<const u32x4 *>(qrow + d0 + D / 2);
-            bf16x8 olo, ohi;
+            for (int kb = 0; kb < KB / 2; ++kb)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const uint32_t wl = lo[e >> 1], wh = hi[e >> 1];
-                const float xl = bf16_bits_to_f32((e & 1) ? (wl >> 16) : (wl & 0xffffu));
-                const float xh = bf16_bits_to_f32((e & 1) ? (wh >> 16) : (wh & 0xffffu));
-                const float2 cs = trow[d0 + e];
-                olo[e] = (__bf16)((xl * cs.x - xh * cs.y) * p.q_scale);
-                ohi[e] = (__bf16)((xh * cs.x + xl * cs.y) * p.q_scale);
+                for (int e = 0; e < 8; ++e) cs[x][kb][e] = tcol[(size_t)(kb * 16 + hh * 8 + e) * p.max_pos];
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // Q rows and tiles 0 and 1 have landed, the table values too
+        // Q rotated at the queries' position IDs, scaled by log2(e)/sqrt(d), bf16: B operand of K.Q
+#pragma unroll
+        for (int x = 0; x < NQT; ++x) {
+            const lds_u8 *qrow = lds + q_region(wave * NQT + x) + col * ROW_BYTES;
+#pragma unroll
+            for (int kb = 0; kb < KB / 2; ++kb) {
+                const u32x4 lo = *reinterpret_cast<const __attribute__((address_space(3))) u32x4 *>(qrow + (((2 * kb + hh) ^ (col & 15)) << 4));
+                const u32x4 hi = *reinterpret_cast<const __attribute__((address_space(3))) u32x4 *>(qrow + (((2 * kb + hh + 8) ^ (col & 15)) << 4));
+                bf16x8 olo, ohi;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const uint32_t wl = lo[e >> 1], wh = hi[e >> 1];
+                    const float xl = bf16_bits_to_f32((e & 1) ? (wl >> 16) : (wl & 0xffffu));
+                    const float xh = bf16_bits_to_f32((e & 1) ? (wh >> 16) : (wh & 0xffffu));
+                    olo[e] = (__bf16)((xl * cs[x][kb][e].x - xh * cs[x][kb][e].y) * p.q_scale);
+                    ohi[e] = (__bf16)((xh * cs[x][kb][e].x + xl * cs[x][kb][e].y) * p.q_scale);
+                }
+                qf[x][kb] = olo;
+                qf[x][kb + KB / 2] = ohi;
             }
-            qf[x][kb] = olo;
-            qf[x][kb + KB / 2] = ohi;
         }
     }
-    // pin Q here: the third tile must not be requested before the loads above have been consumed
-#pragma unroll
-    for (int x = 0; x < NQT; ++x)
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb) {
-            u32x4 w = __builtin_bit_cast(u32x4, qf[x][kb]);
-            asm volatile("" : "+v"(w));
-            qf[x][kb] = __builtin_bit_cast(bf16x8, w);
-        }
-    if (n_tiles > 0) issue_tile(2);
     // smallest query position in the wave: a key tile whose largest position exceeds it needs the mask
     int min_qpos = qt[0].qpos;
 #pragma unroll
@@ -470,9 +491,9 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
 
     // ---- main loop
     if (n_tiles > 0) {
-        // tiles 0 (and 1, 2 when they exist) were issued in the prologue; tile 0 visible:
-        PC_WAIT_VMCNT(2 * DMA_PER_TILE);
+        // tiles 0 and 1 have landed (see the prologue); after this barrier nobody reads staged Q any more
         __syncthreads();
+        issue_tile(2);
         bool mask_cur = tile_needs_mask(0);
 #pragma unroll
         for (int k = 0; k < FRAG_PER_WAVE; ++k) transpose_read(0, k);

@@ -52,6 +52,7 @@ struct pc_ctx {
     std::vector<std::unordered_map<int, pc::ModuleEntry>> modules;  // per layer
 
     float2 *rope_table = nullptr;  // device, [max_pos][head_dim/2] (cos, sin)
+    float2 *rope_table_t = nullptr;  // the same values as [head_dim/2][max_pos]: coalesced when lanes hold consecutive positions
 
     float *scratch = nullptr;  // device, split-KV partials
     size_t scratch_bytes = 0;

@@ -185,12 +185,21 @@ int pc_create(const pc_config *cfg, pc_ctx **out_ctx)
                 host[(size_t)p * half + i] = make_float2((float)cos(a), (float)sin(a));
             }
         ok = hipMemcpy(ctx->rope_table, host.data(), n_entries * sizeof(float2), hipMemcpyHostToDevice) == hipSuccess;
+        // position-minor copy for the attention kernel whose lanes each hold one query (often consecutive positions)
+        if (ok) ok = hipMalloc(reinterpret_cast<void **>(&ctx->rope_table_t), n_entries * sizeof(float2)) == hipSuccess;
+        if (ok) {
+            std::vector<float2> host_t(n_entries);
+            for (int p = 0; p < cfg->max_pos; ++p)
+                for (int i = 0; i < half; ++i) host_t[(size_t)i * cfg->max_pos + p] = host[(size_t)p * half + i];
+            ok = hipMemcpy(ctx->rope_table_t, host_t.data(), n_entries * sizeof(float2), hipMemcpyHostToDevice) == hipSuccess;
+        }
     }
     if (!ok) {
         (void)hipGetLastError();
         if (ctx->pool) (void)hipFree(ctx->pool);
         if (ctx->scratch) (void)hipFree(ctx->scratch);
         if (ctx->rope_table) (void)hipFree(ctx->rope_table);
+        if (ctx->rope_table_t) (void)hipFree(ctx->rope_table_t);
         delete ctx;
         return PC_E_HIP;
     }
@@ -255,6 +264,7 @@ int pc_destroy(pc_ctx *ctx)
     if (ctx->pool) (void)hipFree(ctx->pool);
     if (ctx->scratch) (void)hipFree(ctx->scratch);
     if (ctx->rope_table) (void)hipFree(ctx->rope_table);
+    if (ctx->rope_table_t) (void)hipFree(ctx->rope_table_t);
     delete ctx;
     return PC_OK;
 }
