@@ -29,9 +29,9 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
-# HBM bytes per launch from rocprofv3 FETCH_SIZE (x1.998, calibrated on a copy of known size) + WRITE_SIZE;
-# see profiles/long_doc_8k_hot_path.md.  Only known for the default workload.
-MEASURED_TRAFFIC = {("long_doc_8k", 32): {"attn": 52.6e6 + 34.1e6, "gather": 33.6e6 + 33.6e6}}
+# HBM bytes per launch from rocprofv3 FETCH_SIZE (x1.988, calibrated on a copy of known size) + WRITE_SIZE;
+# the summaries are kept under profiles/.  Only known for the default workload and launch mode.
+MEASURED_TRAFFIC = {("long_doc_8k", 32): {"attn": 52.4e6 + 17.3e6, "gather": 34.6e6 + 34.6e6}}
 
 
 def attn_flops(w, prompt_lens, n_new):
