@@ -74,12 +74,52 @@ __device__ __forceinline__ void gather_tile(const GatherArgs &a, int tile, uint8
         out_pos[sg.dst_row + r0 + r] = sg.start_pos + r0 + r;
 }
 
+// Eight consecutive elements of a row as floats (bf16: one 16-byte access; fp32: two).
+template <typename T>
+struct Vec8;
+template <>
+struct Vec8<uint16_t> {
+    static __device__ __forceinline__ void load(const uint16_t *p, float (&x)[8])
+    {
+        const u32x4 w = *reinterpret_cast<const u32x4 *>(p);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = __uint_as_float((e & 1) ? (w[e >> 1] & 0xffff0000u) : (w[e >> 1] << 16));
+    }
+    static __device__ __forceinline__ void store(uint16_t *p, const float (&x)[8])
+    {
+        typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+        bf16x8 w;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) w[e] = (__bf16)x[e];
+        *reinterpret_cast<bf16x8 *>(p) = w;
+    }
+};
+template <>
+struct Vec8<float> {
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    static __device__ __forceinline__ void load(const float *p, float (&x)[8])
+    {
+        const f32x4 a = *reinterpret_cast<const f32x4 *>(p), b = *reinterpret_cast<const f32x4 *>(p + 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { x[e] = a[e]; x[4 + e] = b[e]; }
+    }
+    static __device__ __forceinline__ void store(float *p, const float (&x)[8])
+    {
+        f32x4 a, b;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { a[e] = x[e]; b[e] = x[4 + e]; }
+        *reinterpret_cast<f32x4 *>(p) = a;
+        *reinterpret_cast<f32x4 *>(p + 4) = b;
+    }
+};
+
 // Row `row` of the append's flat work list, handled by one workgroup: K_new rotated at the row's
-// position ID into the tail of the assembled K, V_new copied, the position ID written.
+// position ID into the tail of the assembled K, V_new copied, the position ID written.  A thread
+// rotates 8 pairs (element i with element i + d/2) per pass when d is a multiple of 16.
 template <typename T>
 __device__ __forceinline__ void append_row(const AppendSeg *seg, int n_segs, int row, const T *k_new, const T *v_new,
-                                              const int32_t *q_pos, T *asm_k, T *asm_v, int32_t *asm_pos,
-                                              int n_kv_heads, int d, const float2 *table, int max_pos)
+                                           const int32_t *q_pos, T *asm_k, T *asm_v, int32_t *asm_pos, int n_kv_heads,
+                                           int d, const float2 *table, int max_pos)
 {
     int r = row, s = 0;
     while (s < n_segs && r >= seg[s].n) {
@@ -97,14 +137,37 @@ __device__ __forceinline__ void append_row(const AppendSeg *seg, int n_segs, int
     const T *vs = v_new + (size_t)src * row_elems;
     T *kd = asm_k + (size_t)dst * row_elems;
     T *vd = asm_v + (size_t)dst * row_elems;
-    for (int e = threadIdx.x; e < n_kv_heads * half; e += kThreads) {
-        const int h = e / half, i = e % half;
-        const float2 cs = trow[i];
-        const float lo = Elem<T>::load(ks + h * d + i), hi = Elem<T>::load(ks + h * d + i + half);
-        Elem<T>::store(kd + h * d + i, lo * cs.x - hi * cs.y);
-        Elem<T>::store(kd + h * d + i + half, hi * cs.x + lo * cs.y);
+    if (d & 15) {   // odd head sizes (fp32 only): element by element
+        for (int e = threadIdx.x; e < n_kv_heads * half; e += kThreads) {
+            const int h = e / half, i = e % half;
+            const float2 cs = trow[i];
+            const float lo = Elem<T>::load(ks + h * d + i), hi = Elem<T>::load(ks + h * d + i + half);
+            Elem<T>::store(kd + h * d + i, lo * cs.x - hi * cs.y);
+            Elem<T>::store(kd + h * d + i + half, hi * cs.x + lo * cs.y);
+        }
+        for (int e = threadIdx.x; e < row_elems; e += kThreads) vd[e] = vs[e];
+    } else {
+        // V first: its copy does not depend on the position ID
+        const int n_vec = (int)((size_t)row_elems * sizeof(T) >> 4);
+        const u32x4 *vs4 = reinterpret_cast<const u32x4 *>(vs);
+        u32x4 *vd4 = reinterpret_cast<u32x4 *>(vd);
+        for (int i = threadIdx.x; i < n_vec; i += kThreads) vd4[i] = vs4[i];
+        const int blocks_per_head = half >> 3;
+        for (int blk = threadIdx.x; blk < n_kv_heads * blocks_per_head; blk += kThreads) {
+            const int h = blk / blocks_per_head, i0 = (blk % blocks_per_head) << 3;
+            float lo[8], hi[8], olo[8], ohi[8];
+            Vec8<T>::load(ks + h * d + i0, lo);
+            Vec8<T>::load(ks + h * d + i0 + half, hi);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float2 cs = trow[i0 + e];
+                olo[e] = lo[e] * cs.x - hi[e] * cs.y;
+                ohi[e] = hi[e] * cs.x + lo[e] * cs.y;
+            }
+            Vec8<T>::store(kd + h * d + i0, olo);
+            Vec8<T>::store(kd + h * d + i0 + half, ohi);
+        }
     }
-    for (int e = threadIdx.x; e < row_elems; e += kThreads) vd[e] = vs[e];
     if (threadIdx.x == 0) asm_pos[dst] = p;
 }
 
