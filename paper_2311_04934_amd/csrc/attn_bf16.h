@@ -82,5 +82,6 @@ __device__ __forceinline__ float sum_across_halves(float x)
 // DMA-staged kernel (attn_bf16_wide.hip): D = 128, 8 row tiles per workgroup, 1 or 2 row tiles per wave
 int launch_attn_bf16_wide(pc_ctx *ctx, attn::AttnParams &p, int n_blocks, hipStream_t stream);
 constexpr int kWideRowTilesPerWg = 8;
+constexpr int kWideMinRowTiles = 4;     // with fewer row tiles per kv head the register-staged kernel is used
 
 }  // namespace pc

@@ -480,7 +480,7 @@ int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const i
     long max_kv = 0;
     for (int s = 0; s < batch.n_seqs; ++s) max_kv = batch.seq[s].n_kv > max_kv ? batch.seq[s].n_kv : max_kv;
     const bool fits_u32 = max_kv * (long)Hkv * D * 2 < (1L << 32);   // the wide kernel uses 32-bit row offsets
-    bool wide = D == 128 && max_row_tiles >= kWideRowTilesPerWg && fits_u32;
+    bool wide = D == 128 && max_row_tiles >= kWideMinRowTiles && fits_u32;
     const int NW = wide ? 4 : (max_row_tiles <= 4 ? 4 : 8);
     const int tiles_per_wg = wide ? kWideRowTilesPerWg : NW;
     const int rb_max = (max_row_tiles + tiles_per_wg - 1) / tiles_per_wg;

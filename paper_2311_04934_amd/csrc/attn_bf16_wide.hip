@@ -516,7 +516,21 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
             for (int g = 0; g < 2 * DB; ++g) read_v(lds + LDS_VT, g);
         }
 
-        for (int t = 0; t < n_tiles; ++t) {
+        // a wave without a row tile (fewer than 8 row tiles in this block) only helps with staging: its
+        // share of the copies and of the V re-layout, and the barriers; the matrix pipe of its SIMD is
+        // left to the wave that has work
+        const bool idle_wave = rb * kWideRowTilesPerWg + wave * NQT >= row_tiles;
+        for (int t = 0; idle_wave && t < n_tiles; ++t) {
+            PC_WAIT_VMCNT(DMA_PER_TILE);
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < DMA_PER_TILE; ++i) issue_piece(t + 3, i);
+#pragma unroll
+            for (int k = 0; k < FRAG_PER_WAVE; ++k) transpose_read(t + 1, k);
+#pragma unroll
+            for (int k = 0; k < FRAG_PER_WAVE; ++k) transpose_write(t + 1, k);
+        }
+        for (int t = 0; !idle_wave && t < n_tiles; ++t) {
             const int buf = t & (NBUF - 1);
             const int n_valid = k_end - (k_begin + t * KT);   // real keys in this tile (may exceed 64)
             const bool has_next = t + 1 < n_tiles;
@@ -545,7 +559,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
         // drain: P.V of the very last sub-tile
         rescale();
 #pragma unroll
-        for (int i = 0; i < 2 * DB; ++i)
+        for (int i = 0; !idle_wave && i < 2 * DB; ++i)
 #pragma unroll
             for (int x = 0; x < NQT; ++x)
                 o_acc[x][i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i], pf[1][x][i / DB], o_acc[x][i % DB], 0, 0, 0);
