@@ -356,7 +356,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) kf[kb] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const lds_u32x4 *>(kbase + koff[kb]));
         PC_FENCE();
-        float m_use[NQT], psum[NQT], pe_even[NQT], dnext[NQT], mxa[NQT][5], mx[NQT], m_new[NQT];
+        float m_use[NQT], psum[NQT], pe_even[NQT], pe_prev[NQT], dnext[NQT], mxa[NQT][5], mx[NQT], m_new[NQT];
         u32x4 pw[NQT][2];
         const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         int e_done = 0;   // softmax elements finished so far (compile-time after unrolling)
@@ -412,24 +412,36 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
                     const int e = e_done + r;
 #pragma unroll
                     for (int x = 0; x < NQT; ++x) {
+                        // The exp of element e is issued here; its consumers (row sum, bf16 pack) handle
+                        // element e-1, whose exp has long finished: nothing waits for a transcendental.
                         float pe = __builtin_amdgcn_exp2f(dnext[x]);
                         asm volatile("" : "+v"(pe));
                         if (e < 15) {
                             dnext[x] = s[x][e + 1] - m_use[x];
                             asm volatile("" : "+v"(dnext[x]));
                         }
-                        psum[x] += pe;
-                        asm volatile("" : "+v"(psum[x]));
-                        if (e & 1) {
-                            typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+                        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+                        if (e > 0) {
+                            psum[x] += pe_prev[x];
+                            asm volatile("" : "+v"(psum[x]));
+                            if ((e - 1) & 1) {
+                                bf16x2 pr;
+                                pr[0] = (__bf16)pe_even[x];
+                                pr[1] = (__bf16)pe_prev[x];
+                                uint32_t w = __builtin_bit_cast(uint32_t, pr);
+                                asm volatile("" : "+v"(w));
+                                pw[x][(e - 1) >> 3][((e - 1) & 7) >> 1] = w;
+                            } else {
+                                pe_even[x] = pe_prev[x];
+                            }
+                        }
+                        pe_prev[x] = pe;
+                        if (e == 15) {   // the last element has no later slot
+                            psum[x] += pe;
                             bf16x2 pr;
                             pr[0] = (__bf16)pe_even[x];
                             pr[1] = (__bf16)pe;
-                            uint32_t w = __builtin_bit_cast(uint32_t, pr);
-                            asm volatile("" : "+v"(w));
-                            pw[x][e >> 3][(e & 7) >> 1] = w;
-                        } else {
-                            pe_even[x] = pe;
+                            pw[x][1][3] = __builtin_bit_cast(uint32_t, pr);
                         }
                     }
                 }
