@@ -42,8 +42,9 @@ def attn_flops(w, prompt_lens, n_new):
     return total
 
 
-def oracle_layer_step(w, starts, layer, prompt_index):
-    """Time the CPU oracle on one layer of one prompt: assemble + rotate/append new K + attention.
+def oracle_layer_step(w, starts, layer, prompt_index, n_queries=None):
+    """Time the CPU oracle on one layer of one prompt: assemble + rotate/append new K + attention
+    (of the first n_queries uncached tokens; all of them by default).
 
     Input generation and dtype widening are outside the timed part.  Returns (seconds,
     attention FLOPs done, description of the sample)."""
@@ -68,18 +69,20 @@ def oracle_layer_step(w, starts, layer, prompt_index):
     K = np.concatenate([aK, oracle.rope(kn, q_pos, w.rope_base)])
     V = np.concatenate([aV, vn])
     P = np.concatenate([aP, q_pos]).astype(np.int32)
-    oracle.attn(q, q_pos, K, V, P, w.rope_base)
+    nq = p.n_new if n_queries is None else min(n_queries, p.n_new)
+    oracle.attn(q[:nq], q_pos[:nq], K, V, P, w.rope_base)
     secs = time.perf_counter() - t0
     T = len(aP)
-    flops = 4 * w.n_q_heads * w.head_dim * (p.n_new * T + p.n_new * (p.n_new + 1) // 2)
-    return secs, flops, f"layer {layer}, prompt {prompt_index} of {w.name}: all {p.n_new} uncached tokens x {w.n_q_heads} heads over {T + p.n_new} keys"
+    flops = 4 * w.n_q_heads * w.head_dim * (nq * T + nq * (nq + 1) // 2)
+    which = f"all {p.n_new}" if nq == p.n_new else f"the first {nq} of {p.n_new}"
+    return secs, flops, f"layer {layer}, prompt {prompt_index} of {w.name}: {which} uncached tokens x {w.n_q_heads} heads over {T + p.n_new} keys"
 
 
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="long_doc_8k",
                     choices=["long_doc_8k", "llama7b_doc", "sparse_selection", "batched_serving"])
     ap.add_argument("--layers", type=int, default=32)
@@ -200,8 +203,10 @@ def main() -> int:
         ms_per_step_events = (time.perf_counter() - t0) * 1e3 / args.steps
         for name, kind in (("gather", pcb.PROF_GATHER), ("append", pcb.PROF_APPEND), ("attn", pcb.PROF_ATTN),
                            ("combine", pcb.PROF_COMBINE)):
-            n, ms = pc.pc_profile_read(kind)
-            kern[name] = {"launches": n, "avg_us": (ms * 1e3 / n) if n else None}
+            each = pc.pc_profile_read_each(kind, args.steps * L) * 1e3      # microseconds per launch
+            n = len(each)
+            kern[name] = {"launches": n, "avg_us": float(each.mean()) if n else None,
+                          "median_us": float(np.median(each)) if n else None, "min_us": float(each.min()) if n else None}
         pc.pc_profile_enable(0)
     launch = pc.pc_last_attn_launch()
 
@@ -234,6 +239,7 @@ def main() -> int:
         attn_tf = flops_layer / (a_us * 1e-6) / 1e12
         gat_gbs = gather_bytes_layer / (g_us * 1e-6) / 1e9
         result["kernels_us"] = {k: (round(v["avg_us"], 2) if v["avg_us"] else None) for k, v in kern.items()}
+        result["kernels_us_median_min"] = {k: [round(v["median_us"], 2), round(v["min_us"], 2)] for k, v in kern.items() if v["avg_us"]}
         result["assemble_GBps"] = round(gat_gbs, 1)
         result["attn_kernel_TFLOPs"] = round(attn_tf, 1)
         result["roofline"] = {"kernel": "attn_bf16_dma_kernel<1,8>" if (w.head_dim == 128 and launch[2] == 8 and launch[0] >= 1 and w.n_q_heads // w.n_kv_heads * ((n_new[0] + 31) // 32) >= 8) else "attn_bf16_kernel", "bound": "mfma", "achieved": round(attn_tf, 1),
@@ -275,6 +281,19 @@ def main() -> int:
         secs, flops_done, sample = oracle_layer_step(w, starts, 0, 0)
         result["cpu_baseline"] = {"value": round(flops_done / secs / 1e12, 6), "unit": "TFLOP/s", "cores": cores,
                                   "kind": "oracle", "seconds": round(secs, 2), "sample": sample}
+        # the same oracle on one core, on an eighth of the queries
+        if oracle.set_threads(1) == 1:
+            secs1, flops1, sample1 = oracle_layer_step(w, starts, 0, 0, n_queries=max(1, w.prompts[0].n_new // 8))
+            result["cpu_baseline"]["one_core"] = {"value": round(flops1 / secs1 / 1e12, 6), "seconds": round(secs1, 2),
+                                                  "sample": sample1}
+        oracle.set_threads(cores)
+        try:
+            with open("/proc/cpuinfo") as f:
+                model = next((ln.split(":", 1)[1].strip() for ln in f if ln.startswith("model name")), None)
+            result["cpu_baseline"]["cpu"] = model
+            result["cpu_baseline"]["host_cores"] = os.cpu_count()
+        except OSError:
+            pass
     result["paper_context"] = "paper reports TTFT reductions up to 8x (GPU: RTX 4090/A40/A100) and 60x (CPU: i9-13900K/Ryzen 7950X); no GB/s or TFLOP/s"
     pc.close()
     print(json.dumps(result))

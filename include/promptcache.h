@@ -274,11 +274,15 @@ int pc_last_attn_launch(const pc_ctx *ctx, int *n_splits, int *n_workgroups, int
  * (until they are used up), which then holds that kernel's own begin and end timestamps on
  * the stream it ran on.  pc_profile_read waits for the recorded events of one kind, returns
  * how many launches were timed and the sum of their durations in milliseconds, and resets
- * that kind's counter.  kind: 0 gather (pc_assemble_kv*), 1 append, 2 attention main kernel,
- * 3 split-KV merge, 4 pc_rope.
+ * that kind's counter.  pc_profile_read_each does the same and also copies the first
+ * `capacity` durations (milliseconds, launch order) to the host array ms_out.
+ * kind: 0 gather (pc_assemble_kv*, pc_assemble_append_kv_batched), 1 append, 2 attention
+ * main kernel, 3 split-KV merge, 4 pc_rope.
  */
 int pc_profile_enable(pc_ctx *ctx, int max_records_per_kind);
 int pc_profile_read(pc_ctx *ctx, int kind, int *n_records, double *total_ms);
+int pc_profile_read_each(pc_ctx *ctx, int kind, float *ms_out, int capacity, int *n_records,
+                         double *total_ms);
 
 #ifdef __cplusplus
 }

@@ -24,6 +24,7 @@ EXPORTS = [
     "pc_prefill_attn_batched",
     "pc_schema_layout", "pc_uncached_positions", "pc_check_selection", "pc_bytes_per_token",
     "pc_module_info", "pc_pool_usage", "pc_last_attn_launch", "pc_profile_enable", "pc_profile_read",
+    "pc_profile_read_each",
 ]
 PROF_GATHER, PROF_APPEND, PROF_ATTN, PROF_COMBINE, PROF_ROPE = range(5)
 
@@ -79,6 +80,7 @@ def lib() -> ctypes.CDLL:
     L.pc_last_attn_launch.argtypes = [vp, ip, ip, ip]
     L.pc_profile_enable.argtypes = [vp, i]
     L.pc_profile_read.argtypes = [vp, i, ip, ctypes.POINTER(ctypes.c_double)]
+    L.pc_profile_read_each.argtypes = [vp, i, vp, i, ip, ctypes.POINTER(ctypes.c_double)]
     for name in EXPORTS:
         fn = getattr(L, name)
         if name not in ("pc_strerror", "pc_schema_layout", "pc_bytes_per_token"):
@@ -282,3 +284,11 @@ class PromptCache:
         n, ms = ctypes.c_int(0), ctypes.c_double(0.0)
         _check(lib().pc_profile_read(self._ctx, int(kind), ctypes.byref(n), ctypes.byref(ms)), "pc_profile_read")
         return n.value, ms.value
+
+    def pc_profile_read_each(self, kind: int, capacity: int) -> np.ndarray:
+        """Durations (ms) of the recorded launches of one kind, in launch order."""
+        buf = np.zeros(max(capacity, 1), dtype=np.float32)
+        n, ms = ctypes.c_int(0), ctypes.c_double(0.0)
+        _check(lib().pc_profile_read_each(self._ctx, int(kind), _np_ptr(buf), int(capacity), ctypes.byref(n),
+                                          ctypes.byref(ms)), "pc_profile_read_each")
+        return buf[:min(n.value, capacity)].copy()

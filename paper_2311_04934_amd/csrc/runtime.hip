@@ -236,9 +236,9 @@ int pc_profile_enable(pc_ctx *ctx, int max_records_per_kind)
     return PC_OK;
 }
 
-int pc_profile_read(pc_ctx *ctx, int kind, int *n_records, double *total_ms)
+int pc_profile_read_each(pc_ctx *ctx, int kind, float *ms_out, int capacity, int *n_records, double *total_ms)
 {
-    if (!ctx || kind < 0 || kind >= kProfKinds) return PC_E_BADARG;
+    if (!ctx || kind < 0 || kind >= kProfKinds || capacity < 0 || (capacity > 0 && !ms_out)) return PC_E_BADARG;
     double sum = 0.0;
     const int n = ctx->prof.used[kind];
     for (int i = 0; i < n; ++i) {
@@ -248,12 +248,18 @@ int pc_profile_read(pc_ctx *ctx, int kind, int *n_records, double *total_ms)
             (void)hipGetLastError();
             return PC_E_HIP;
         }
+        if (i < capacity) ms_out[i] = ms;
         sum += ms;
     }
     ctx->prof.used[kind] = 0;
     if (n_records) *n_records = n;
     if (total_ms) *total_ms = sum;
     return PC_OK;
+}
+
+int pc_profile_read(pc_ctx *ctx, int kind, int *n_records, double *total_ms)
+{
+    return pc_profile_read_each(ctx, kind, nullptr, 0, n_records, total_ms);
 }
 
 int pc_destroy(pc_ctx *ctx)
