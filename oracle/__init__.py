@@ -55,6 +55,8 @@ def _load():
     lib.orc_attn.restype = None
     lib.orc_full_masked.argtypes = [P, P, P, P, P, c_int, c_int, c_int, c_int, c_dbl, P, P]
     lib.orc_full_masked.restype = None
+    lib.orc_fill_param.argtypes = [P, P, P, c_int, c_int, P, P, c_int, c_int, c_int, c_dbl]
+    lib.orc_fill_param.restype = c_int
     lib.orc_bytes_per_token.argtypes = [c_int, c_int, c_int, c_int]
     lib.orc_bytes_per_token.restype = c_long
     _lib = lib
@@ -174,6 +176,25 @@ def full_masked(Q_raw, K_raw, V, pos, module_of, base: float = 10000.0):
     _load().orc_full_masked(_ptr(Q), _ptr(K), _ptr(V), _ptr(p), _ptr(m), N, Hq, Hkv, d, float(base),
                             _ptr(out), _ptr(K_enc))
     return out, K_enc
+
+
+POS_NONE = 2 ** 31 - 1   # position ID of a buffer row that holds no token (never visible)
+
+
+def fill_param(K, V, pos, row0: int, length: int, K_arg_raw, V_arg, base: float = 10000.0):
+    """Supply an argument to a parameter whose placeholder rows are [row0, row0+length) of an
+    assembled fp64 buffer (Sec. 3.3): returns new (K, V, pos); see orc_fill_param."""
+    K = np.array(_f64(K), copy=True)
+    V = np.array(_f64(V), copy=True)
+    pos = np.array(_i32(pos), copy=True)
+    ka, va = _f64(K_arg_raw), _f64(V_arg)
+    assert K.ndim == 3 and V.shape == K.shape and ka.shape == va.shape and ka.shape[1:] == K.shape[1:]
+    assert 0 <= row0 and row0 + length <= K.shape[0]
+    rc = _load().orc_fill_param(_ptr(K), _ptr(V), _ptr(pos), int(row0), int(length), _ptr(ka), _ptr(va),
+                                int(ka.shape[0]), int(K.shape[1]), int(K.shape[2]), float(base))
+    if rc != 0:
+        raise ValueError("argument longer than the parameter")
+    return K, V, pos
 
 
 def bytes_per_token(n_layers: int, n_kv_heads: int, head_dim: int, elem_bytes: int) -> int:

@@ -304,6 +304,47 @@ void orc_full_masked(const double *Q_raw, const double *K_raw, const double *V, 
 }
 
 /* ------------------------------------------------------------------ */
+/* Parameterised modules  (Sec. 3.2.2; Sec. 3.3, last paragraph)        */
+/* ------------------------------------------------------------------ */
+
+/* Position ID of a buffer row that holds no token: larger than any query's,
+ * so the rule  pos_k <= pos_q  never admits it. */
+#define ORC_POS_NONE INT32_MAX
+
+/*
+ * A module was encoded with a parameter of `len` placeholder tokens; their
+ * rows sit at K/V/pos[row0 .. row0+len) of an assembled buffer and already
+ * carry the placeholders' position IDs.  A prompt supplies an argument of
+ * n_arg <= len tokens.  Argument token i takes over the position ID of
+ * placeholder i; its states replace the placeholder's: the key is the raw key
+ * rotated at that position ID, the value is copied.  Placeholders beyond the
+ * argument are white space that carries no meaning: they cease to be tokens
+ * (their position becomes ORC_POS_NONE; their states are left as they are
+ * and can never be seen).
+ *
+ * K,V   [rows][n_heads][d] assembled buffer (fp64), pos [rows]
+ * K_arg_raw, V_arg  [n_arg][n_heads][d]
+ * returns 0, or -1 when the argument is longer than the parameter.
+ */
+int orc_fill_param(double *K, double *V, int32_t *pos, int row0, int len, const double *K_arg_raw,
+                   const double *V_arg, int n_arg, int n_heads, int d, double base)
+{
+    if (n_arg < 0 || len < 0 || n_arg > len) return -1;
+    const size_t row = (size_t)n_heads * d;
+    for (int i = 0; i < n_arg; ++i) {
+        double *k = K + (size_t)(row0 + i) * row;
+        double *v = V + (size_t)(row0 + i) * row;
+        for (size_t c = 0; c < row; ++c) {
+            k[c] = K_arg_raw[(size_t)i * row + c];
+            v[c] = V_arg[(size_t)i * row + c];
+        }
+        orc_rope(k, 1, n_heads, d, &pos[row0 + i], base);
+    }
+    for (int i = n_arg; i < len; ++i) pos[row0 + i] = ORC_POS_NONE;
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
 /* Memory per cached token  (Table 2)                                   */
 /* ------------------------------------------------------------------ */
 

@@ -404,6 +404,73 @@ def test_toy_transformer_detects_wrong_positions():
 
 
 # ---------------------------------------------------------------- cost model (Sec. 2.2, 5.4)
+# ------------------------------------------------------------------ parameterised modules (Sec. 3.2.2, Sec. 3.3)
+def _param_case(rng, n_arg, H=2, d=8, start=110, n_mod=12, off=5, plen=4, n_new=3):
+    Kmod = rope_complex(rng.standard_normal((n_mod, H, d)), np.arange(start, start + n_mod))
+    Vmod = rng.standard_normal((n_mod, H, d))
+    K, V, P = oracle.assemble([Kmod], [Vmod], [start])
+    Ka, Va = rng.standard_normal((n_arg, H, d)), rng.standard_normal((n_arg, H, d))
+    Q = rng.standard_normal((n_new, H, d))
+    q_pos = np.arange(start + n_mod, start + n_mod + n_new, dtype=np.int32)
+    return K, V, P, Ka, Va, Q, q_pos, off, plen
+
+
+def test_param_positions_follow_the_logged_placeholders():
+    rng = np.random.default_rng(40)
+    for line in open(os.path.join(GOLDEN, "param_example.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        lhs, rhs = line.split("->")
+        start, off, plen, n_arg = (int(t) for t in lhs.split())
+        want_pos = [int(t) for t in rhs.split("|")[0].split()]
+        want_none = int(rhs.split("|")[1])
+        K, V, P, Ka, Va, *_ = _param_case(rng, n_arg, start=start, off=off, plen=plen)
+        K2, V2, P2 = oracle.fill_param(K, V, P, off, plen, Ka, Va)
+        assert P2[off:off + n_arg].tolist() == want_pos
+        assert int(np.sum(P2 == oracle.POS_NONE)) == want_none
+        assert np.array_equal(np.delete(P2, np.s_[off + n_arg:off + plen]), np.delete(P, np.s_[off + n_arg:off + plen]))
+
+
+def test_param_full_length_argument_equals_module_encoded_with_the_argument_in_place():
+    rng = np.random.default_rng(41)
+    K, V, P, Ka, Va, Q, q_pos, off, plen = _param_case(rng, 4)
+    K2, V2, P2 = oracle.fill_param(K, V, P, off, plen, Ka, Va)
+    # the module as it would have been encoded had the argument's tokens stood where the placeholders are
+    K_ref, V_ref = K.copy(), V.copy()
+    K_ref[off:off + plen] = rope_complex(Ka, P[off:off + plen])
+    V_ref[off:off + plen] = Va
+    assert np.allclose(K2, K_ref, rtol=0, atol=1e-12) and np.array_equal(V2, V_ref) and np.array_equal(P2, P)
+    # rows outside the parameter are untouched, bit for bit
+    keep = np.r_[0:off, off + plen:len(P)]
+    assert np.array_equal(K2[keep], K[keep]) and np.array_equal(V2[keep], V[keep])
+
+
+@pytest.mark.parametrize("n_arg", [0, 1, 3])
+def test_param_shorter_argument_trailing_placeholders_stop_being_tokens(n_arg):
+    """Attention over the filled buffer equals attention over the buffer with the unused placeholder rows cut out."""
+    rng = np.random.default_rng(42 + n_arg)
+    K, V, P, Ka, Va, Q, q_pos, off, plen = _param_case(rng, n_arg)
+    K2, V2, P2 = oracle.fill_param(K, V, P, off, plen, Ka, Va)
+    got = oracle.attn(Q, q_pos, K2, V2, P2)
+    cut = np.s_[off + n_arg:off + plen]
+    Kc, Vc, Pc = np.delete(K2, cut, axis=0), np.delete(V2, cut, axis=0), np.delete(P2, cut)
+    assert not np.any(Pc == oracle.POS_NONE)
+    # library attention on the shortened buffer (every remaining key precedes every query here)
+    ref = sdpa_masked(rope_complex(Q, q_pos), Kc, Vc, np.ones((len(q_pos), len(Pc)), dtype=bool))
+    assert np.allclose(got, ref, rtol=0, atol=1e-12)
+    # and the placeholder states that were left behind cannot leak, whatever they hold
+    V3 = V2.copy()
+    V3[cut] = 1e6
+    assert np.array_equal(oracle.attn(Q, q_pos, K2, V3, P2), got)
+
+
+def test_param_argument_longer_than_parameter_is_rejected():
+    rng = np.random.default_rng(46)
+    K, V, P, Ka, Va, *_rest, off, plen = _param_case(rng, 5)
+    with pytest.raises(ValueError):
+        oracle.fill_param(K, V, P, off, plen, Ka, Va)
+
+
 def test_attention_flop_count_matches_papers_quadratic_term():
     """4*d FLOPs per (query, key) pair: summed over all n^2 pairs it is the paper's 4 n^2 d."""
     n, d = 3000, 4096
