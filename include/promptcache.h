@@ -67,7 +67,8 @@ typedef enum {
     PC_E_POS_RANGE = -8,      /* a position ID would fall outside [0, max_pos)           */
     PC_E_UNSUPPORTED = -9,    /* head_dim / dtype / head ratio the kernels do not cover  */
     PC_E_HIP = -10,           /* a HIP runtime call failed (no GPU, out of memory, ...)  */
-    PC_E_SCHEMA = -11         /* malformed schema description                            */
+    PC_E_SCHEMA = -11,        /* malformed schema description                            */
+    PC_E_PARAM = -12          /* no such parameter, or argument longer than the parameter */
 } pc_status;
 
 typedef struct {
@@ -183,6 +184,40 @@ int pc_append_kv(pc_ctx *ctx, int layer, const void *K_new_raw, const void *V_ne
                  int n_kv_before, int capacity_tokens, void *stream);
 
 /* ------------------------------------------- batched (several prompts at once) */
+
+/* Position ID of an assembled row that holds no token (an unused placeholder of a
+ * parameter): larger than any query position, so no query ever sees the row. */
+#define PC_POS_NONE 0x7fffffff
+
+/*
+ * Sec. 3.2.2 "Maximizing reuse with parameters", Sec. 3.3 (last paragraph): a module may
+ * contain parameters, runs of `len` placeholder tokens whose position IDs are fixed at
+ * encoding time.  pc_set_module_params records, for module_id in every layer, that rows
+ * [offsets[j], offsets[j]+lens[j]) of the module are parameter j (host arrays; ranges
+ * sorted, disjoint, non-negative; n_params = 0 clears).  It replaces an earlier record.
+ * Errors: PC_E_BADARG.
+ */
+int pc_set_module_params(pc_ctx *ctx, int module_id, int n_params, const int *offsets, const int *lens);
+
+/*
+ * Supply arguments to parameters of the modules of an assembled prompt (same section).
+ * module_ids/n_modules is the list that pc_assemble_kv was called with (it fixes where each
+ * module's rows are).  Argument a belongs to parameter arg_param[a] of module
+ * module_ids[arg_module[a]] and consists of rows arg_offsets[a] .. arg_offsets[a+1]-1 of
+ * K_arg_raw / V_arg (device, [tokens][n_kv_heads][head_dim], keys not yet rotated).  Its
+ * tokens take the placeholders' position IDs in order; the rotated keys and the values
+ * overwrite the placeholders' rows of asm_K / asm_V.  An argument may be shorter than the
+ * parameter: the remaining placeholder rows keep their states but get position PC_POS_NONE,
+ * so they are tokens no more.  A parameter that gets no argument is left as encoded.
+ * One kernel launch on `stream`; host arrays: module_ids, arg_module, arg_param,
+ * arg_offsets (int[n_args+1]).  Errors: PC_E_LAYER, PC_E_UNKNOWN_MODULE, PC_E_BADARG,
+ * PC_E_PARAM (unknown parameter, range outside the module, argument too long),
+ * PC_E_CAPACITY (the modules do not fit capacity_tokens); nothing is enqueued on error.
+ */
+int pc_fill_params(pc_ctx *ctx, int layer, const int *module_ids, int n_modules, int n_args,
+                   const int *arg_module, const int *arg_param, const int *arg_offsets,
+                   const void *K_arg_raw, const void *V_arg, void *asm_K, void *asm_V,
+                   int32_t *asm_pos, int capacity_tokens, void *stream);
 
 /*
  * Sec. 3.4 "batch inference": B prompts derived from one schema, possibly

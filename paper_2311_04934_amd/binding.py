@@ -24,9 +24,10 @@ EXPORTS = [
     "pc_prefill_attn_batched",
     "pc_schema_layout", "pc_uncached_positions", "pc_check_selection", "pc_bytes_per_token",
     "pc_module_info", "pc_pool_usage", "pc_last_attn_launch", "pc_profile_enable", "pc_profile_read",
-    "pc_profile_read_each",
+    "pc_profile_read_each", "pc_set_module_params", "pc_fill_params",
 ]
 PROF_GATHER, PROF_APPEND, PROF_ATTN, PROF_COMBINE, PROF_ROPE = range(5)
+PC_POS_NONE = 0x7FFFFFFF
 
 
 class PcConfig(ctypes.Structure):
@@ -69,6 +70,8 @@ def lib() -> ctypes.CDLL:
     L.pc_append_kv_batched.argtypes = [vp, i, vp, vp, vp, vp, i, vp, vp, vp, vp, vp, vp]
     L.pc_assemble_append_kv_batched.argtypes = [vp, i, vp, vp, i, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     L.pc_prefill_attn_batched.argtypes = [vp, i, vp, vp, vp, i, vp, vp, vp, vp, vp, vp, vp]
+    L.pc_set_module_params.argtypes = [vp, i, i, vp, vp]
+    L.pc_fill_params.argtypes = [vp, i, vp, i, i, vp, vp, vp, vp, vp, vp, vp, vp, i, vp]
     L.pc_schema_layout.argtypes = [i, vp, vp, vp]
     L.pc_schema_layout.restype = ctypes.c_long
     L.pc_uncached_positions.argtypes = [i, i, i, vp]
@@ -259,6 +262,21 @@ class PromptCache:
         _check(lib().pc_prefill_attn_batched(self._ctx, layer, _dev(Q_new), _dev(q_pos), _np_ptr(qo), B, _dev(asm_K),
                                              _dev(asm_V), _dev(asm_pos), _np_ptr(kvo), _np_ptr(kvl), _dev(out),
                                              _stream(stream)), "pc_prefill_attn_batched")
+
+    def pc_set_module_params(self, module_id: int, offsets: Sequence[int], lens: Sequence[int]) -> None:
+        o, l = _ints(offsets), _ints(lens)
+        assert len(o) == len(l)
+        _check(lib().pc_set_module_params(self._ctx, int(module_id), len(o), _np_ptr(o), _np_ptr(l)),
+               "pc_set_module_params")
+
+    def pc_fill_params(self, layer: int, module_ids: Sequence[int], arg_module: Sequence[int],
+                       arg_param: Sequence[int], arg_offsets: Sequence[int], K_arg_raw, V_arg, asm_K, asm_V, asm_pos,
+                       stream=None) -> None:
+        ids, am, ap, ao = _ints(module_ids), _ints(arg_module), _ints(arg_param), _ints(arg_offsets)
+        assert len(am) == len(ap) and len(ao) == len(am) + 1
+        _check(lib().pc_fill_params(self._ctx, layer, _np_ptr(ids), len(ids), len(am), _np_ptr(am), _np_ptr(ap),
+                                    _np_ptr(ao), _dev(K_arg_raw), _dev(V_arg), _dev(asm_K), _dev(asm_V), _dev(asm_pos),
+                                    int(asm_pos.shape[0]), _stream(stream)), "pc_fill_params")
 
     # -- queries
     def pc_module_info(self, layer: int, module_id: int) -> Tuple[int, int]:

@@ -23,6 +23,12 @@ struct ModuleEntry {
     int start_pos;
 };
 
+// A parameter of a module (Sec. 3.2.2): rows [offset, offset+len) of the module hold placeholder states.
+struct ParamSlot {
+    int offset;
+    int len;
+};
+
 // Optional per-kernel timing with HIP events recorded on the caller's stream right
 // around each kernel launch (off by default; see pc_profile_enable).
 enum ProfKind { kProfGather = 0, kProfAppend = 1, kProfAttn = 2, kProfCombine = 3, kProfRope = 4, kProfKinds = 5 };
@@ -50,6 +56,7 @@ struct pc_ctx {
     uint8_t *pool = nullptr;  // module pool (device)
     size_t pool_used = 0;
     std::vector<std::unordered_map<int, pc::ModuleEntry>> modules;  // per layer
+    std::unordered_map<int, std::vector<pc::ParamSlot>> params;     // per module id (schema level, all layers)
 
     float2 *rope_table = nullptr;  // device, [max_pos][head_dim/2] (cos, sin)
     float2 *rope_table_t = nullptr;  // the same values as [head_dim/2][max_pos]: coalesced when lanes hold consecutive positions
@@ -97,7 +104,11 @@ struct AppendSeg {
     int q_begin;
     int n;
     int dst_row;
+    int pos0;   // kPosFromArray: position IDs come from the q_pos array; kPosMaskRows: the rows only lose
+                // their position (no token there any more); >= 0: row r gets position pos0 + r
 };
+constexpr int kPosFromArray = -1;
+constexpr int kPosMaskRows = -2;
 constexpr int kMaxAppendSegs = 128;
 struct AppendArgs {
     int n_segs;

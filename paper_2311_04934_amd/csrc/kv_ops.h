@@ -129,9 +129,14 @@ __device__ __forceinline__ void append_row(const AppendSeg *seg, int n_segs, int
     if (s >= n_segs) return;
     const int src = seg[s].q_begin + r;
     const int dst = seg[s].dst_row + r;
+    const int mode = seg[s].pos0;
+    if (mode == kPosMaskRows) {   // an unused placeholder row: it stops being a token, its states stay
+        if (threadIdx.x == 0) asm_pos[dst] = PC_POS_NONE;
+        return;
+    }
     const int half = d >> 1;
     const int row_elems = n_kv_heads * d;
-    const int p = q_pos[src];
+    const int p = mode >= 0 ? mode + r : q_pos[src];
     const float2 *trow = table + (size_t)clamp_pos(p, max_pos) * half;
     const T *ks = k_new + (size_t)src * row_elems;
     const T *vs = v_new + (size_t)src * row_elems;

@@ -145,6 +145,7 @@ const char *pc_strerror(int status)
     case PC_E_POS_RANGE: return "position ID outside [0, max_pos)";
     case PC_E_UNSUPPORTED: return "unsupported head_dim / dtype";
     case PC_E_HIP: return "HIP runtime error";
+    case PC_E_PARAM: return "no such parameter, or argument longer than the parameter";
     case PC_E_SCHEMA: return "malformed schema";
     default: return "unknown status";
     }
@@ -380,6 +381,7 @@ int pc_append_kv_batched(pc_ctx *ctx, int layer, const void *K_new_raw, const vo
             a.seg[i].q_begin = q_offsets[b];
             a.seg[i].n = q_offsets[b + 1] - q_offsets[b];
             a.seg[i].dst_row = kv_offsets[b] + kv_lens[b];
+            a.seg[i].pos0 = kPosFromArray;
             a.total_rows += a.seg[i].n;
         }
         int rc = launch_append(ctx, a, K_new_raw, V_new, q_pos, asm_K, asm_V, asm_pos, as_stream(stream));
@@ -433,6 +435,7 @@ int pc_assemble_append_kv_batched(pc_ctx *ctx, int layer, const int *module_ids_
             a.app[b].q_begin = q_offsets[b];
             a.app[b].n = q_offsets[b + 1] - q_offsets[b];
             a.app[b].dst_row = kv_offsets[b] + rows[b];
+            a.app[b].pos0 = kPosFromArray;
         }
         rc = launch_gather_append(ctx, a, static_cast<uint8_t *>(out_K), static_cast<uint8_t *>(out_V), out_pos,
                                   K_new_raw, V_new, q_pos, as_stream(stream));
@@ -446,6 +449,73 @@ int pc_assemble_append_kv_batched(pc_ctx *ctx, int layer, const int *module_ids_
     if (rc == PC_OK && out_n_tokens)
         for (int b = 0; b < n_prompts; ++b) out_n_tokens[b] = rows[b] + (q_offsets[b + 1] - q_offsets[b]);
     return rc;
+}
+
+int pc_set_module_params(pc_ctx *ctx, int module_id, int n_params, const int *offsets, const int *lens)
+{
+    if (!ctx || n_params < 0 || (n_params > 0 && (!offsets || !lens))) return PC_E_BADARG;
+    std::vector<ParamSlot> slots(n_params);
+    long end = 0;
+    for (int j = 0; j < n_params; ++j) {
+        if (offsets[j] < end || lens[j] < 0) return PC_E_BADARG;   // sorted, disjoint, non-negative
+        slots[j].offset = offsets[j];
+        slots[j].len = lens[j];
+        end = (long)offsets[j] + lens[j];
+        if (end > ctx->cfg.max_pos) return PC_E_BADARG;
+    }
+    if (n_params == 0) ctx->params.erase(module_id);
+    else ctx->params[module_id] = std::move(slots);
+    return PC_OK;
+}
+
+int pc_fill_params(pc_ctx *ctx, int layer, const int *module_ids, int n_modules, int n_args, const int *arg_module,
+                   const int *arg_param, const int *arg_offsets, const void *K_arg_raw, const void *V_arg, void *asm_K,
+                   void *asm_V, int32_t *asm_pos, int capacity_tokens, void *stream)
+{
+    if (!ctx || n_modules < 0 || n_args < 0 || capacity_tokens < 0) return PC_E_BADARG;
+    if (layer < 0 || layer >= ctx->cfg.n_layers) return PC_E_LAYER;
+    if (n_modules > 0 && !module_ids) return PC_E_BADARG;
+    if (n_args == 0) return PC_OK;
+    if (!arg_module || !arg_param || !arg_offsets || !asm_K || !asm_V || !asm_pos) return PC_E_BADARG;
+    // where each module's rows are in the packed buffer (the order pc_assemble_kv used)
+    const auto &table = ctx->modules[layer];
+    std::vector<int> row0(n_modules), len(n_modules), start(n_modules);
+    long rows = 0;
+    for (int i = 0; i < n_modules; ++i) {
+        auto it = table.find(module_ids[i]);
+        if (it == table.end()) return PC_E_UNKNOWN_MODULE;
+        row0[i] = (int)rows;
+        len[i] = it->second.n_tokens;
+        start[i] = it->second.start_pos;
+        rows += len[i];
+    }
+    if (rows > capacity_tokens) return PC_E_CAPACITY;
+    std::vector<AppendSeg> segs;
+    long total_arg_rows = 0;
+    for (int a = 0; a < n_args; ++a) {
+        const int mi = arg_module[a], n = arg_offsets[a + 1] - arg_offsets[a];
+        if (mi < 0 || mi >= n_modules || n < 0 || arg_offsets[a] < 0) return PC_E_BADARG;
+        auto ps = ctx->params.find(module_ids[mi]);
+        if (ps == ctx->params.end() || arg_param[a] < 0 || arg_param[a] >= (int)ps->second.size()) return PC_E_PARAM;
+        const ParamSlot slot = ps->second[arg_param[a]];
+        if ((long)slot.offset + slot.len > len[mi] || n > slot.len) return PC_E_PARAM;
+        if (n > 0) segs.push_back(AppendSeg{arg_offsets[a], n, row0[mi] + slot.offset, start[mi] + slot.offset});
+        if (slot.len > n) segs.push_back(AppendSeg{0, slot.len - n, row0[mi] + slot.offset + n, kPosMaskRows});
+        total_arg_rows += n;
+    }
+    if (total_arg_rows > 0 && (!K_arg_raw || !V_arg)) return PC_E_BADARG;
+    for (size_t base = 0; base < segs.size(); base += kMaxAppendSegs) {
+        AppendArgs a;
+        a.n_segs = (int)std::min<size_t>(kMaxAppendSegs, segs.size() - base);
+        a.total_rows = 0;
+        for (int i = 0; i < a.n_segs; ++i) {
+            a.seg[i] = segs[base + i];
+            a.total_rows += a.seg[i].n;
+        }
+        int rc = launch_append(ctx, a, K_arg_raw, V_arg, nullptr, asm_K, asm_V, asm_pos, as_stream(stream));
+        if (rc != PC_OK) return rc;
+    }
+    return PC_OK;
 }
 
 int pc_append_kv(pc_ctx *ctx, int layer, const void *K_new_raw, const void *V_new, const int32_t *q_pos, int n_q,

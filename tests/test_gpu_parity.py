@@ -355,6 +355,112 @@ def test_fused_assemble_append_capacity_error_touches_nothing():
     r.close()
 
 
+# ------------------------------------------------------------------ parameterised modules (Sec. 3.2.2, Sec. 3.3)
+def _param_setup(dtype):
+    hq, hkv, d = (8, 2, 128) if dtype == "bf16" else (4, 2, 64)
+    w = W.custom("params_" + dtype, dtype, hq, hkv, d, [300, 64, 90], None, [W.Prompt([0, 2], 40)], max_pos=1024)
+    c = build_case(w, 0)
+    slots = {0: ([10, 200], [16, 8]), 2: ([0], [5])}              # module id -> (offsets, lens)
+    # (index into the prompt's module list, parameter index, argument length): full, short, empty
+    args = [(0, 0, 16), (0, 1, 3), (1, 0, 0)]
+    g = torch.Generator().manual_seed(777)
+    n_arg_rows = sum(a[2] for a in args)
+    Ka = torch.randn((n_arg_rows, hkv, d), generator=g).to(w.torch_dtype)
+    Va = torch.randn((n_arg_rows, hkv, d), generator=g).to(w.torch_dtype)
+    return w, c, slots, args, Ka, Va
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_parameter_arguments_replace_placeholders(dtype):
+    w, c, slots, args, Ka, Va = _param_setup(dtype)
+    pcx = c.prompts[0]
+    r = GpuRunner(c)
+    dev = r.dev
+    for m, (offs, lens) in slots.items():
+        r.pc.pc_set_module_params(m, offs, lens)
+    n_mod = sum(w.sizes[m] for m in pcx.module_ids)
+    n_new = len(pcx.q_pos)
+    cap = n_mod + n_new
+    asm_K = torch.full((cap, w.n_kv_heads, w.head_dim), float("nan"), dtype=w.torch_dtype, device=dev)
+    asm_V = torch.full_like(asm_K, float("nan"))
+    asm_pos = torch.full((cap,), -7, dtype=torch.int32, device=dev)
+    assert r.pc.pc_assemble_kv(0, pcx.module_ids, asm_K, asm_V, asm_pos) == n_mod
+    before_K, before_V = asm_K.cpu().clone(), asm_V.cpu().clone()
+    arg_off = np.concatenate([[0], np.cumsum([a[2] for a in args])])
+    r.pc.pc_fill_params(0, pcx.module_ids, [a[0] for a in args], [a[1] for a in args], arg_off, Ka.to(dev), Va.to(dev),
+                        asm_K, asm_V, asm_pos)
+    q_pos = torch.from_numpy(pcx.q_pos).to(dev)
+    r.pc.pc_append_kv(0, pcx.K_new.to(dev), pcx.V_new.to(dev), q_pos, asm_K, asm_V, asm_pos, n_mod)
+    out = torch.full((n_new, w.n_q_heads, w.head_dim), float("nan"), dtype=w.torch_dtype, device=dev)
+    r.pc.pc_prefill_attn(0, pcx.Q.to(dev), q_pos, asm_K, asm_V, asm_pos, cap, out)
+    torch.cuda.synchronize()
+    gK, gV, gP, gO = asm_K.cpu(), asm_V.cpu(), asm_pos.cpu().numpy(), out.cpu()
+    r.close()
+
+    # ---- the oracle's version of the same prompt
+    K, V, P = oracle_full_kv(c, 0)
+    row0 = np.concatenate([[0], np.cumsum([w.sizes[m] for m in pcx.module_ids])])
+    touched = np.zeros(cap, dtype=bool)
+    for (mi, pj, n), o0 in zip(args, arg_off[:-1]):
+        offs, lens = slots[pcx.module_ids[mi]]
+        r0 = int(row0[mi]) + offs[pj]
+        K, V, P = oracle.fill_param(K, V, P, r0, lens[pj], to_f64(Ka[o0:o0 + n]), to_f64(Va[o0:o0 + n]), w.rope_base)
+        touched[r0:r0 + n] = True
+        # values of the argument are copied bit for bit
+        assert np.array_equal(as_words(gV[r0:r0 + n]), as_words(Va[o0:o0 + n]))
+    assert np.array_equal(gP, P), "position IDs (including the rows that lost theirs) differ"
+    assert int(np.sum(gP == pcb.PC_POS_NONE)) == 5 + 5
+    # rows that no argument token landed on keep their bytes (placeholders left behind included)
+    keep = ~touched
+    keep[n_mod:] = False
+    assert np.array_equal(as_words(gK[keep]), as_words(before_K[keep]))
+    assert np.array_equal(as_words(gV[keep]), as_words(before_V[keep]))
+    # rotated argument keys: one rounding away from the fp64 rotation
+    ulp = 2.0 ** -8 if dtype == "bf16" else 2.0 ** -22
+    kg, kr = to_f64(gK[touched]), K[touched]
+    assert np.all(np.abs(kg - kr) <= ulp * np.maximum(np.abs(kr), 1.0) + 1e-6)
+    # attention over the prompt with its arguments
+    ref = oracle.attn(to_f64(pcx.Q), pcx.q_pos, K, V, P, w.rope_base)
+    err, rel = attn_errors(gO, ref)
+    print(f"[params {dtype}] max abs err {err:.3e} rel L2 {rel:.3e}", flush=True)
+    assert not torch.isnan(gO).any()
+    assert err <= TOL_ABS[dtype] and rel <= TOL_REL[dtype]
+
+
+def test_parameter_error_paths_touch_nothing():
+    w, c, slots, args, Ka, Va = _param_setup("bf16")
+    pcx = c.prompts[0]
+    r = GpuRunner(c)
+    dev = r.dev
+    cap = sum(w.sizes[m] for m in pcx.module_ids)
+    asm_K = torch.full((cap, w.n_kv_heads, w.head_dim), 3.0, dtype=w.torch_dtype, device=dev)
+    asm_V = torch.full_like(asm_K, 3.0)
+    asm_pos = torch.full((cap,), -7, dtype=torch.int32, device=dev)
+    ka, va = Ka.to(dev), Va.to(dev)
+
+    def status(fn):
+        try:
+            fn()
+            return 0
+        except pcb.PcError as e:
+            return e.status
+
+    fill = lambda am, ap, ao, ids=pcx.module_ids: r.pc.pc_fill_params(0, ids, am, ap, ao, ka, va, asm_K, asm_V, asm_pos)
+    assert status(lambda: fill([0], [0], [0, 4])) == -12                       # no parameters registered yet
+    r.pc.pc_set_module_params(0, [10, 200], [16, 8])
+    assert status(lambda: fill([0], [2], [0, 4])) == -12                       # parameter index out of range
+    assert status(lambda: fill([0], [1], [0, 9])) == -12                       # 9 tokens into a parameter of 8
+    assert status(lambda: fill([2], [0], [0, 1])) == -1                        # module index outside the list
+    assert status(lambda: fill([0], [0], [0, 1], ids=[0, 99])) == -3           # unknown module in the list
+    assert status(lambda: r.pc.pc_set_module_params(0, [10, 20], [16, 8])) == -1   # overlapping parameters
+    r.pc.pc_set_module_params(2, [80], [20])                                   # 80 + 20 > 90 rows of module 2
+    assert status(lambda: fill([1], [0], [0, 1])) == -12
+    torch.cuda.synchronize()
+    assert torch.all(asm_K == 3.0) and torch.all(asm_V == 3.0) and torch.all(asm_pos == -7)
+    assert status(lambda: fill([0], [1], [0, 8])) == 0                         # and a valid call still works
+    r.close()
+
+
 # ------------------------------------------------------------------ the benchmark's configurations at full size
 @pytest.mark.parametrize("layer", [0, 31])
 def test_config2_llama7b_full_size_sampled(layer):
