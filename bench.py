@@ -5,7 +5,9 @@ A step is one pass of the whole path over all layers of one synthetic workload:
 for every layer, assemble the prompt's KV from the module pool and append the
 uncached tokens' rotated K and V (one launch: pc_assemble_append_kv_batched; with
 --separate-launches: pc_assemble_kv_batched then pc_append_kv_batched) and run the
-uncached tokens' attention over the result (pc_prefill_attn_batched).  Inputs are resident in HBM
+uncached tokens' attention over the result (pc_prefill_attn_batched).  With --modules-in-place the
+copy is skipped: only the uncached tokens' rows are written (to a tail buffer) and attention reads
+the modules where the pool holds them (pc_prefill_attn_shared_batched).  Inputs are resident in HBM
 before the timed region starts; every layer has its own buffers so that the
 working set (pool + assembled KV, > 2 GB) cannot be served from cache.
 
@@ -91,6 +93,9 @@ def main() -> int:
     ap.add_argument("--no-full-prefill", action="store_true")
     ap.add_argument("--separate-launches", action="store_true",
                     help="assemble and append with two calls (two launches) instead of the fused one")
+    ap.add_argument("--modules-in-place", action="store_true",
+                    help="no packed copy: append the uncached tokens' rows to a tail buffer and let attention read the "
+                         "modules from the pool (pc_prefill_attn_shared_batched)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -170,8 +175,30 @@ def main() -> int:
     f_asm, f_app, f_att = lib.pc_assemble_kv_batched, lib.pc_append_kv_batched, lib.pc_prefill_attn_batched
     f_fus = lib.pc_assemble_append_kv_batched
     fused = not args.separate_launches
+    in_place = args.modules_in_place
+    if in_place:
+        # no packed copy: the uncached tokens' rows go to a tail buffer laid out like Q, attention reads
+        # the modules from the pool through a row-range table
+        zeros_c = np.zeros(B, dtype=np.intc)
+        tail_K = [torch.empty((total_q, w.n_kv_heads, w.head_dim), dtype=w.torch_dtype, device=dev) for _ in range(L)]
+        tail_V = [torch.empty_like(t) for t in tail_K]
+        tail_pos = torch.empty((total_q,), dtype=torch.int32, device=dev)
+        f_shr = lib.pc_prefill_attn_shared_batched
+        calls_ip = []
+        for layer in range(L):
+            a_tail = (ctx, layer, P(Kn[layer]), P(Vn[layer]), P(q_pos), hp(q_off_c), B, P(tail_K[layer]), P(tail_V[layer]),
+                      P(tail_pos), hp(q_off_c), hp(zeros_c), stream)
+            a_shr = (ctx, layer, P(Q[layer]), P(q_pos), hp(q_off_c), B, hp(ids_flat), hp(mod_offs), P(tail_K[layer]),
+                     P(tail_V[layer]), P(out[layer]), stream)
+            calls_ip.append((a_tail, a_shr))
 
     def step():
+        if in_place:
+            for a_tail, a_shr in calls_ip:
+                rc = f_app(*a_tail) or f_shr(*a_shr)
+                if rc:
+                    raise pcb.PcError(rc, "bench step (modules in place)")
+            return
         for a_asm, a_app, a_att, a_fus in calls:
             rc = (f_fus(*a_fus) if fused else (f_asm(*a_asm) or f_app(*a_app))) or f_att(*a_att)
             if rc:
@@ -213,7 +240,9 @@ def main() -> int:
     # ---------------- algorithmic work per layer
     flops_layer = attn_flops(w, n_mod, n_new)
     gather_bytes_layer = sum(n_mod) * (2 * 2 * w.row_bytes + 4)       # K and V, read + write, + int32 position
-    if fused:   # the same launch also reads and writes the uncached tokens' rows (and reads/writes their position IDs)
+    if in_place:   # only the uncached tokens' rows move: read raw, written rotated, + position IDs
+        gather_bytes_layer = sum(n_new) * (2 * 2 * w.row_bytes + 8)
+    elif fused:   # the same launch also reads and writes the uncached tokens' rows (and reads/writes their position IDs)
         gather_bytes_layer += sum(n_new) * (2 * 2 * w.row_bytes + 8)
     attn_tflops_step = flops_layer * L / (ms_per_step * 1e-3) / 1e12
 
@@ -226,7 +255,7 @@ def main() -> int:
         "ms_per_step_with_event_records": round(ms_per_step_events, 4) if ms_per_step_events else None,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": w.name, "layers": L, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
+        "config": {"workload": w.name, "kv_path": "modules read in place" if in_place else "packed copy", "layers": L, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
                    "head_dim": w.head_dim, "prompts": B, "module_tokens": n_mod if B <= 4 else [n_mod[0], "..."],
                    "uncached_tokens": n_new[0], "attn_launch": {"kv_splits": launch[0], "workgroups": launch[1],
                                                               "waves_per_wg": launch[2]}},
@@ -235,7 +264,7 @@ def main() -> int:
     }
     if kern.get("attn", {}).get("avg_us"):
         a_us = kern["attn"]["avg_us"]
-        g_us = kern["gather"]["avg_us"]
+        g_us = kern["append" if in_place else "gather"]["avg_us"]
         attn_tf = flops_layer / (a_us * 1e-6) / 1e12
         gat_gbs = gather_bytes_layer / (g_us * 1e-6) / 1e9
         result["kernels_us"] = {k: (round(v["avg_us"], 2) if v["avg_us"] else None) for k, v in kern.items()}
@@ -245,13 +274,13 @@ def main() -> int:
         result["roofline"] = {"kernel": "attn_bf16_dma_kernel<1,8>" if (w.head_dim == 128 and launch[2] == 8 and launch[0] >= 1 and w.n_q_heads // w.n_kv_heads * ((n_new[0] + 31) // 32) >= 8) else "attn_bf16_kernel", "bound": "mfma", "achieved": round(attn_tf, 1),
                               "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                               "frac": round(attn_tf / MFMA_BF16_PEAK_TFLOPS, 4),
-                              "traffic": MEASURED_TRAFFIC.get((w.name, L if L == 32 else 32), {}).get("attn")}
-        result["roofline_assemble"] = {"kernel": "gather_append_kernel" if fused else "gather_kv_kernel", "bound": "hbm", "achieved": round(gat_gbs, 1),
+                              "traffic": None if in_place else MEASURED_TRAFFIC.get((w.name, 32), {}).get("attn")}
+        result["roofline_assemble"] = {"kernel": "append_kernel" if in_place else ("gather_append_kernel" if fused else "gather_kv_kernel"), "bound": "hbm", "achieved": round(gat_gbs, 1),
                                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gat_gbs / HBM_PEAK_GBS, 4),
-                                       "traffic": MEASURED_TRAFFIC.get((w.name, 32), {}).get("gather")}
+                                       "traffic": None if in_place else MEASURED_TRAFFIC.get((w.name, 32), {}).get("gather")}
 
     # ---------------- full prefill of the same prompt with the same kernel (ordinary causal mask), one layer
-    if not args.no_full_prefill and B == 1:
+    if not args.no_full_prefill and B == 1 and not in_place:
         N = kv_len[0]
         g = torch.Generator().manual_seed(99)
         Qf = torch.randn((N, w.n_q_heads, w.head_dim), generator=g).to(w.torch_dtype).to(dev)

@@ -267,6 +267,28 @@ int pc_prefill_attn_batched(pc_ctx *ctx, int layer, const void *Q_new, const int
                             const int32_t *asm_pos, const int *kv_offsets, const int *kv_lens,
                             void *out, void *stream);
 
+/*
+ * Sec. 3.4 (sharing modules between the prompts of a batch instead of copying them) and
+ * Sec. 3.3: attention of every prompt's uncached tokens over its imported modules READ IN
+ * PLACE from the module pool, followed by the uncached tokens' own rows.  No packed KV
+ * buffer is assembled; a module imported by many prompts is read from its one copy.
+ * The result equals pc_assemble_append_kv_batched + pc_prefill_attn_batched.
+ *   module_ids_flat, mod_offsets  host, as in pc_assemble_kv_batched: prompt b imports
+ *                       module_ids_flat[mod_offsets[b] .. mod_offsets[b+1]-1], in this order;
+ *                       their position ranges must not overlap (PC_E_OVERLAP).
+ *   Q_new, q_pos, q_offsets, out  as in pc_prefill_attn_batched.
+ *   K_tail, V_tail      device [total_q, n_kv_heads, head_dim], 16-byte aligned: the uncached
+ *                       tokens' keys ALREADY ROTATED to q_pos, and values, row q_offsets[b]+i
+ *                       for prompt b's token i (what pc_append_kv_batched writes into an
+ *                       empty buffer with kv_offsets = q_offsets and kv_lens = 0).
+ * bf16 contexts with head_dim 128 only (PC_E_UNSUPPORTED otherwise), at most 63 modules per
+ * prompt.  Inputs are read, never written; ownership stays with the caller.
+ */
+int pc_prefill_attn_shared_batched(pc_ctx *ctx, int layer, const void *Q_new, const int32_t *q_pos,
+                                   const int *q_offsets, int n_prompts, const int *module_ids_flat,
+                                   const int *mod_offsets, const void *K_tail, const void *V_tail,
+                                   void *out, void *stream);
+
 /* ----------------------------------------------- host-side integer helpers */
 
 /*

@@ -21,7 +21,7 @@ PC_F32, PC_BF16 = 0, 1
 EXPORTS = [
     "pc_create", "pc_destroy", "pc_strerror", "pc_store_module", "pc_assemble_kv", "pc_prefill_attn",
     "pc_rope", "pc_append_kv", "pc_assemble_kv_batched", "pc_append_kv_batched", "pc_assemble_append_kv_batched",
-    "pc_prefill_attn_batched",
+    "pc_prefill_attn_batched", "pc_prefill_attn_shared_batched",
     "pc_schema_layout", "pc_uncached_positions", "pc_check_selection", "pc_bytes_per_token",
     "pc_module_info", "pc_pool_usage", "pc_last_attn_launch", "pc_profile_enable", "pc_profile_read",
     "pc_profile_read_each", "pc_set_module_params", "pc_fill_params",
@@ -70,6 +70,7 @@ def lib() -> ctypes.CDLL:
     L.pc_append_kv_batched.argtypes = [vp, i, vp, vp, vp, vp, i, vp, vp, vp, vp, vp, vp]
     L.pc_assemble_append_kv_batched.argtypes = [vp, i, vp, vp, i, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     L.pc_prefill_attn_batched.argtypes = [vp, i, vp, vp, vp, i, vp, vp, vp, vp, vp, vp, vp]
+    L.pc_prefill_attn_shared_batched.argtypes = [vp, i, vp, vp, vp, i, vp, vp, vp, vp, vp, vp]
     L.pc_set_module_params.argtypes = [vp, i, i, vp, vp]
     L.pc_fill_params.argtypes = [vp, i, vp, i, i, vp, vp, vp, vp, vp, vp, vp, vp, i, vp]
     L.pc_schema_layout.argtypes = [i, vp, vp, vp]
@@ -262,6 +263,17 @@ class PromptCache:
         _check(lib().pc_prefill_attn_batched(self._ctx, layer, _dev(Q_new), _dev(q_pos), _np_ptr(qo), B, _dev(asm_K),
                                              _dev(asm_V), _dev(asm_pos), _np_ptr(kvo), _np_ptr(kvl), _dev(out),
                                              _stream(stream)), "pc_prefill_attn_batched")
+
+    def pc_prefill_attn_shared_batched(self, layer: int, Q_new, q_pos, q_offsets: Sequence[int],
+                                       module_ids: Sequence[Sequence[int]], K_tail, V_tail, out, stream=None) -> None:
+        qo = _ints(q_offsets)
+        flat = _ints([m for ids in module_ids for m in ids])
+        offs = _ints(np.concatenate([[0], np.cumsum([len(ids) for ids in module_ids])]))
+        B = len(module_ids)
+        assert len(qo) == B + 1
+        _check(lib().pc_prefill_attn_shared_batched(self._ctx, layer, _dev(Q_new), _dev(q_pos), _np_ptr(qo), B,
+                                                    _np_ptr(flat), _np_ptr(offs), _dev(K_tail), _dev(V_tail), _dev(out),
+                                                    _stream(stream)), "pc_prefill_attn_shared_batched")
 
     def pc_set_module_params(self, module_id: int, offsets: Sequence[int], lens: Sequence[int]) -> None:
         o, l = _ints(offsets), _ints(lens)

@@ -79,8 +79,26 @@ __device__ __forceinline__ float sum_across_halves(float x)
 
 }  // namespace attn
 
-// DMA-staged kernel (attn_bf16_wide.hip): D = 128, 8 row tiles per workgroup, 1 or 2 row tiles per wave
-int launch_attn_bf16_wide(pc_ctx *ctx, attn::AttnParams &p, int n_blocks, hipStream_t stream);
+// A prompt's KV as a list of row ranges read in place (module blocks of the pool, then the uncached
+// tokens' own rows) instead of one packed buffer.  Rows of segment s are the prompt's rows
+// [first_row, first_row of s+1); all three pointers address the segment's row 0.
+struct KvSeg {
+    const uint8_t *k;
+    const uint8_t *v;
+    const int32_t *pos;
+    int first_row;
+    int pad_;
+};
+constexpr int kMaxKvSegs = 64;
+struct KvSegTable {
+    int seg_begin[kMaxAttnSeqs + 1];   // prompt i owns seg[seg_begin[i] .. seg_begin[i+1])
+    KvSeg seg[kMaxKvSegs];
+};
+
+// DMA-staged kernel (attn_bf16_wide.hip): D = 128, 8 row tiles per workgroup, 1 row tile per wave.
+// tab != nullptr: K/V and positions are read through the segment table (p.k, p.v, p.kv_pos unused).
+int launch_attn_bf16_wide(pc_ctx *ctx, attn::AttnParams &p, int n_blocks, hipStream_t stream,
+                          const KvSegTable *tab = nullptr);
 constexpr int kWideRowTilesPerWg = 8;
 constexpr int kWideMinRowTiles = 4;     // with fewer row tiles per kv head the register-staged kernel is used
 

@@ -460,7 +460,7 @@ int launch_variant(pc_ctx *ctx, AttnParams &p, int n_blocks, hipStream_t stream)
 }  // namespace
 
 int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const int32_t *q_pos, const void *k,
-                     const void *v, const int32_t *kv_pos, void *out, hipStream_t stream)
+                     const void *v, const int32_t *kv_pos, void *out, hipStream_t stream, const KvSegTable *tab)
 {
     const int D = ctx->cfg.head_dim, Hq = ctx->cfg.n_q_heads, Hkv = ctx->cfg.n_kv_heads, G = Hq / Hkv;
     if (D != 64 && D != 128) return PC_E_UNSUPPORTED;
@@ -480,7 +480,9 @@ int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const i
     long max_kv = 0;
     for (int s = 0; s < batch.n_seqs; ++s) max_kv = batch.seq[s].n_kv > max_kv ? batch.seq[s].n_kv : max_kv;
     const bool fits_u32 = max_kv * (long)Hkv * D * 2 < (1L << 32);   // the wide kernel uses 32-bit row offsets
-    bool wide = D == 128 && max_row_tiles >= kWideMinRowTiles && fits_u32;
+    // a range table is read by the DMA-staged kernel only (32-bit offsets there are per range, checked by the caller)
+    if (tab && D != 128) return PC_E_UNSUPPORTED;
+    bool wide = D == 128 && (tab || (max_row_tiles >= kWideMinRowTiles && fits_u32));
     const int NW = wide ? 4 : (max_row_tiles <= 4 ? 4 : 8);
     const int tiles_per_wg = wide ? kWideRowTilesPerWg : NW;
     const int rb_max = (max_row_tiles + tiles_per_wg - 1) / tiles_per_wg;
@@ -527,7 +529,7 @@ int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const i
     int rc;
     int waves_used = NW;
     if (wide) {
-        rc = launch_attn_bf16_wide(ctx, p, n_blocks, stream);
+        rc = launch_attn_bf16_wide(ctx, p, n_blocks, stream, tab);
         waves_used = 8;
     } else if (D == 128) {
         rc = NW == 8 ? launch_variant<128, 8>(ctx, p, n_blocks, stream) : launch_variant<128, 4>(ctx, p, n_blocks, stream);

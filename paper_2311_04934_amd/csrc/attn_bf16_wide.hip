@@ -27,6 +27,8 @@
 // instantiated (two tiles per wave need all 512 registers, which leaves one wave per SIMD, and
 // measured slower).
 
+#include <type_traits>
+
 #include "attn_bf16.h"
 
 namespace pc {
@@ -80,8 +82,14 @@ struct QTile {        // one 32-query row tile of a wave
     int qpos;         // its position ID (+inf when the lane has no query)
 };
 
-template <int NQT, int NW>
-__global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams p)
+struct NoSegTable {
+    int unused;
+};
+
+// PAGED: the keys come from a list of row ranges (see KvSegTable) instead of one packed buffer.
+template <int NQT, int NW, bool PAGED>
+__global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams p,
+                                                                const std::conditional_t<PAGED, KvSegTable, NoSegTable> tab)
 {
     static_assert(NQT * NW == kWideRowTilesPerWg, "a workgroup covers 8 row tiles");
     constexpr int GRP_PER_WAVE = 16 / NW;                // 1-KiB (4-row) groups of a tile each wave copies, per tensor
@@ -133,10 +141,73 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
     }
 
     const size_t kv_row_stride = (size_t)p.Hkv * D;  // elements
-    const uint16_t *k_base = p.k + (size_t)seq.kv_begin * kv_row_stride + (size_t)kvh * D;
-    const uint16_t *v_base = p.v + (size_t)seq.kv_begin * kv_row_stride + (size_t)kvh * D;
-    const int32_t *pos_base = p.kv_pos + seq.kv_begin;
+    const uint16_t *k_base = PAGED ? nullptr : p.k + (size_t)seq.kv_begin * kv_row_stride + (size_t)kvh * D;
+    const uint16_t *v_base = PAGED ? nullptr : p.v + (size_t)seq.kv_begin * kv_row_stride + (size_t)kvh * D;
+    const int32_t *pos_base = PAGED ? nullptr : p.kv_pos + seq.kv_begin;
     const int last_row = k_end - 1;
+
+    // PAGED: which row range holds a given row of the prompt.  The range table stays in the kernel
+    // arguments and is only ever indexed with wave-uniform values, i.e. through the scalar cache: a
+    // vector-memory load between the asynchronous copies would have to wait for all of them.  Tiles
+    // are requested in increasing order, so the wave keeps the range of the tile's first row in scalar
+    // registers (seg_cur, its pointers, its first row and the next range's first row): a tile inside
+    // one range, the usual case, costs the same address arithmetic as the packed buffer.  Only a tile
+    // that straddles a boundary walks the ranges it touches and selects per lane.
+    int seg_cur = 0, seg_lo = 0, n_seg = 0;
+    uint32_t cur_first = 0, next_first = 0xffffffffu;
+    uint64_t cur_k = 0, cur_v = 0, cur_p = 0;
+    auto seg_at = [&](int e) -> KvSeg {   // e uniform, < n_seg
+        if constexpr (PAGED) return tab.seg[__builtin_amdgcn_readfirstlane(seg_lo + e)];
+        else return KvSeg{};
+    };
+    auto uniform64 = [](uint64_t x) -> uint64_t {   // tells the compiler that the value is the same in every lane
+        const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)x), hi = __builtin_amdgcn_readfirstlane((uint32_t)(x >> 32));
+        return ((uint64_t)hi << 32) | lo;
+    };
+    auto load_seg = [&](int e) {
+        const KvSeg sg = seg_at(e);
+        cur_k = uniform64(reinterpret_cast<uint64_t>(sg.k));
+        cur_v = uniform64(reinterpret_cast<uint64_t>(sg.v));
+        cur_p = uniform64(reinterpret_cast<uint64_t>(sg.pos));
+        cur_first = __builtin_amdgcn_readfirstlane((uint32_t)sg.first_row);
+        next_first = e + 1 < n_seg ? __builtin_amdgcn_readfirstlane((uint32_t)seg_at(e + 1).first_row) : 0xffffffffu;
+    };
+    if constexpr (PAGED) {
+        seg_lo = tab.seg_begin[seq_i];
+        n_seg = tab.seg_begin[seq_i + 1] - seg_lo;
+        load_seg(0);   // a prompt with query rows has at least the range of its own tokens
+    }
+    auto advance_to = [&](uint32_t row) {   // uniform row: first row the coming requests can touch
+        if constexpr (PAGED)
+            while (next_first <= row) {
+                seg_cur = __builtin_amdgcn_readfirstlane(seg_cur + 1);
+                load_seg(seg_cur);
+            }
+    };
+    // row (per lane, >= the row of the last advance_to, < row_hi) -> the addresses of that row's K, V and position
+    auto locate = [&](uint32_t row, uint32_t row_hi, const uint8_t *&kp, const uint8_t *&vp, const int32_t *&pp) {
+        if constexpr (PAGED) {
+            const uint32_t head_off = (uint32_t)(kvh * D * 2), stride = (uint32_t)(kv_row_stride * 2u);
+            uint64_t bk = cur_k, bv = cur_v, bp = cur_p;
+            uint32_t first = cur_first;
+            if (next_first < row_hi) {   // uniform: the tile runs into later ranges
+                for (int sx = seg_cur + 1; sx < n_seg; ++sx) {
+                    const KvSeg sg = seg_at(sx);
+                    if ((uint32_t)sg.first_row >= row_hi) break;
+                    const bool in = row >= (uint32_t)sg.first_row;
+                    bk = in ? reinterpret_cast<uint64_t>(sg.k) : bk;
+                    bv = in ? reinterpret_cast<uint64_t>(sg.v) : bv;
+                    bp = in ? reinterpret_cast<uint64_t>(sg.pos) : bp;
+                    first = in ? (uint32_t)sg.first_row : first;
+                }
+            }
+            const uint32_t local = row - first;
+            const uint32_t off = local * stride + head_off;   // < 4 GiB per range
+            kp = reinterpret_cast<const uint8_t *>(bk) + off;
+            vp = reinterpret_cast<const uint8_t *>(bv) + off;
+            pp = reinterpret_cast<const int32_t *>(bp) + local;
+        }
+    };
 
     // ---- global -> LDS, asynchronously.  One wave instruction fills 1 KiB = 4 rows; LDS slot
     // (row r, 16-byte chunk c) receives global chunk c ^ swz(r).  Rows past the split's end are
@@ -160,17 +231,34 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
         const uint32_t row0 = (uint32_t)(k_begin + t * KT);
         const uint32_t dst0 = __builtin_amdgcn_readfirstlane(lds_base + buf * TILE_BYTES + wave * 1024);
         const uint32_t dstv = __builtin_amdgcn_readfirstlane(lds_base + LDS_V + (t % NVRAW) * TILE_BYTES + wave * 1024);
+        const uint32_t row_hi = PAGED ? (row0 + KT < (uint32_t)k_end ? row0 + KT : (uint32_t)k_end) : 0u;
+        advance_to(row0 < (uint32_t)last_row ? row0 : (uint32_t)last_row);
 #pragma unroll
         for (int j = 0; j < GRP_PER_WAVE; ++j) {
             uint32_t grow = row0 + dma_r[j];
             grow = grow < (uint32_t)last_row ? grow : (uint32_t)last_row;
-            const uint32_t off = grow * row_bytes_g;               // < 4 GiB, checked by the launcher
-            dma_b128(k_bytes + off + dma_ck[j], dst0 + LDS_K + j * NW * 1024);
-            dma_b128(v_bytes + off + dma_cv[j], dstv + j * NW * 1024);
+            if constexpr (PAGED) {
+                const uint8_t *kp, *vp;
+                const int32_t *pp;
+                locate(grow, row_hi, kp, vp, pp);
+                dma_b128(kp + dma_ck[j], dst0 + LDS_K + j * NW * 1024);
+                dma_b128(vp + dma_cv[j], dstv + j * NW * 1024);
+            } else {
+                const uint32_t off = grow * row_bytes_g;               // < 4 GiB, checked by the launcher
+                dma_b128(k_bytes + off + dma_ck[j], dst0 + LDS_K + j * NW * 1024);
+                dma_b128(v_bytes + off + dma_cv[j], dstv + j * NW * 1024);
+            }
         }
         uint32_t prow = row0 + (uint32_t)lane;
         prow = prow < (uint32_t)last_row ? prow : (uint32_t)last_row;
-        dma_b32(pos_base + prow, __builtin_amdgcn_readfirstlane(lds_base + LDS_POS + buf * KT * 4));
+        if constexpr (PAGED) {
+            const uint8_t *kp, *vp;
+            const int32_t *pp;
+            locate(prow, row_hi, kp, vp, pp);
+            dma_b32(pp, __builtin_amdgcn_readfirstlane(lds_base + LDS_POS + buf * KT * 4));
+        } else {
+            dma_b32(pos_base + prow, __builtin_amdgcn_readfirstlane(lds_base + LDS_POS + buf * KT * 4));
+        }
     };
 
     // ---- prologue.  Order matters for latency.  The position IDs come first (the rotation-table
@@ -326,18 +414,36 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
     auto issue_piece = [&](int t, int k) {
         const int buf = t & (NBUF - 1);
         const uint32_t row0 = (uint32_t)(k_begin + t * KT);
+        const uint32_t row_hi = PAGED ? (row0 + KT < (uint32_t)k_end ? row0 + KT : (uint32_t)k_end) : 0u;
         if (k < 2 * GRP_PER_WAVE) {
             const int j = k >> 1;
             const uint32_t dst0 = __builtin_amdgcn_readfirstlane(lds_base + buf * TILE_BYTES + wave * 1024 + j * NW * 1024);
             uint32_t grow = row0 + dma_r[j];
             grow = grow < (uint32_t)last_row ? grow : (uint32_t)last_row;
-            const uint32_t off = grow * row_bytes_g;               // < 4 GiB, checked by the launcher
-            if (k & 1) dma_b128(v_bytes + off + dma_cv[j], __builtin_amdgcn_readfirstlane(lds_base + LDS_V + (t % NVRAW) * TILE_BYTES + wave * 1024 + j * NW * 1024));
-            else dma_b128(k_bytes + off + dma_ck[j], dst0 + LDS_K);
+            const uint32_t dstv1 = __builtin_amdgcn_readfirstlane(lds_base + LDS_V + (t % NVRAW) * TILE_BYTES + wave * 1024 + j * NW * 1024);
+            if constexpr (PAGED) {
+                if (k == 0) advance_to(row0 < (uint32_t)last_row ? row0 : (uint32_t)last_row);
+                const uint8_t *kp, *vp;
+                const int32_t *pp;
+                locate(grow, row_hi, kp, vp, pp);
+                if (k & 1) dma_b128(vp + dma_cv[j], dstv1);
+                else dma_b128(kp + dma_ck[j], dst0 + LDS_K);
+            } else {
+                const uint32_t off = grow * row_bytes_g;               // < 4 GiB, checked by the launcher
+                if (k & 1) dma_b128(v_bytes + off + dma_cv[j], dstv1);
+                else dma_b128(k_bytes + off + dma_ck[j], dst0 + LDS_K);
+            }
         } else {
             uint32_t prow = row0 + (uint32_t)lane;
             prow = prow < (uint32_t)last_row ? prow : (uint32_t)last_row;
-            dma_b32(pos_base + prow, __builtin_amdgcn_readfirstlane(lds_base + LDS_POS + buf * KT * 4));
+            if constexpr (PAGED) {
+                const uint8_t *kp, *vp;
+                const int32_t *pp;
+                locate(prow, row_hi, kp, vp, pp);
+                dma_b32(pp, __builtin_amdgcn_readfirstlane(lds_base + LDS_POS + buf * KT * 4));
+            } else {
+                dma_b32(pos_base + prow, __builtin_amdgcn_readfirstlane(lds_base + LDS_POS + buf * KT * 4));
+            }
         }
     };
 
@@ -351,7 +457,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
     // between slots so that this order survives; the empty asm statements keep each value's
     // computation in its slot.
     auto step = [&](const bf16x8 (&pp)[NQT][2], const lds_u8 *kbase, f32x16 (&snext)[NQT], const f32x16 (&s)[NQT],
-                    bf16x8 (&pout)[NQT][2], const lds_u8 *vnext, bool do_dma, int dma_tile) {
+                    bf16x8 (&pout)[NQT][2], const lds_u8 *vnext, bool do_dma, int dma_tile, bool do_tr, int tr_tile) {
         bf16x8 kf[KB];
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) kf[kb] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const lds_u32x4 *>(kbase + koff[kb]));
@@ -450,9 +556,9 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
             // ---- refill vf for the next step once this step's P.V instructions have been issued
             if (i >= 2 * DB) read_v(vnext, i - 2 * DB);
             if (do_dma && i < DMA_PER_TILE) issue_piece(dma_tile, i);
-            // re-layout of the V tile that became visible at the last barrier (dma_tile - 2)
-            if (do_dma && i < FRAG_PER_WAVE) transpose_read(dma_tile - 2, i);
-            if (do_dma && i >= 4 && i < 4 + FRAG_PER_WAVE) transpose_write(dma_tile - 2, i - 4);
+            // re-layout of the V tile that became visible at the last barrier
+            if (do_tr && i < FRAG_PER_WAVE) transpose_read(tr_tile, i);
+            if (do_tr && i >= 4 && i < 4 + FRAG_PER_WAVE) transpose_write(tr_tile, i - 4);
             PC_FENCE();
         }
 #pragma unroll
@@ -532,6 +638,11 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
         // share of the copies and of the V re-layout, and the barriers; the matrix pipe of its SIMD is
         // left to the wave that has work
         const bool idle_wave = rb * kWideRowTilesPerWg + wave * NQT >= row_tiles;
+        // Per tile, ONE workgroup barrier at the top.  It makes visible what the iteration reads for the
+        // first time: the staged K, V and position IDs of tile t+1 (copies issued two iterations ago) and
+        // the V^T fragments of tile t (written during the previous iteration).  Everything an iteration
+        // overwrites was last read before that barrier: the copies of tile t+3 go into the K buffer of
+        // tile t-1 and the raw-V buffer of tile t, the V^T fragments of tile t+1 replace those of tile t-1.
         for (int t = 0; idle_wave && t < n_tiles; ++t) {
             PC_WAIT_VMCNT(DMA_PER_TILE);
             __syncthreads();
@@ -551,21 +662,22 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
             // K.Q of the next tile's first half (past the last tile: recomputed on this tile, result unused)
             const lds_u8 *k_nxt = lds + LDS_K + (has_next ? (t + 1) & (NBUF - 1) : buf) * TILE_BYTES;
 
-            if (mask_cur) apply_mask(sc[0], buf, 0, n_valid);
-            rescale();
-            // P.V of tile t-1's second half | K.Q of this tile's second half | softmax of its first half
-            step(pf[1], k_cur + 32 * ROW_BYTES, sc[1], sc[0], pf[0], v_cur, false, 0);
-
-            // make tile t+1 visible; its copies were issued two tiles ago, those of tile t+2 may stay in flight
+            // tile t+1 and the V^T fragments of tile t become visible; the copies of tile t+2 may stay in flight
             PC_WAIT_VMCNT(DMA_PER_TILE);
             __syncthreads();
             const bool mask_next = has_next ? tile_needs_mask(t + 1) : false;
 
+            if (mask_cur) apply_mask(sc[0], buf, 0, n_valid);
+            rescale();
+            // P.V of tile t-1's second half | K.Q of this tile's second half | softmax of its first half;
+            // the copies of tile t+3 are issued here
+            step(pf[1], k_cur + 32 * ROW_BYTES, sc[1], sc[0], pf[0], v_cur, true, t + 3, false, 0);
+
             if (mask_cur) apply_mask(sc[1], buf, 1, n_valid);
             rescale();
             // P.V of this tile's first half | K.Q of tile t+1's first half | softmax of this tile's second half;
-            // tile t+3 is copied into the buffer tile t-1 used: every wave is past it since the barrier
-            step(pf[0], k_nxt, sc[0], sc[1], pf[1], v_cur + 8 * 1024, true, t + 3);
+            // V of tile t+1 is brought into fragment order
+            step(pf[0], k_nxt, sc[0], sc[1], pf[1], v_cur + 8 * 1024, false, 0, true, t + 1);
             mask_cur = mask_next;
         }
         // drain: P.V of the very last sub-tile
@@ -600,12 +712,19 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
             }
     // (m, l) of the partial, one lane per query
     if (p.n_splits > 1 && hh == 0) {
+        // the row index is recomputed from an opaque copy of the lane's column: kept from the prologue it
+        // would occupy two registers across the whole main loop, which has none to spare
+        int col2 = lane & 31;
+        asm volatile("" : "+v"(col2));
 #pragma unroll
-        for (int x = 0; x < NQT; ++x)
-            if (qt[x].valid) {
-                const size_t out_row = (size_t)(seq.q_begin + qt[x].qi) * p.Hq + qt[x].head;
+        for (int x = 0; x < NQT; ++x) {
+            const int rt = __builtin_amdgcn_readfirstlane(rb * kWideRowTilesPerWg + wave * NQT + x);
+            const int qi2 = (rt % tiles_q) * RW + col2;
+            if (rt < row_tiles && qi2 < seq.n_q) {
+                const size_t out_row = (size_t)(seq.q_begin + qi2) * p.Hq + (kvh * p.G + rt / tiles_q);
                 p.part_ml[(size_t)split * p.total_q * p.Hq + out_row] = make_float2(m_run[x], l_tot[x]);
             }
+        }
     }
     __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): this wave's LDS writes have landed
     __builtin_amdgcn_wave_barrier();
@@ -637,25 +756,27 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
     }
 }
 
-template <int NQT, int NW>
-int launch_one(pc_ctx *ctx, AttnParams &p, int n_blocks, hipStream_t stream)
+template <int NQT, int NW, bool PAGED, typename Tab>
+int launch_one(pc_ctx *ctx, AttnParams &p, int n_blocks, hipStream_t stream, const Tab &tab)
 {
     static bool attr_set[16] = {false};
-    auto kern = attn_bf16_dma_kernel<NQT, NW>;
+    auto kern = attn_bf16_dma_kernel<NQT, NW, PAGED>;
     if (!attr_set[ctx->device & 15]) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 LDS_TOTAL) != hipSuccess)
             return PC_E_HIP;
         attr_set[ctx->device & 15] = true;
     }
-    return launch_kernel(ctx, kProfAttn, kern, dim3(n_blocks), dim3(NW * 64), LDS_TOTAL, stream, p);
+    return launch_kernel(ctx, kProfAttn, kern, dim3(n_blocks), dim3(NW * 64), LDS_TOTAL, stream, p,
+                         tab);
 }
 
 }  // namespace
 
-int launch_attn_bf16_wide(pc_ctx *ctx, attn::AttnParams &p, int n_blocks, hipStream_t stream)
+int launch_attn_bf16_wide(pc_ctx *ctx, attn::AttnParams &p, int n_blocks, hipStream_t stream, const KvSegTable *tab)
 {
-    return launch_one<1, 8>(ctx, p, n_blocks, stream);
+    if (tab) return launch_one<1, 8, true>(ctx, p, n_blocks, stream, *tab);
+    return launch_one<1, 8, false>(ctx, p, n_blocks, stream, NoSegTable{0});
 }
 
 }  // namespace pc

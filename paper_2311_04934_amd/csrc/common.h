@@ -59,6 +59,7 @@ struct pc_ctx {
     std::unordered_map<int, std::vector<pc::ParamSlot>> params;     // per module id (schema level, all layers)
 
     float2 *rope_table = nullptr;  // device, [max_pos][head_dim/2] (cos, sin)
+    int32_t *iota = nullptr;  // device, 0, 1, .. max_pos-1: position IDs of module rows read in place
     float2 *rope_table_t = nullptr;  // the same values as [head_dim/2][max_pos]: coalesced when lanes hold consecutive positions
 
     float *scratch = nullptr;  // device, split-KV partials
@@ -146,8 +147,9 @@ struct AttnBatch {
 int launch_attn_f32(pc_ctx *ctx, const AttnBatch &batch, const float *q, const int32_t *q_pos, const float *k,
                     const float *v, const int32_t *kv_pos, float *out, hipStream_t stream);
 
+struct KvSegTable;
 int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const int32_t *q_pos, const void *k,
-                     const void *v, const int32_t *kv_pos, void *out, hipStream_t stream);
+                     const void *v, const int32_t *kv_pos, void *out, hipStream_t stream, const KvSegTable *tab = nullptr);
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? PC_OK : PC_E_HIP; }
 

@@ -9,6 +9,7 @@
 #include <new>
 
 #include "common.h"
+#include "attn_bf16.h"
 
 using namespace pc;
 
@@ -194,6 +195,12 @@ int pc_create(const pc_config *cfg, pc_ctx **out_ctx)
                 for (int i = 0; i < half; ++i) host_t[(size_t)i * cfg->max_pos + p] = host[(size_t)p * half + i];
             ok = hipMemcpy(ctx->rope_table_t, host_t.data(), n_entries * sizeof(float2), hipMemcpyHostToDevice) == hipSuccess;
         }
+        if (ok) ok = hipMalloc(reinterpret_cast<void **>(&ctx->iota), (size_t)cfg->max_pos * sizeof(int32_t)) == hipSuccess;
+        if (ok) {
+            std::vector<int32_t> ids(cfg->max_pos);
+            for (int p = 0; p < cfg->max_pos; ++p) ids[p] = p;
+            ok = hipMemcpy(ctx->iota, ids.data(), ids.size() * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess;
+        }
     }
     if (!ok) {
         (void)hipGetLastError();
@@ -201,6 +208,7 @@ int pc_create(const pc_config *cfg, pc_ctx **out_ctx)
         if (ctx->scratch) (void)hipFree(ctx->scratch);
         if (ctx->rope_table) (void)hipFree(ctx->rope_table);
         if (ctx->rope_table_t) (void)hipFree(ctx->rope_table_t);
+        if (ctx->iota) (void)hipFree(ctx->iota);
         delete ctx;
         return PC_E_HIP;
     }
@@ -272,6 +280,7 @@ int pc_destroy(pc_ctx *ctx)
     if (ctx->scratch) (void)hipFree(ctx->scratch);
     if (ctx->rope_table) (void)hipFree(ctx->rope_table);
     if (ctx->rope_table_t) (void)hipFree(ctx->rope_table_t);
+    if (ctx->iota) (void)hipFree(ctx->iota);
     delete ctx;
     return PC_OK;
 }
@@ -558,6 +567,74 @@ int pc_prefill_attn_batched(pc_ctx *ctx, int layer, const void *Q_new, const int
             ab.seq[i].n_kv = kv_lens[b];
         }
         int rc = run_attn(ctx, ab, Q_new, q_pos, asm_K, asm_V, asm_pos, out, as_stream(stream));
+        if (rc != PC_OK) return rc;
+    }
+    return PC_OK;
+}
+
+int pc_prefill_attn_shared_batched(pc_ctx *ctx, int layer, const void *Q_new, const int32_t *q_pos, const int *q_offsets,
+                                   int n_prompts, const int *module_ids_flat, const int *mod_offsets, const void *K_tail,
+                                   const void *V_tail, void *out, void *stream)
+{
+    if (!ctx || n_prompts < 0 || !q_offsets || !mod_offsets) return PC_E_BADARG;
+    if (layer < 0 || layer >= ctx->cfg.n_layers) return PC_E_LAYER;
+    if (ctx->cfg.dtype != PC_BF16) return PC_E_UNSUPPORTED;
+    long total_q = 0;
+    for (int b = 0; b < n_prompts; ++b) {
+        const int n = q_offsets[b + 1] - q_offsets[b], nm = mod_offsets[b + 1] - mod_offsets[b];
+        if (n < 0 || nm < 0 || q_offsets[b] < 0 || (nm > 0 && !module_ids_flat)) return PC_E_BADARG;
+        total_q += n;
+    }
+    if (total_q == 0) return PC_OK;
+    if (!Q_new || !q_pos || !out || !K_tail || !V_tail || !aligned16(Q_new) || !aligned16(out) || !aligned16(K_tail) ||
+        !aligned16(V_tail))
+        return PC_E_BADARG;
+    const auto &table = ctx->modules[layer];
+    const uint8_t *kt = static_cast<const uint8_t *>(K_tail), *vt = static_cast<const uint8_t *>(V_tail);
+    // every prompt is checked before the first launch, so that an error leaves `out` untouched
+    for (int b = 0; b < n_prompts; ++b) {
+        const int nm = mod_offsets[b + 1] - mod_offsets[b], nq = q_offsets[b + 1] - q_offsets[b];
+        if (nm + 1 > kMaxKvSegs || (size_t)nq * ctx->row_bytes >= ((size_t)1 << 32)) return PC_E_UNSUPPORTED;
+        std::vector<int> starts(nm), lens(nm);
+        for (int i = 0; i < nm; ++i) {
+            auto it = table.find(module_ids_flat[mod_offsets[b] + i]);
+            if (it == table.end()) return PC_E_UNKNOWN_MODULE;
+            starts[i] = it->second.start_pos;
+            lens[i] = it->second.n_tokens;
+            if ((size_t)lens[i] * ctx->row_bytes >= ((size_t)1 << 32)) return PC_E_UNSUPPORTED;   // 32-bit offsets inside a range
+        }
+        int rc = check_ranges(nm, starts.data(), lens.data(), ctx->cfg.max_pos);
+        if (rc != PC_OK) return rc;
+    }
+    int b = 0;
+    while (b < n_prompts) {
+        // as many prompts per launch as the range table and the prompt table hold
+        AttnBatch ab;
+        KvSegTable tab;
+        ab.n_seqs = 0;
+        int n_seg = 0;
+        for (; b < n_prompts && ab.n_seqs < kMaxAttnSeqs; ++b) {
+            const int nm = mod_offsets[b + 1] - mod_offsets[b], nq = q_offsets[b + 1] - q_offsets[b];
+            if (n_seg + nm + 1 > kMaxKvSegs) break;
+            const int seg0 = n_seg;
+            int rows = 0;
+            for (int i = 0; i < nm; ++i) {
+                const ModuleEntry &m = table.find(module_ids_flat[mod_offsets[b] + i])->second;
+                if (m.n_tokens == 0) continue;
+                tab.seg[n_seg++] = KvSeg{ctx->pool + m.k_offset, ctx->pool + m.v_offset, ctx->iota + m.start_pos, rows, 0};
+                rows += m.n_tokens;
+            }
+            if (nq > 0) {   // the prompt's own tokens: rows q_offsets[b].. of the tail buffers, positions q_pos
+                tab.seg[n_seg++] = KvSeg{kt + (size_t)q_offsets[b] * ctx->row_bytes, vt + (size_t)q_offsets[b] * ctx->row_bytes,
+                                         q_pos + q_offsets[b], rows, 0};
+                rows += nq;
+            }
+            tab.seg_begin[ab.n_seqs] = seg0;
+            ab.seq[ab.n_seqs] = AttnSeq{q_offsets[b], nq, 0, rows};
+            ++ab.n_seqs;
+        }
+        tab.seg_begin[ab.n_seqs] = n_seg;
+        int rc = launch_attn_bf16(ctx, ab, Q_new, q_pos, nullptr, nullptr, nullptr, out, as_stream(stream), &tab);
         if (rc != PC_OK) return rc;
     }
     return PC_OK;

@@ -461,6 +461,174 @@ def test_parameter_error_paths_touch_nothing():
     r.close()
 
 
+# ------------------------------------------------------------------ modules read in place (no packed copy)
+def _shared_run(w, layer, q_sample):
+    """Attention over the module pool itself plus a tail buffer of the new tokens' rows, against the
+    oracle's attention over its own concatenated buffer (Sec. 3.4: one stored copy serves every prompt)."""
+    c = build_case(w, layer)
+    r = GpuRunner(c)
+    dev = r.dev
+    B = len(c.prompts)
+    n_new = [len(p.q_pos) for p in c.prompts]
+    q_off = np.concatenate([[0], np.cumsum(n_new)]).astype(np.int64)
+    total_q = int(q_off[-1])
+    Q = torch.cat([p.Q for p in c.prompts]).to(dev)
+    Kn = torch.cat([p.K_new for p in c.prompts]).to(dev)
+    Vn = torch.cat([p.V_new for p in c.prompts]).to(dev)
+    qp = torch.from_numpy(np.concatenate([p.q_pos for p in c.prompts])).to(dev)
+    # the new tokens' rotated keys and values: an append into an empty buffer laid out like Q
+    tail_K = torch.full((total_q, w.n_kv_heads, w.head_dim), float("nan"), dtype=w.torch_dtype, device=dev)
+    tail_V = torch.full_like(tail_K, float("nan"))
+    tail_pos = torch.full((total_q,), -7, dtype=torch.int32, device=dev)
+    r.pc.pc_append_kv_batched(layer, Kn, Vn, qp, q_off, tail_K, tail_V, tail_pos, q_off, [0] * B)
+    out = torch.full((total_q, w.n_q_heads, w.head_dim), float("nan"), dtype=w.torch_dtype, device=dev)
+    r.pc.pc_prefill_attn_shared_batched(layer, Q, qp, q_off, [p.module_ids for p in c.prompts], tail_K, tail_V, out)
+    torch.cuda.synchronize()
+    launch = r.pc.pc_last_attn_launch()
+    o, tp = out.cpu(), tail_pos.cpu().numpy()
+    r.close()
+    assert np.array_equal(tp, qp.cpu().numpy())
+    rng = np.random.default_rng(5)
+    check = range(B) if B <= 5 else sorted(rng.choice(B, size=3, replace=False).tolist() + [0, B - 1])
+    for b in check:
+        if n_new[b] == 0:
+            continue
+        res = dict(out=o[q_off[b]:q_off[b + 1]], launch=launch)
+        rows = None
+        if q_sample and n_new[b] > q_sample:
+            rows = np.unique(np.concatenate([[0, n_new[b] - 1], rng.choice(n_new[b], size=q_sample - 2, replace=False)]))
+        check_attention(c, b, res, rows, "/in-place")
+
+
+def test_shared_modules_small_ragged_batch():
+    """Modules of odd sizes (ranges start and end inside 64-key tiles, several ranges per tile), a prompt
+    without modules, one with a single new token, and different module orders."""
+    w = W.custom("shared_small", "bf16", 8, 2, 128, [300, 64, 90, 70, 120, 33, 5, 1, 7], [-1, 0, 0, 0, 1, 1, -1, -1, -1],
+                 [W.Prompt([0, 1, 4], 40), W.Prompt([0, 2], 17), W.Prompt([], 9), W.Prompt([3, 0, 5], 64),
+                  W.Prompt([0], 1), W.Prompt([6, 7, 8, 1, 5], 33), W.Prompt([8, 0, 7, 6], 130)], max_pos=1024)
+    _shared_run(w, 0, None)
+
+
+def test_shared_modules_one_kv_head_group_few_rows():
+    """Fewer stacked query rows than one workgroup's eight row tiles: waves without rows only stage."""
+    w = W.custom("shared_mha", "bf16", 4, 4, 128, [200, 77, 150], None,
+                 [W.Prompt([0, 1, 2], 20), W.Prompt([2, 0], 70)], max_pos=1024)
+    _shared_run(w, 0, None)
+
+
+def test_shared_modules_more_ranges_than_one_launch_holds():
+    """70 prompts with two or three ranges each: the call is served by several launches."""
+    sizes = [40, 24, 56]
+    prompts = [W.Prompt([i % 3, (i + 1) % 3] if i % 2 else [i % 3], 1 + (i % 5)) for i in range(70)]
+    w = W.custom("shared_many", "bf16", 4, 2, 128, sizes, None, prompts, max_pos=512)
+    _shared_run(w, 0, None)
+
+
+def test_shared_modules_errors_touch_nothing():
+    w = W.custom("shared_err", "bf16", 8, 2, 128, [64, 48, 32], [-1, 0, 0], [W.Prompt([0, 1], 8), W.Prompt([2], 8)], max_pos=256)
+    c = build_case(w, 0)
+    r = GpuRunner(c)
+    dev = r.dev
+    Q = c.prompts[0].Q.to(dev)
+    qp = torch.from_numpy(c.prompts[0].q_pos).to(dev)
+    tK = torch.zeros((8, 2, 128), dtype=torch.bfloat16, device=dev)
+    out = torch.full((8, 8, 128), 3.0, dtype=torch.bfloat16, device=dev)
+    try:
+        with pytest.raises(pcb.PcError) as e:
+            r.pc.pc_prefill_attn_shared_batched(0, Q, qp, [0, 8], [[0, 99]], tK, tK, out)
+        assert e.value.status == -3
+        with pytest.raises(pcb.PcError) as e:   # modules 1 and 2 are members of one union: same positions
+            r.pc.pc_prefill_attn_shared_batched(0, Q, qp, [0, 8], [[0, 1, 2]], tK, tK, out)
+        assert e.value.status == -4
+        with pytest.raises(pcb.PcError) as e:
+            r.pc.pc_prefill_attn_shared_batched(7, Q, qp, [0, 8], [[0]], tK, tK, out)
+        assert e.value.status == -2
+        with pytest.raises(pcb.PcError) as e:
+            r.pc.pc_prefill_attn_shared_batched(0, Q, qp, [0, 8], [[0]], None, tK, out)
+        assert e.value.status == -1
+        torch.cuda.synchronize()
+        assert torch.all(out == 3.0)
+    finally:
+        r.close()
+
+
+def test_shared_modules_fp32_context_is_refused():
+    w = W.tiny_fp32()
+    c = build_case(w, 0)
+    r = GpuRunner(c)
+    p0 = c.prompts[0]
+    dev = r.dev
+    n = len(p0.q_pos)
+    try:
+        with pytest.raises(pcb.PcError) as e:
+            r.pc.pc_prefill_attn_shared_batched(0, p0.Q.to(dev), torch.from_numpy(p0.q_pos).to(dev), [0, n],
+                                                [p0.module_ids], p0.K_new.to(dev), p0.V_new.to(dev),
+                                                torch.zeros_like(p0.Q, device=dev))
+        assert e.value.status == -9
+    finally:
+        r.close()
+
+
+# ------------------------------------------------------------------ run-to-run determinism
+def _determinism_run(w, in_place, n_runs=60):
+    """The same attention launched many times back to back, with no host synchronisation between the
+    launches, must give the same bits every time: the kernels have no atomics and a fixed reduction
+    order, so any difference is a missing synchronisation between the waves of a workgroup."""
+    c = build_case(w, 0)
+    r = GpuRunner(c)
+    dev = r.dev
+    B = len(c.prompts)
+    n_mod = [sum(w.sizes[m] for m in p.module_ids) for p in c.prompts]
+    n_new = [len(p.q_pos) for p in c.prompts]
+    lens = [a + b for a, b in zip(n_mod, n_new)]
+    kv_off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    q_off = np.concatenate([[0], np.cumsum(n_new)]).astype(np.int64)
+    Q = torch.cat([p.Q for p in c.prompts]).to(dev)
+    Kn = torch.cat([p.K_new for p in c.prompts]).to(dev)
+    Vn = torch.cat([p.V_new for p in c.prompts]).to(dev)
+    qp = torch.from_numpy(np.concatenate([p.q_pos for p in c.prompts])).to(dev)
+    ids = [p.module_ids for p in c.prompts]
+    rows = int(q_off[-1]) if in_place else int(kv_off[-1])
+    bK = torch.empty((rows, w.n_kv_heads, w.head_dim), dtype=w.torch_dtype, device=dev)
+    bV = torch.empty_like(bK)
+    bP = torch.empty((rows,), dtype=torch.int32, device=dev)
+    if in_place:
+        r.pc.pc_append_kv_batched(0, Kn, Vn, qp, q_off, bK, bV, bP, q_off, [0] * B)
+        run = lambda o: r.pc.pc_prefill_attn_shared_batched(0, Q, qp, q_off, ids, bK, bV, o)
+    else:
+        r.pc.pc_assemble_append_kv_batched(0, ids, Kn, Vn, qp, q_off, bK, bV, bP, kv_off)
+        run = lambda o: r.pc.pc_prefill_attn_batched(0, Q, qp, q_off, bK, bV, bP, kv_off, lens, o)
+    outs = [torch.full_like(Q, float("nan")) for _ in range(n_runs)]
+    torch.cuda.synchronize()
+    for o in outs:
+        run(o)
+    torch.cuda.synchronize()
+    launch = r.pc.pc_last_attn_launch()
+    differ = [i for i, o in enumerate(outs) if not torch.equal(o, outs[0])]
+    r.close()
+    print(f"[{w.name}{'/in-place' if in_place else ''}] {n_runs} launches, launch={launch}, differing: {differ}", flush=True)
+    assert not torch.isnan(outs[0]).any()
+    assert not differ, f"runs {differ} differ from run 0"
+
+
+@pytest.mark.parametrize("in_place", [False, True])
+def test_attention_deterministic_long_single_pass(in_place):
+    """Config 5: 82 key tiles per workgroup in one pass, the longest inner loop of the benchmark."""
+    _determinism_run(W.batched_serving(), in_place)
+
+
+@pytest.mark.parametrize("in_place", [False, True])
+def test_attention_deterministic_split_kv(in_place):
+    _determinism_run(W.long_doc_8k(), in_place)
+
+
+def test_attention_deterministic_register_staged_kernel():
+    """head_dim 64 and few query rows: the kernel that stages K/V through registers."""
+    w = W.custom("det_d64", "bf16", 8, 8, 64, [4096, 2048, 1000], None,
+                 [W.Prompt([0, 1, 2], 96), W.Prompt([1, 0], 64), W.Prompt([2], 33)], max_pos=8192)
+    _determinism_run(w, False)
+
+
 # ------------------------------------------------------------------ the benchmark's configurations at full size
 @pytest.mark.parametrize("layer", [0, 31])
 def test_config2_llama7b_full_size_sampled(layer):
@@ -483,3 +651,11 @@ def test_config3_long_doc_8k_fused_assembly_full_size_sampled():
 
 def test_config5_batched_serving_full_size_sampled():
     _batched_run(W.batched_serving(), 0, 4)
+
+
+def test_config3_long_doc_8k_modules_in_place_full_size_sampled():
+    _shared_run(W.long_doc_8k(), 31, 24)
+
+
+def test_config5_batched_serving_modules_in_place_full_size_sampled():
+    _shared_run(W.batched_serving(), 0, 4)
