@@ -96,7 +96,15 @@ def main() -> int:
     ap.add_argument("--modules-in-place", action="store_true",
                     help="no packed copy: append the uncached tokens' rows to a tail buffer and let attention read the "
                          "modules from the pool (pc_prefill_attn_shared_batched)")
+    ap.add_argument("--host-tier", choices=["kernel", "engine"], default=None,
+                    help="keep the modules in pinned host memory (Sec. 4.1) and bring them in at every use: 'kernel' = "
+                         "the assembly kernel loads them over the host link, 'engine' = copy-engine transfers")
+    ap.add_argument("--overlap", action="store_true",
+                    help="assemble layer l+1 on a second stream while layer l's attention runs")
     args = ap.parse_args()
+    if args.host_tier and args.modules_in_place:
+        print("bench.py: --host-tier modules have to be assembled; it excludes --modules-in-place", file=sys.stderr)
+        return 2
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         return 2
@@ -119,9 +127,15 @@ def main() -> int:
 
     # ---------------- resident inputs
     pc = pcb.PromptCache.for_workload(w)
+    if args.host_tier:
+        pc.pc_host_pool_reserve(L * sum(2 * (w.sizes[m] * w.row_bytes + 512) for m in used))
+        pc.pc_set_host_copy_mode(pcb.PC_HOST_COPY_ENGINE if args.host_tier == "engine" else pcb.PC_HOST_READ_KERNEL)
     for layer in range(L):
         for m in used:
             k, v = W.module_raw_kv(w, layer, m)      # N(0,1), bf16; stored as the module's encoded states
+            if args.host_tier:
+                pc.pc_store_module_host(layer, m, k.contiguous(), v.contiguous(), starts[m])
+                continue
             pc.pc_store_module(layer, m, k.to(dev), v.to(dev), starts[m])
     torch.cuda.synchronize()
 
@@ -154,6 +168,9 @@ def main() -> int:
     lib = pcb.lib()
     ctx = pc._ctx
     stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream or None)
+    # --overlap: KV assembly on a second stream (default priority), attention stays on the first
+    copy_stream_t = torch.cuda.Stream() if args.overlap else None
+    asm_stream = ctypes.c_void_p(copy_stream_t.cuda_stream) if args.overlap else stream
     P = lambda t: ctypes.c_void_p(t.data_ptr())
     ids_flat = np.ascontiguousarray(np.asarray([m for ids in mod_ids for m in ids], dtype=np.intc))
     mod_offs = np.ascontiguousarray(np.concatenate([[0], np.cumsum([len(i) for i in mod_ids])]).astype(np.intc))
@@ -164,13 +181,13 @@ def main() -> int:
     calls = []
     for layer in range(L):
         a_asm = (ctx, layer, hp(ids_flat), hp(mod_offs), B, P(asm_K[layer]), P(asm_V[layer]), P(asm_pos[layer]),
-                 hp(kv_off_c), hp(n_out), stream)
+                 hp(kv_off_c), hp(n_out), asm_stream)
         a_app = (ctx, layer, P(Kn[layer]), P(Vn[layer]), P(q_pos), hp(q_off_c), B, P(asm_K[layer]), P(asm_V[layer]),
-                 P(asm_pos[layer]), hp(kv_off_c), hp(n_mod_c), stream)
+                 P(asm_pos[layer]), hp(kv_off_c), hp(n_mod_c), asm_stream)
         a_att = (ctx, layer, P(Q[layer]), P(q_pos), hp(q_off_c), B, P(asm_K[layer]), P(asm_V[layer]), P(asm_pos[layer]),
                  hp(kv_off_c), hp(kv_len_c), P(out[layer]), stream)
         a_fus = (ctx, layer, hp(ids_flat), hp(mod_offs), B, P(Kn[layer]), P(Vn[layer]), P(q_pos), hp(q_off_c),
-                 P(asm_K[layer]), P(asm_V[layer]), P(asm_pos[layer]), hp(kv_off_c), hp(n_out), stream)
+                 P(asm_K[layer]), P(asm_V[layer]), P(asm_pos[layer]), hp(kv_off_c), hp(n_out), asm_stream)
         calls.append((a_asm, a_app, a_att, a_fus))
     f_asm, f_app, f_att = lib.pc_assemble_kv_batched, lib.pc_append_kv_batched, lib.pc_prefill_attn_batched
     f_fus = lib.pc_assemble_append_kv_batched
@@ -192,12 +209,32 @@ def main() -> int:
                      P(tail_V[layer]), P(out[layer]), stream)
             calls_ip.append((a_tail, a_shr))
 
+    if args.overlap:
+        ev_asm = [torch.cuda.Event() for _ in range(L)]
+        ev_att = [torch.cuda.Event() for _ in range(L)]
+        for e in ev_att:
+            e.record(torch.cuda.current_stream())
+
     def step():
         if in_place:
             for a_tail, a_shr in calls_ip:
                 rc = f_app(*a_tail) or f_shr(*a_shr)
                 if rc:
                     raise pcb.PcError(rc, "bench step (modules in place)")
+            return
+        if args.overlap:
+            # layer l's KV is assembled on the second stream while the first runs layer l-1's attention; a
+            # layer's buffers are not overwritten before the previous step's attention on them has finished
+            main_t = torch.cuda.current_stream()
+            for l, (a_asm, a_app, a_att, a_fus) in enumerate(calls):
+                copy_stream_t.wait_event(ev_att[l])
+                rc = f_fus(*a_fus) if fused else (f_asm(*a_asm) or f_app(*a_app))
+                ev_asm[l].record(copy_stream_t)
+                main_t.wait_event(ev_asm[l])
+                rc = rc or f_att(*a_att)
+                ev_att[l].record(main_t)
+                if rc:
+                    raise pcb.PcError(rc, "bench step (overlapped)")
             return
         for a_asm, a_app, a_att, a_fus in calls:
             rc = (f_fus(*a_fus) if fused else (f_asm(*a_asm) or f_app(*a_app))) or f_att(*a_att)
@@ -255,7 +292,9 @@ def main() -> int:
         "ms_per_step_with_event_records": round(ms_per_step_events, 4) if ms_per_step_events else None,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": w.name, "kv_path": "modules read in place" if in_place else "packed copy", "layers": L, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
+        "config": {"workload": w.name, "kv_path": "modules read in place" if in_place else "packed copy",
+                   "module_tier": ("host memory, " + ("loaded by the assembly kernel" if args.host_tier == "kernel" else "copy engine")) if args.host_tier else "HBM pool",
+                   "overlap": bool(args.overlap), "layers": L, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
                    "head_dim": w.head_dim, "prompts": B, "module_tokens": n_mod if B <= 4 else [n_mod[0], "..."],
                    "uncached_tokens": n_new[0], "attn_launch": {"kv_splits": launch[0], "workgroups": launch[1],
                                                               "waves_per_wg": launch[2]}},
@@ -278,6 +317,20 @@ def main() -> int:
         result["roofline_assemble"] = {"kernel": "append_kernel" if in_place else ("gather_append_kernel" if fused else "gather_kv_kernel"), "bound": "hbm", "achieved": round(gat_gbs, 1),
                                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gat_gbs / HBM_PEAK_GBS, 4),
                                        "traffic": None if in_place else MEASURED_TRAFFIC.get((w.name, 32), {}).get("gather")}
+
+    if args.host_tier:
+        # PCIe-inclusive view: the modules' K and V cross the host link once per layer and step
+        h2d_layer = sum(n_mod) * 2 * w.row_bytes
+        result["host_tier"] = {"h2d_mbytes_per_layer": round(h2d_layer / 1e6, 3),
+                               "h2d_GBps_over_whole_step": round(h2d_layer * L / (ms_per_step * 1e-3) / 1e9, 2),
+                               "link_peak_GBps": 64.0, "link": "PCIe Gen5 x16, one direction"}
+        if "roofline_assemble" in result:
+            g_us = kern["gather"]["avg_us"]
+            result["roofline_assemble"].update({"bound": "host link", "peak": 64.0, "traffic": None,
+                                                "achieved": round(h2d_layer / (g_us * 1e-6) / 1e9, 2) if args.host_tier == "kernel" else None,
+                                                "frac": round(h2d_layer / (g_us * 1e-6) / 1e9 / 64.0, 4) if args.host_tier == "kernel" else None})
+        if "roofline" in result:
+            result["roofline"]["traffic"] = None
 
     # ---------------- full prefill of the same prompt with the same kernel (ordinary causal mask), one layer
     if not args.no_full_prefill and B == 1 and not in_place:

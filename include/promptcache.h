@@ -268,6 +268,39 @@ int pc_prefill_attn_batched(pc_ctx *ctx, int layer, const void *Q_new, const int
                             void *out, void *stream);
 
 /*
+ * Sec. 4.1: prompt modules kept in CPU memory (capacity of host DRAM instead of HBM, at the
+ * price of a host-to-device copy at every use; Sec. 5.4 measures that copy).
+ *
+ * pc_host_pool_reserve    allocates the context's host pool once: `bytes` of pinned host memory
+ *                         that the GPU can address.  PC_E_BADARG if a pool exists already or
+ *                         bytes == 0, PC_E_HIP if the allocation fails.
+ * pc_store_module_host    like pc_store_module, but K_host/V_host are HOST pointers
+ *                         ([n_tokens, n_kv_heads, head_dim], position-encoded keys) and the copy
+ *                         into the host pool is done by the CPU before the call returns; the
+ *                         caller keeps ownership of its buffers.  A module lives in the tier it
+ *                         was first stored in: storing an id again in the other tier is
+ *                         PC_E_DUP_MODULE.  Refreshing a host module while an assembly that reads
+ *                         it is still running on the GPU is a race the caller must avoid.
+ *                         PC_E_POOL_FULL if no host pool was reserved or it cannot hold the module.
+ * pc_set_host_copy_mode   how the assemble calls (pc_assemble_kv, pc_assemble_kv_batched,
+ *                         pc_assemble_append_kv_batched) bring host-resident modules in:
+ *                         PC_HOST_READ_KERNEL (default): the assembly kernel loads them from the
+ *                         pinned pool over the host link, in the same single launch as the
+ *                         HBM-resident modules; PC_HOST_COPY_ENGINE: one hipMemcpyAsync per module
+ *                         and tensor on the caller's stream straight into the packed buffer, the
+ *                         kernel then writes only those rows' position IDs.
+ * All other calls take module ids of either tier, except pc_prefill_attn_shared_batched, which
+ * refuses host-resident modules (PC_E_UNSUPPORTED): they have to be assembled first.
+ * The result of an assembly is bit-identical whichever tier and mode served it.
+ */
+#define PC_HOST_READ_KERNEL 0
+#define PC_HOST_COPY_ENGINE 1
+int pc_host_pool_reserve(pc_ctx *ctx, size_t bytes);
+int pc_store_module_host(pc_ctx *ctx, int layer, int module_id, const void *K_host, const void *V_host,
+                         int n_tokens, int start_pos);
+int pc_set_host_copy_mode(pc_ctx *ctx, int mode);
+
+/*
  * Sec. 3.4 (sharing modules between the prompts of a batch instead of copying them) and
  * Sec. 3.3: attention of every prompt's uncached tokens over its imported modules READ IN
  * PLACE from the module pool, followed by the uncached tokens' own rows.  No packed KV

@@ -25,9 +25,11 @@ EXPORTS = [
     "pc_schema_layout", "pc_uncached_positions", "pc_check_selection", "pc_bytes_per_token",
     "pc_module_info", "pc_pool_usage", "pc_last_attn_launch", "pc_profile_enable", "pc_profile_read",
     "pc_profile_read_each", "pc_set_module_params", "pc_fill_params",
+    "pc_host_pool_reserve", "pc_store_module_host", "pc_set_host_copy_mode",
 ]
 PROF_GATHER, PROF_APPEND, PROF_ATTN, PROF_COMBINE, PROF_ROPE = range(5)
 PC_POS_NONE = 0x7FFFFFFF
+PC_HOST_READ_KERNEL, PC_HOST_COPY_ENGINE = 0, 1
 
 
 class PcConfig(ctypes.Structure):
@@ -71,6 +73,9 @@ def lib() -> ctypes.CDLL:
     L.pc_assemble_append_kv_batched.argtypes = [vp, i, vp, vp, i, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     L.pc_prefill_attn_batched.argtypes = [vp, i, vp, vp, vp, i, vp, vp, vp, vp, vp, vp, vp]
     L.pc_prefill_attn_shared_batched.argtypes = [vp, i, vp, vp, vp, i, vp, vp, vp, vp, vp, vp]
+    L.pc_host_pool_reserve.argtypes = [vp, ctypes.c_size_t]
+    L.pc_store_module_host.argtypes = [vp, i, i, vp, vp, i, i]
+    L.pc_set_host_copy_mode.argtypes = [vp, i]
     L.pc_set_module_params.argtypes = [vp, i, i, vp, vp]
     L.pc_fill_params.argtypes = [vp, i, vp, i, i, vp, vp, vp, vp, vp, vp, vp, vp, i, vp]
     L.pc_schema_layout.argtypes = [i, vp, vp, vp]
@@ -274,6 +279,20 @@ class PromptCache:
         _check(lib().pc_prefill_attn_shared_batched(self._ctx, layer, _dev(Q_new), _dev(q_pos), _np_ptr(qo), B,
                                                     _np_ptr(flat), _np_ptr(offs), _dev(K_tail), _dev(V_tail), _dev(out),
                                                     _stream(stream)), "pc_prefill_attn_shared_batched")
+
+    def pc_host_pool_reserve(self, n_bytes: int) -> None:
+        _check(lib().pc_host_pool_reserve(self._ctx, int(n_bytes)), "pc_host_pool_reserve")
+
+    def pc_store_module_host(self, layer: int, module_id: int, K_host, V_host, start_pos: int) -> None:
+        """K_host / V_host: contiguous CPU torch tensors [n_tokens, n_kv_heads, head_dim]."""
+        assert not K_host.is_cuda and not V_host.is_cuda and K_host.is_contiguous() and V_host.is_contiguous()
+        assert K_host.shape == V_host.shape
+        n = int(K_host.shape[0])
+        _check(lib().pc_store_module_host(self._ctx, layer, int(module_id), K_host.data_ptr() if n else None,
+                                          V_host.data_ptr() if n else None, n, int(start_pos)), "pc_store_module_host")
+
+    def pc_set_host_copy_mode(self, mode: int) -> None:
+        _check(lib().pc_set_host_copy_mode(self._ctx, int(mode)), "pc_set_host_copy_mode")
 
     def pc_set_module_params(self, module_id: int, offsets: Sequence[int], lens: Sequence[int]) -> None:
         o, l = _ints(offsets), _ints(lens)

@@ -21,6 +21,7 @@ struct ModuleEntry {
     size_t v_offset;
     int n_tokens;
     int start_pos;
+    bool host = false;   // offsets are into the pinned host pool (Sec. 4.1, modules kept in CPU memory)
 };
 
 // A parameter of a module (Sec. 3.2.2): rows [offset, offset+len) of the module hold placeholder states.
@@ -55,6 +56,9 @@ struct pc_ctx {
 
     uint8_t *pool = nullptr;  // module pool (device)
     size_t pool_used = 0;
+    uint8_t *host_pool = nullptr;  // module pool in pinned host memory, mapped into the device's address space
+    size_t host_pool_bytes = 0, host_pool_used = 0;
+    int host_copy_mode = PC_HOST_READ_KERNEL;
     std::vector<std::unordered_map<int, pc::ModuleEntry>> modules;  // per layer
     std::unordered_map<int, std::vector<pc::ParamSlot>> params;     // per module id (schema level, all layers)
 
@@ -75,8 +79,8 @@ namespace pc {
 // ---- gather (KV assembly) ---------------------------------------------------
 // One contiguous run of rows copied from the pool to the packed output.
 struct GatherSeg {
-    const uint8_t *src_k;
-    const uint8_t *src_v;
+    const uint8_t *src_k;   // nullptr: the rows are brought in by a copy-engine transfer, the kernel writes
+    const uint8_t *src_v;   //          their position IDs only (tiles of kPosOnlyTileFactor x rows_per_tile rows)
     int dst_row;     // first output row
     int n_rows;
     int start_pos;   // position ID of the first row
@@ -84,6 +88,7 @@ struct GatherSeg {
 };
 
 constexpr int kMaxGatherSegs = 64;
+constexpr int kPosOnlyTileFactor = 64;
 
 struct GatherArgs {
     int n_segs;

@@ -38,6 +38,13 @@ __device__ __forceinline__ void gather_tile(const GatherArgs &a, int tile, uint8
         else hi = mid - 1;
     }
     const GatherSeg sg = a.seg[lo];
+    if (sg.src_k == nullptr) {   // rows copied by the copy engine: position IDs only, in larger tiles
+        const int rpt = a.rows_per_tile * kPosOnlyTileFactor;
+        const int p0 = (tile - sg.first_tile) * rpt;
+        const int pn = sg.n_rows - p0 < rpt ? sg.n_rows - p0 : rpt;
+        for (int r = threadIdx.x; r < pn; r += kThreads) out_pos[sg.dst_row + p0 + r] = sg.start_pos + p0 + r;
+        return;
+    }
     const int r0 = (tile - sg.first_tile) * a.rows_per_tile;
     int n_rows = sg.n_rows - r0;
     if (n_rows > a.rows_per_tile) n_rows = a.rows_per_tile;

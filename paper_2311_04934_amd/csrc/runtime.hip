@@ -80,8 +80,8 @@ int plan_prompt(const pc_ctx *ctx, int layer, const int *ids, int n, int dst_row
         const ModuleEntry &m = table.find(ids[i])->second;
         if (m.n_tokens == 0) continue;
         GatherSeg s;
-        s.src_k = ctx->pool + m.k_offset;
-        s.src_v = ctx->pool + m.v_offset;
+        s.src_k = (m.host ? ctx->host_pool : ctx->pool) + m.k_offset;
+        s.src_v = (m.host ? ctx->host_pool : ctx->pool) + m.v_offset;
         s.dst_row = row;
         s.n_rows = m.n_tokens;
         s.start_pos = m.start_pos;
@@ -93,9 +93,41 @@ int plan_prompt(const pc_ctx *ctx, int layer, const int *ids, int n, int dst_row
     return PC_OK;
 }
 
-int run_gather(pc_ctx *ctx, const std::vector<GatherSeg> &segs, void *out_K, void *out_V, int32_t *out_pos,
+bool in_host_pool(const pc_ctx *ctx, const uint8_t *p)
+{
+    return ctx->host_pool && p >= ctx->host_pool && p < ctx->host_pool + ctx->host_pool_bytes;
+}
+
+// Host-resident modules under PC_HOST_COPY_ENGINE: one transfer per module and tensor on the caller's
+// stream, straight into the packed buffer (a module's rows are contiguous on both sides); the segment
+// is then left to the kernel for its position IDs only.
+int copy_host_segments(pc_ctx *ctx, std::vector<GatherSeg> &segs, void *out_K, void *out_V, hipStream_t stream)
+{
+    if (ctx->host_copy_mode != PC_HOST_COPY_ENGINE) return PC_OK;
+    for (GatherSeg &sg : segs) {
+        if (!in_host_pool(ctx, sg.src_k)) continue;
+        const size_t bytes = (size_t)sg.n_rows * ctx->row_bytes, dst = (size_t)sg.dst_row * ctx->row_bytes;
+        if (hipMemcpyAsync(static_cast<uint8_t *>(out_K) + dst, sg.src_k, bytes, hipMemcpyHostToDevice, stream) != hipSuccess ||
+            hipMemcpyAsync(static_cast<uint8_t *>(out_V) + dst, sg.src_v, bytes, hipMemcpyHostToDevice, stream) != hipSuccess) {
+            (void)hipGetLastError();
+            return PC_E_HIP;
+        }
+        sg.src_k = sg.src_v = nullptr;
+    }
+    return PC_OK;
+}
+
+int tiles_of(const GatherSeg &sg, int rows_per_tile)
+{
+    const int rpt = sg.src_k ? rows_per_tile : rows_per_tile * kPosOnlyTileFactor;
+    return (sg.n_rows + rpt - 1) / rpt;
+}
+
+int run_gather(pc_ctx *ctx, std::vector<GatherSeg> &segs, void *out_K, void *out_V, int32_t *out_pos,
                hipStream_t stream)
 {
+    int rc = copy_host_segments(ctx, segs, out_K, out_V, stream);
+    if (rc != PC_OK) return rc;
     // about 16 KiB of K (and as much of V) per workgroup
     int rows_per_tile = (int)(16384 / ctx->row_bytes);
     if (rows_per_tile < 1) rows_per_tile = 1;
@@ -108,10 +140,10 @@ int run_gather(pc_ctx *ctx, const std::vector<GatherSeg> &segs, void *out_K, voi
         for (int i = 0; i < a.n_segs; ++i) {
             a.seg[i] = segs[base + i];
             a.seg[i].first_tile = tiles;
-            tiles += (a.seg[i].n_rows + rows_per_tile - 1) / rows_per_tile;
+            tiles += tiles_of(a.seg[i], rows_per_tile);
         }
         a.total_tiles = tiles;
-        int rc = launch_gather(ctx, a, static_cast<uint8_t *>(out_K), static_cast<uint8_t *>(out_V), out_pos, stream);
+        rc = launch_gather(ctx, a, static_cast<uint8_t *>(out_K), static_cast<uint8_t *>(out_V), out_pos, stream);
         if (rc != PC_OK) return rc;
     }
     return PC_OK;
@@ -281,6 +313,7 @@ int pc_destroy(pc_ctx *ctx)
     if (ctx->rope_table) (void)hipFree(ctx->rope_table);
     if (ctx->rope_table_t) (void)hipFree(ctx->rope_table_t);
     if (ctx->iota) (void)hipFree(ctx->iota);
+    if (ctx->host_pool) (void)hipHostFree(ctx->host_pool);
     delete ctx;
     return PC_OK;
 }
@@ -298,7 +331,7 @@ int pc_store_module(pc_ctx *ctx, int layer, int module_id, const void *K, const 
     auto it = table.find(module_id);
     ModuleEntry e;
     if (it != table.end()) {
-        if (it->second.n_tokens != n_tokens || it->second.start_pos != start_pos) return PC_E_DUP_MODULE;
+        if (it->second.n_tokens != n_tokens || it->second.start_pos != start_pos || it->second.host) return PC_E_DUP_MODULE;
         e = it->second;  // refresh in place
     } else {
         const size_t k_off = align_up(ctx->pool_used, kPoolAlign);
@@ -319,6 +352,66 @@ int pc_store_module(pc_ctx *ctx, int layer, int module_id, const void *K, const 
     if (it == table.end()) {
         table.emplace(module_id, e);
         ctx->pool_used = e.v_offset + bytes;
+    }
+    return PC_OK;
+}
+
+int pc_host_pool_reserve(pc_ctx *ctx, size_t bytes)
+{
+    if (!ctx || bytes == 0 || ctx->host_pool) return PC_E_BADARG;
+    if (hipSetDevice(ctx->device) != hipSuccess) return PC_E_HIP;
+    void *p = nullptr;
+    // pinned and mapped: the copy engine transfers from it at link speed and kernels can load from it
+    if (hipHostMalloc(&p, bytes, hipHostMallocDefault) != hipSuccess) {
+        (void)hipGetLastError();
+        return PC_E_HIP;
+    }
+    ctx->host_pool = static_cast<uint8_t *>(p);
+    ctx->host_pool_bytes = bytes;
+    ctx->host_pool_used = 0;
+    return PC_OK;
+}
+
+int pc_set_host_copy_mode(pc_ctx *ctx, int mode)
+{
+    if (!ctx || (mode != PC_HOST_READ_KERNEL && mode != PC_HOST_COPY_ENGINE)) return PC_E_BADARG;
+    ctx->host_copy_mode = mode;
+    return PC_OK;
+}
+
+int pc_store_module_host(pc_ctx *ctx, int layer, int module_id, const void *K_host, const void *V_host, int n_tokens,
+                         int start_pos)
+{
+    if (!ctx || module_id < 0 || n_tokens < 0) return PC_E_BADARG;
+    if (layer < 0 || layer >= ctx->cfg.n_layers) return PC_E_LAYER;
+    if (n_tokens > 0 && (!K_host || !V_host)) return PC_E_BADARG;
+    if (start_pos < 0 || (long)start_pos + n_tokens > (long)ctx->cfg.max_pos) return PC_E_POS_RANGE;
+
+    auto &table = ctx->modules[layer];
+    const size_t bytes = (size_t)n_tokens * ctx->row_bytes;
+    auto it = table.find(module_id);
+    ModuleEntry e;
+    if (it != table.end()) {
+        // refresh in place; a module keeps the tier it was first stored in
+        if (it->second.n_tokens != n_tokens || it->second.start_pos != start_pos || !it->second.host) return PC_E_DUP_MODULE;
+        e = it->second;
+    } else {
+        const size_t k_off = align_up(ctx->host_pool_used, kPoolAlign);
+        const size_t v_off = align_up(k_off + bytes, kPoolAlign);
+        if (!ctx->host_pool || v_off + bytes > ctx->host_pool_bytes) return PC_E_POOL_FULL;
+        e.k_offset = k_off;
+        e.v_offset = v_off;
+        e.n_tokens = n_tokens;
+        e.start_pos = start_pos;
+        e.host = true;
+    }
+    if (bytes) {
+        memcpy(ctx->host_pool + e.k_offset, K_host, bytes);
+        memcpy(ctx->host_pool + e.v_offset, V_host, bytes);
+    }
+    if (it == table.end()) {
+        table.emplace(module_id, e);
+        ctx->host_pool_used = e.v_offset + bytes;
     }
     return PC_OK;
 }
@@ -425,6 +518,8 @@ int pc_assemble_append_kv_batched(pc_ctx *ctx, int layer, const int *module_ids_
 
     int rc = PC_OK;
     if (segs.size() <= (size_t)kMaxGatherSegs && n_prompts <= kMaxFusedAppendSegs) {
+        rc = copy_host_segments(ctx, segs, out_K, out_V, as_stream(stream));
+        if (rc != PC_OK) return rc;
         FusedKvArgs a;
         int rows_per_tile = (int)(16384 / ctx->row_bytes);
         if (rows_per_tile < 1) rows_per_tile = 1;
@@ -435,7 +530,7 @@ int pc_assemble_append_kv_batched(pc_ctx *ctx, int layer, const int *module_ids_
         for (int i = 0; i < a.g.n_segs; ++i) {
             a.g.seg[i] = segs[i];
             a.g.seg[i].first_tile = tiles;
-            tiles += (a.g.seg[i].n_rows + rows_per_tile - 1) / rows_per_tile;
+            tiles += tiles_of(a.g.seg[i], rows_per_tile);
         }
         a.g.total_tiles = tiles;
         a.n_app = n_prompts;
@@ -602,6 +697,7 @@ int pc_prefill_attn_shared_batched(pc_ctx *ctx, int layer, const void *Q_new, co
             starts[i] = it->second.start_pos;
             lens[i] = it->second.n_tokens;
             if ((size_t)lens[i] * ctx->row_bytes >= ((size_t)1 << 32)) return PC_E_UNSUPPORTED;   // 32-bit offsets inside a range
+            if (it->second.host) return PC_E_UNSUPPORTED;   // host-resident modules are assembled (copied), not read in place
         }
         int rc = check_ranges(nm, starts.data(), lens.data(), ctx->cfg.max_pos);
         if (rc != PC_OK) return rc;

@@ -123,7 +123,8 @@ def oracle_attn(c: Case, pi: int, q_rows: Optional[Sequence[int]] = None) -> np.
 class GpuRunner:
     """Stores a case's modules in a pool and serves its prompts through the C ABI."""
 
-    def __init__(self, c: Case, scratch_bytes: int = 0):
+    def __init__(self, c: Case, scratch_bytes: int = 0, host_modules: Sequence[int] = (), host_mode: Optional[int] = None):
+        """host_modules: ids stored in the pinned host pool instead of the HBM pool (Sec. 4.1)."""
         self.c = c
         w = c.w
         self.pc = pcb.PromptCache.for_workload(w, n_layers=max(c.layer + 1, 1), scratch_bytes=scratch_bytes)
@@ -131,8 +132,16 @@ class GpuRunner:
         starts, _ = pcb.pc_schema_layout(w.sizes, w.union_ids)
         assert starts == c.starts
         self.dev = torch.device("cuda:0")
+        host = set(host_modules)
+        if host:
+            self.pc.pc_host_pool_reserve(sum(2 * (w.sizes[m] * w.row_bytes + 512) for m in host))
+        if host_mode is not None:
+            self.pc.pc_set_host_copy_mode(host_mode)
         for m in sorted(c.mod_K):
-            self.pc.pc_store_module(c.layer, m, c.mod_K[m].to(self.dev), c.mod_V[m].to(self.dev), c.starts[m])
+            if m in host:
+                self.pc.pc_store_module_host(c.layer, m, c.mod_K[m].contiguous(), c.mod_V[m].contiguous(), c.starts[m])
+            else:
+                self.pc.pc_store_module(c.layer, m, c.mod_K[m].to(self.dev), c.mod_V[m].to(self.dev), c.starts[m])
         torch.cuda.synchronize()
 
     def close(self):

@@ -54,9 +54,9 @@ def check_attention(c, pi, res, q_rows=None, label=""):
     assert rel <= TOL_REL[c.w.dtype], (err, rel)
 
 
-def run_and_check(w, layer=0, q_sample=None, scratch_bytes=0, extra_capacity=0, label=""):
+def run_and_check(w, layer=0, q_sample=None, scratch_bytes=0, extra_capacity=0, label="", **runner_kw):
     c = build_case(w, layer)
-    r = GpuRunner(c, scratch_bytes=scratch_bytes)
+    r = GpuRunner(c, scratch_bytes=scratch_bytes, **runner_kw)
     try:
         for pi in range(len(c.prompts)):
             res = r.serve(pi, extra_capacity=extra_capacity)
@@ -266,9 +266,9 @@ def test_error_paths():
 
 
 # ------------------------------------------------------------------ batched (config 5 shape, reduced and full)
-def _batched_run(w, layer, q_sample, fused=False):
+def _batched_run(w, layer, q_sample, fused=False, **runner_kw):
     c = build_case(w, layer)
-    r = GpuRunner(c)
+    r = GpuRunner(c, **runner_kw)
     dev = r.dev
     B = len(c.prompts)
     n_mod = [sum(w.sizes[m] for m in p.module_ids) for p in c.prompts]
@@ -569,6 +569,73 @@ def test_shared_modules_fp32_context_is_refused():
         r.close()
 
 
+# ------------------------------------------------------------------ modules kept in host memory (Sec. 4.1)
+HOST_MODES = [pcb.PC_HOST_READ_KERNEL, pcb.PC_HOST_COPY_ENGINE]
+
+
+@pytest.mark.parametrize("mode", HOST_MODES)
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_host_tier_mixed_with_hbm_modules(mode, dtype):
+    """Some modules in pinned host memory, some in the HBM pool, odd sizes: the assembled rows, position IDs
+    and the attention on top must not depend on where a module was kept or how it was brought in."""
+    hq, hkv, d = (8, 2, 128) if dtype == "bf16" else (4, 2, 64)
+    w = W.custom("host_mixed", dtype, hq, hkv, d, [300, 64, 90, 70, 120, 33, 0, 1], [-1, 0, 0, 0, 1, 1, -1, -1],
+                 [W.Prompt([0, 1, 4], 40), W.Prompt([0, 2], 17), W.Prompt([], 9), W.Prompt([3, 0, 5, 6, 7], 64),
+                  W.Prompt([7], 1)], max_pos=1024)
+    for fused in (False, True):
+        _batched_run(w, 0, None, fused=fused, host_modules=[0, 2, 5, 6, 7], host_mode=mode)
+    run_and_check(w, host_modules=[1, 3, 4], host_mode=mode, label=f"/host mode {mode}")
+
+
+@pytest.mark.parametrize("mode", HOST_MODES)
+def test_host_tier_more_segments_than_one_launch(mode):
+    sizes = [40, 24, 56]
+    prompts = [W.Prompt([i % 3], 1 + (i % 5)) for i in range(70)]
+    w = W.custom("host_many", "bf16", 4, 2, 64, sizes, None, prompts, max_pos=512)
+    _batched_run(w, 0, None, fused=True, host_modules=[0, 2], host_mode=mode)
+
+
+def test_host_tier_error_paths():
+    w = W.custom("host_err", "bf16", 8, 2, 128, [64, 48], None, [W.Prompt([0, 1], 8)], max_pos=256)
+    c = build_case(w, 0)
+    r = GpuRunner(c)          # both modules in the HBM pool, no host pool yet
+    pc = r.pc
+    k = c.mod_K[0].contiguous()
+
+    def status(fn):
+        try:
+            fn()
+            return 0
+        except pcb.PcError as e:
+            return e.status
+
+    try:
+        assert status(lambda: pc.pc_store_module_host(0, 5, k, k, 128)) == -6       # no host pool reserved
+        assert status(lambda: pc.pc_host_pool_reserve(0)) == -1
+        assert status(lambda: pc.pc_host_pool_reserve(2 * k.numel() * 2 + 1024)) == 0
+        assert status(lambda: pc.pc_host_pool_reserve(1 << 20)) == -1               # only once
+        assert status(lambda: pc.pc_store_module_host(0, 0, k, k, 0)) == -7         # id 0 lives in the HBM pool
+        assert status(lambda: pc.pc_store_module_host(0, 5, k, k, 128)) == 0
+        assert status(lambda: pc.pc_store_module_host(0, 5, k, k, 128)) == 0        # refresh in place
+        assert status(lambda: pc.pc_store_module_host(0, 5, k[:8], k[:8], 128)) == -7
+        assert status(lambda: pc.pc_store_module(0, 5, k.to(r.dev), k.to(r.dev), 128)) == -7   # id 5 lives in host memory
+        assert status(lambda: pc.pc_store_module_host(0, 6, k, k, 192)) == -6       # host pool full
+        assert status(lambda: pc.pc_store_module_host(0, 7, k, k, 224)) == -8       # beyond max_pos
+        assert status(lambda: pc.pc_store_module_host(3, 7, k, k, 0)) == -2
+        assert status(lambda: pc.pc_set_host_copy_mode(2)) == -1
+        # a host-resident module cannot be read in place by the attention kernel
+        Q = c.prompts[0].Q.to(r.dev)
+        qp = torch.from_numpy(c.prompts[0].q_pos).to(r.dev)
+        tK = torch.zeros((8, 2, 128), dtype=torch.bfloat16, device=r.dev)
+        out = torch.full((8, 8, 128), 3.0, dtype=torch.bfloat16, device=r.dev)
+        assert status(lambda: pc.pc_prefill_attn_shared_batched(0, Q, qp, [0, 8], [[0, 5]], tK, tK, out)) == -9
+        torch.cuda.synchronize()
+        assert torch.all(out == 3.0)
+        assert pc.pc_module_info(0, 5) == (64, 128)
+    finally:
+        r.close()
+
+
 # ------------------------------------------------------------------ run-to-run determinism
 def _determinism_run(w, in_place, n_runs=60):
     """The same attention launched many times back to back, with no host synchronisation between the
@@ -659,3 +726,9 @@ def test_config3_long_doc_8k_modules_in_place_full_size_sampled():
 
 def test_config5_batched_serving_modules_in_place_full_size_sampled():
     _shared_run(W.batched_serving(), 0, 4)
+
+
+@pytest.mark.parametrize("mode", HOST_MODES)
+def test_config3_long_doc_8k_host_tier_full_size_sampled(mode):
+    w = W.long_doc_8k()
+    _batched_run(w, 0, 12, fused=True, host_modules=w.used_module_ids(), host_mode=mode)
