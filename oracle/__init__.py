@@ -53,6 +53,10 @@ def _load():
     lib.orc_assemble.restype = c_long
     lib.orc_attn.argtypes = [P, P, c_int, P, P, P, c_int, c_int, c_int, c_int, c_dbl, P]
     lib.orc_attn.restype = None
+    lib.orc_alibi_slopes.argtypes = [c_int, P]
+    lib.orc_alibi_slopes.restype = None
+    lib.orc_attn_alibi.argtypes = [P, P, c_int, P, P, P, c_int, c_int, c_int, c_int, P, P]
+    lib.orc_attn_alibi.restype = None
     lib.orc_full_masked.argtypes = [P, P, P, P, P, c_int, c_int, c_int, c_int, c_dbl, P, P]
     lib.orc_full_masked.restype = None
     lib.orc_fill_param.argtypes = [P, P, P, c_int, c_int, P, P, c_int, c_int, c_int, c_dbl]
@@ -158,6 +162,31 @@ def attn(Q, q_pos, K, V, k_pos, base: float = 10000.0) -> np.ndarray:
     assert qp.shape == (nq,) and kp.shape == (nkv,)
     out = np.zeros((nq, Hq, d), dtype=np.float64)
     _load().orc_attn(_ptr(Q), _ptr(qp), nq, _ptr(K), _ptr(V), _ptr(kp), nkv, Hq, Hkv, d, float(base), _ptr(out))
+    return out
+
+
+def alibi_slopes(n_heads: int) -> np.ndarray:
+    """Per-head slopes of the linear attention bias (Sec. 4.2, ALiBi): 8 heads -> 1/2 ... 1/256."""
+    out = np.zeros(n_heads, dtype=np.float64)
+    _load().orc_alibi_slopes(int(n_heads), _ptr(out))
+    return out
+
+
+def attn_alibi(Q, q_pos, K, V, k_pos, slopes) -> np.ndarray:
+    """Uncached-token attention with the linear bias -slope[h] * (q_pos - k_pos) on position IDs (Sec. 4.2).
+
+    Q [nq,Hq,d] and K [nkv,Hkv,d] enter as they are (no rotation); key j is visible to query q iff
+    k_pos[j] <= q_pos[q].  Returns fp64 [nq,Hq,d].
+    """
+    Q, K, V = _f64(Q), _f64(K), _f64(V)
+    qp, kp = _i32(q_pos), _i32(k_pos)
+    sl = _f64(slopes)
+    nq, Hq, d = Q.shape
+    nkv, Hkv, d2 = K.shape
+    assert d == d2 and V.shape == K.shape and Hq % Hkv == 0 and sl.shape == (Hq,)
+    assert qp.shape == (nq,) and kp.shape == (nkv,)
+    out = np.zeros((nq, Hq, d), dtype=np.float64)
+    _load().orc_attn_alibi(_ptr(Q), _ptr(qp), nq, _ptr(K), _ptr(V), _ptr(kp), nkv, Hq, Hkv, d, _ptr(sl), _ptr(out))
     return out
 
 

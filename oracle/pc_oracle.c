@@ -247,6 +247,64 @@ void orc_attn(const double *Q, const int32_t *q_pos, int nq, const double *K, co
 }
 
 /* ------------------------------------------------------------------ */
+/* ALiBi at arbitrary position IDs  (Sec. 4.2, "ALiBi")                 */
+/* ------------------------------------------------------------------ */
+
+/*
+ * Per-head slopes of the linear attention bias as its authors define them:
+ * for a power-of-two head count n the geometric sequence 2^(-8/n), 2^(-16/n),
+ * ... (8 heads: 1/2, 1/4, ..., 1/256).  For other counts: the sequence of the
+ * largest power of two p below n, followed by every other member (the 1st,
+ * 3rd, ...) of the sequence for 2p until n slopes exist.
+ */
+void orc_alibi_slopes(int n_heads, double *slopes)
+{
+    int p = 1;
+    while (2 * p <= n_heads) p *= 2;
+    for (int i = 0; i < p; ++i) slopes[i] = pow(2.0, -8.0 * (double)(i + 1) / (double)p);
+    for (int i = 0; p + i < n_heads; ++i) slopes[p + i] = pow(2.0, -8.0 * (double)(2 * i + 1) / (double)(2 * p));
+}
+
+/*
+ * Attention with the linear bias instead of a rotation:
+ *   out[q][h][:] = sum_j softmax_j( Q[q][h] . K[j][kv(h)] / sqrt(d)  -  slope[h] (q_pos[q] - k_pos[j]) ) V[j][kv(h)]
+ * over the keys j with k_pos[j] <= q_pos[q].  The paper asks for the bias to
+ * follow the provided position IDs, so the distance is a difference of
+ * position IDs, not of buffer rows: a module left out of the prompt leaves
+ * its distance in place.  Q and K enter as they are (nothing is rotated).
+ *
+ * Q [nq][Hq][d]   K,V [nkv][Hkv][d]   slope [Hq]   out [nq][Hq][d]
+ */
+void orc_attn_alibi(const double *Q, const int32_t *q_pos, int nq, const double *K, const double *V,
+                    const int32_t *k_pos, int nkv, int Hq, int Hkv, int d, const double *slope, double *out)
+{
+    int group = Hq / Hkv;
+    double inv_sqrt_d = 1.0 / sqrt((double)d);
+    long pairs = (long)nq * Hq;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 4) num_threads(g_threads)
+#endif
+    for (long w = 0; w < pairs; ++w) {
+        int q = (int)(w / Hq), h = (int)(w % Hq);
+        int kvh = h / group;
+        const double *qv = Q + ((size_t)q * Hq + h) * d;
+        double *s = (double *)malloc(sizeof(double) * (size_t)(nkv > 0 ? nkv : 1));
+        for (int j = 0; j < nkv; ++j) {
+            if (k_pos[j] <= q_pos[q]) {
+                const double *k = K + ((size_t)j * Hkv + kvh) * d;
+                double dot = 0.0;
+                for (int c = 0; c < d; ++c) dot += qv[c] * k[c];
+                s[j] = dot * inv_sqrt_d - slope[h] * (double)(q_pos[q] - k_pos[j]);
+            } else {
+                s[j] = -INFINITY;
+            }
+        }
+        softmax_times_v(s, nkv, V + (size_t)kvh * d, Hkv * d, d, out + ((size_t)q * Hq + h) * d);
+        free(s);
+    }
+}
+
+/* ------------------------------------------------------------------ */
 /* Full recompute under module-local masking  (Sec. 3.1, Sec. 3.3)      */
 /* ------------------------------------------------------------------ */
 

@@ -9,6 +9,7 @@ import os
 
 import numpy as np
 import pytest
+import torch
 
 import oracle
 from oracle.toy import ToyModel
@@ -479,3 +480,87 @@ def test_attention_flop_count_matches_papers_quadratic_term():
     # cached serving touches n_new * n pairs instead (Sec. 3.4): ratio n / n_new
     n_new = 100
     assert (per_pair * n * n) / (per_pair * n_new * n) == n / n_new
+
+
+# ------------------------------------------------------------------ ALiBi at arbitrary position IDs (Sec. 4.2)
+def test_alibi_slopes_match_the_published_sequence():
+    for line in open(os.path.join(GOLDEN, "alibi_slopes.txt")).read().splitlines():
+        if not line.strip() or line.startswith("#"):
+            continue
+        n, vals = line.split(":")
+        want = [2.0 ** float(t[2:]) for t in vals.split()]
+        got = oracle.alibi_slopes(int(n))
+        assert got.shape == (int(n),)
+        assert np.allclose(got, want, rtol=1e-15, atol=0)
+
+
+def test_alibi_zero_queries_give_the_geometric_closed_form():
+    """Q = 0 leaves only the bias: over positions 0..n-1 the last token's weights are r^(n-1-j) (1-r)/(1-r^n),
+    r = exp(-slope); V = identity rows exposes the weights themselves."""
+    n, H = 24, 4
+    slopes = oracle.alibi_slopes(H)
+    Q = np.zeros((1, H, n))
+    K = np.random.default_rng(50).standard_normal((n, H, n))
+    V = np.broadcast_to(np.eye(n)[:, None, :], (n, H, n)).copy()
+    pos = np.arange(n, dtype=np.int32)
+    out = oracle.attn_alibi(Q, pos[-1:], K, V, pos, slopes)
+    for h in range(H):
+        r = math.exp(-slopes[h])
+        want = np.array([r ** (n - 1 - j) for j in range(n)]) * (1 - r) / (1 - r ** n)
+        assert np.allclose(out[0, h], want, rtol=1e-12, atol=1e-15)
+
+
+def test_alibi_distance_is_measured_in_position_ids_not_buffer_rows():
+    """A module left out of the prompt (positions 3..9 missing) keeps its distance: weights follow 11 - pos."""
+    H, slopes = 2, np.array([0.3, 0.05])
+    k_pos = np.array([10, 11, 0, 1, 2], dtype=np.int32)          # buffer order differs from position order
+    n = len(k_pos)
+    V = np.broadcast_to(np.eye(n)[:, None, :], (n, H, n)).copy()
+    out = oracle.attn_alibi(np.zeros((1, H, n)), np.array([11], dtype=np.int32), np.ones((n, H, n)), V, k_pos, slopes)
+    for h in range(H):
+        w = np.exp(-slopes[h] * (11 - k_pos))
+        assert np.allclose(out[0, h], w / w.sum(), rtol=1e-12)
+    # a key whose position lies after the query's is hidden
+    out2 = oracle.attn_alibi(np.zeros((1, H, n)), np.array([10], dtype=np.int32), np.ones((n, H, n)), V, k_pos, slopes)
+    assert np.all(out2[0, :, 1] == 0.0) and np.allclose(out2[0].sum(axis=-1), 1.0)
+
+
+def test_alibi_matches_library_attention_with_an_additive_mask():
+    """torch's scaled_dot_product_attention with a float mask -slope*(p_q - p_k) (and -inf where hidden), GQA
+    expanded by hand, keys in shuffled buffer order, position IDs with gaps."""
+    rng = np.random.default_rng(51)
+    Hq, Hkv, d, nk, nq = 6, 2, 16, 40, 7
+    slopes = oracle.alibi_slopes(Hq)
+    k_pos = rng.permutation(np.r_[0:15, 30:45, 60:70]).astype(np.int32)
+    q_pos = np.array([70, 71, 72, 20, 44, 5, 69], dtype=np.int32)
+    Q, K, V = rng.standard_normal((nq, Hq, d)), rng.standard_normal((nk, Hkv, d)), rng.standard_normal((nk, Hkv, d))
+    got = oracle.attn_alibi(Q, q_pos, K, V, k_pos, slopes)
+    g = Hq // Hkv
+    Kx, Vx = np.repeat(K, g, axis=1), np.repeat(V, g, axis=1)
+    dist = (q_pos[:, None] - k_pos[None, :]).astype(np.float64)
+    bias = np.where(dist >= 0, -slopes[:, None, None] * dist[None], -np.inf)          # [Hq, nq, nk]
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a))
+    ref = torch.nn.functional.scaled_dot_product_attention(t(Q).permute(1, 0, 2)[None], t(Kx).permute(1, 0, 2)[None],
+                                                           t(Vx).permute(1, 0, 2)[None], attn_mask=t(bias)[None])
+    ref = ref[0].permute(1, 0, 2).numpy()
+    assert np.allclose(got, ref, rtol=0, atol=1e-12)
+
+
+def test_alibi_depends_on_position_differences_only_and_reduces_to_plain_attention():
+    rng = np.random.default_rng(52)
+    Hq, Hkv, d, nk, nq = 4, 4, 8, 12, 3
+    Q, K, V = rng.standard_normal((nq, Hq, d)), rng.standard_normal((nk, Hkv, d)), rng.standard_normal((nk, Hkv, d))
+    k_pos = np.arange(nk, dtype=np.int32) * 2
+    q_pos = np.array([23, 24, 11], dtype=np.int32)
+    slopes = oracle.alibi_slopes(Hq)
+    a = oracle.attn_alibi(Q, q_pos, K, V, k_pos, slopes)
+    b = oracle.attn_alibi(Q, q_pos + 1000, K, V, k_pos + 1000, slopes)
+    assert np.allclose(a, b, rtol=0, atol=1e-13)
+    # slope 0 at position 0 everywhere: no bias, nothing hidden, and the rotary path's rotation is the identity
+    z = np.zeros(nk, dtype=np.int32)
+    assert np.allclose(oracle.attn_alibi(Q, z[:nq], K, V, z, np.zeros(Hq)), oracle.attn(Q, z[:nq], K, V, z), rtol=0, atol=1e-13)
+    # a steeper slope moves weight towards the nearest visible key (V = key index makes that measurable)
+    Vi = np.broadcast_to(k_pos[:, None, None].astype(np.float64), (nk, Hkv, d)).copy()
+    flat = oracle.attn_alibi(np.zeros((1, Hq, d)), q_pos[:1], K, Vi, k_pos, np.full(Hq, 0.01))
+    steep = oracle.attn_alibi(np.zeros((1, Hq, d)), q_pos[:1], K, Vi, k_pos, np.full(Hq, 2.0))
+    assert np.all(steep > flat) and np.all(steep <= 22.0)
