@@ -99,6 +99,8 @@ def main() -> int:
     ap.add_argument("--host-tier", choices=["kernel", "engine"], default=None,
                     help="keep the modules in pinned host memory (Sec. 4.1) and bring them in at every use: 'kernel' = "
                          "the assembly kernel loads them over the host link, 'engine' = copy-engine transfers")
+    ap.add_argument("--alibi", action="store_true",
+                    help="position as a linear bias on the scores (Sec. 4.2, ALiBi) instead of a rotation; no CPU baseline")
     ap.add_argument("--overlap", action="store_true",
                     help="assemble layer l+1 on a second stream while layer l's attention runs")
     args = ap.parse_args()
@@ -127,6 +129,9 @@ def main() -> int:
 
     # ---------------- resident inputs
     pc = pcb.PromptCache.for_workload(w)
+    if args.alibi:
+        pc.pc_set_alibi(pcb.pc_alibi_slopes(w.n_q_heads))
+        args.no_cpu_baseline = True
     if args.host_tier:
         pc.pc_host_pool_reserve(L * sum(2 * (w.sizes[m] * w.row_bytes + 512) for m in used))
         pc.pc_set_host_copy_mode(pcb.PC_HOST_COPY_ENGINE if args.host_tier == "engine" else pcb.PC_HOST_READ_KERNEL)
@@ -294,7 +299,7 @@ def main() -> int:
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "kv_path": "modules read in place" if in_place else "packed copy",
                    "module_tier": ("host memory, " + ("loaded by the assembly kernel" if args.host_tier == "kernel" else "copy engine")) if args.host_tier else "HBM pool",
-                   "overlap": bool(args.overlap), "layers": L, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
+                   "overlap": bool(args.overlap), "position_encoding": "alibi" if args.alibi else "rope", "layers": L, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
                    "head_dim": w.head_dim, "prompts": B, "module_tokens": n_mod if B <= 4 else [n_mod[0], "..."],
                    "uncached_tokens": n_new[0], "attn_launch": {"kv_splits": launch[0], "workgroups": launch[1],
                                                               "waves_per_wg": launch[2]}},

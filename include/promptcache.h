@@ -268,6 +268,26 @@ int pc_prefill_attn_batched(pc_ctx *ctx, int layer, const void *Q_new, const int
                             void *out, void *stream);
 
 /*
+ * Sec. 4.2, ALiBi: models that encode position as a linear bias on the attention scores
+ * instead of a rotation.  The bias follows the given position IDs:
+ *     score(q, k) = Q.K / sqrt(d)  -  slope[head] * (pos_q - pos_k),   visible iff pos_k <= pos_q.
+ *
+ * pc_set_alibi     slopes: HOST float[n_q_heads], finite and >= 0 (PC_E_BADARG otherwise); the
+ *                  context switches to the linear bias: pc_prefill_attn* add it and use Q as it
+ *                  is, pc_append_kv*, pc_assemble_append_kv_batched and pc_fill_params store keys
+ *                  unrotated (modules must then be stored unrotated too).  slopes == NULL switches
+ *                  back to rotation.  A set-up call: it copies synchronously and must not overlap
+ *                  with attention calls in flight on the context.
+ *                  bf16 contexts need head_dim 128 for attention in this mode
+ *                  (PC_E_UNSUPPORTED from the attention calls otherwise); fp32: any even head_dim.
+ * pc_alibi_slopes  the sequence that encoding's authors define (host helper, no context):
+ *                  n a power of two: 2^(-8/n), 2^(-16/n), ...; otherwise the sequence of the
+ *                  largest power of two below n followed by the odd members of the next one.
+ */
+int pc_set_alibi(pc_ctx *ctx, const float *slopes);
+int pc_alibi_slopes(int n_heads, float *slopes);
+
+/*
  * Sec. 4.1: prompt modules kept in CPU memory (capacity of host DRAM instead of HBM, at the
  * price of a host-to-device copy at every use; Sec. 5.4 measures that copy).
  *

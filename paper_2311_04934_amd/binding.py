@@ -25,7 +25,7 @@ EXPORTS = [
     "pc_schema_layout", "pc_uncached_positions", "pc_check_selection", "pc_bytes_per_token",
     "pc_module_info", "pc_pool_usage", "pc_last_attn_launch", "pc_profile_enable", "pc_profile_read",
     "pc_profile_read_each", "pc_set_module_params", "pc_fill_params",
-    "pc_host_pool_reserve", "pc_store_module_host", "pc_set_host_copy_mode",
+    "pc_host_pool_reserve", "pc_store_module_host", "pc_set_host_copy_mode", "pc_set_alibi", "pc_alibi_slopes",
 ]
 PROF_GATHER, PROF_APPEND, PROF_ATTN, PROF_COMBINE, PROF_ROPE = range(5)
 PC_POS_NONE = 0x7FFFFFFF
@@ -76,6 +76,8 @@ def lib() -> ctypes.CDLL:
     L.pc_host_pool_reserve.argtypes = [vp, ctypes.c_size_t]
     L.pc_store_module_host.argtypes = [vp, i, i, vp, vp, i, i]
     L.pc_set_host_copy_mode.argtypes = [vp, i]
+    L.pc_set_alibi.argtypes = [vp, vp]
+    L.pc_alibi_slopes.argtypes = [i, vp]
     L.pc_set_module_params.argtypes = [vp, i, i, vp, vp]
     L.pc_fill_params.argtypes = [vp, i, vp, i, i, vp, vp, vp, vp, vp, vp, vp, vp, i, vp]
     L.pc_schema_layout.argtypes = [i, vp, vp, vp]
@@ -96,6 +98,12 @@ def lib() -> ctypes.CDLL:
             fn.restype = ctypes.c_int
     _lib = L
     return L
+
+
+def pc_alibi_slopes(n_heads: int) -> np.ndarray:
+    out = np.zeros(max(int(n_heads), 1), dtype=np.float32)
+    _check(lib().pc_alibi_slopes(int(n_heads), _np_ptr(out)), "pc_alibi_slopes")
+    return out[:n_heads]
 
 
 def strerror(status: int) -> str:
@@ -293,6 +301,14 @@ class PromptCache:
 
     def pc_set_host_copy_mode(self, mode: int) -> None:
         _check(lib().pc_set_host_copy_mode(self._ctx, int(mode)), "pc_set_host_copy_mode")
+
+    def pc_set_alibi(self, slopes) -> None:
+        """slopes: n_q_heads floats (host), or None to return to rotary encoding."""
+        if slopes is None:
+            _check(lib().pc_set_alibi(self._ctx, None), "pc_set_alibi")
+            return
+        a = np.ascontiguousarray(np.asarray(slopes, dtype=np.float32))
+        _check(lib().pc_set_alibi(self._ctx, _np_ptr(a)), "pc_set_alibi")
 
     def pc_set_module_params(self, module_id: int, offsets: Sequence[int], lens: Sequence[int]) -> None:
         o, l = _ints(offsets), _ints(lens)

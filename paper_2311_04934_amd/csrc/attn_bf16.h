@@ -33,6 +33,7 @@ struct AttnParams {
     float2 *part_ml;         // [n_splits][total_q][Hq]
     const float2 *rope;      // [max_pos][D/2]
     const float2 *rope_t;    // [D/2][max_pos]
+    const float *alibi;      // [Hq] slopes of the linear bias, or nullptr: rotation
     int max_pos;
     int Hq, Hkv, G;
     int n_splits;

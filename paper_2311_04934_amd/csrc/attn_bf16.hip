@@ -481,8 +481,10 @@ int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const i
     for (int s = 0; s < batch.n_seqs; ++s) max_kv = batch.seq[s].n_kv > max_kv ? batch.seq[s].n_kv : max_kv;
     const bool fits_u32 = max_kv * (long)Hkv * D * 2 < (1L << 32);   // the wide kernel uses 32-bit row offsets
     // a range table is read by the DMA-staged kernel only (32-bit offsets there are per range, checked by the caller)
-    if (tab && D != 128) return PC_E_UNSUPPORTED;
-    bool wide = D == 128 && (tab || (max_row_tiles >= kWideMinRowTiles && fits_u32));
+    // the linear bias (ALiBi) is implemented in the DMA-staged kernel only
+    if ((tab || ctx->use_alibi) && D != 128) return PC_E_UNSUPPORTED;
+    if (ctx->use_alibi && !tab && !fits_u32) return PC_E_UNSUPPORTED;
+    bool wide = D == 128 && (tab || ctx->use_alibi || (max_row_tiles >= kWideMinRowTiles && fits_u32));
     const int NW = wide ? 4 : (max_row_tiles <= 4 ? 4 : 8);
     const int tiles_per_wg = wide ? kWideRowTilesPerWg : NW;
     const int rb_max = (max_row_tiles + tiles_per_wg - 1) / tiles_per_wg;
@@ -514,6 +516,7 @@ int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const i
     p.part_ml = reinterpret_cast<float2 *>(reinterpret_cast<uint8_t *>(ctx->scratch) + (((size_t)n_splits * total_q * Hq * D * sizeof(uint16_t) + 255) & ~(size_t)255));
     p.rope = ctx->rope_table;
     p.rope_t = ctx->rope_table_t;
+    p.alibi = ctx->use_alibi ? ctx->alibi : nullptr;
     p.max_pos = ctx->cfg.max_pos;
     p.Hq = Hq;
     p.Hkv = Hkv;

@@ -87,7 +87,9 @@ struct NoSegTable {
 };
 
 // PAGED: the keys come from a list of row ranges (see KvSegTable) instead of one packed buffer.
-template <int NQT, int NW, bool PAGED>
+// ALIBI: position enters as the linear bias -slope[head] * (pos_q - pos_k) on the scores (Sec. 4.2 of the
+// paper: the bias follows the given position IDs) instead of a rotation of Q; keys are stored unrotated.
+template <int NQT, int NW, bool PAGED, bool ALIBI>
 __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams p,
                                                                 const std::conditional_t<PAGED, KvSegTable, NoSegTable> tab)
 {
@@ -139,6 +141,12 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
         qt[x].valid = act && qt[x].qi < seq.n_q;
         qt[x].qpos = qt[x].valid ? p.q_pos[seq.q_begin + qt[x].qi] : kPosInf;
     }
+
+    // ALIBI: this wave's slope in the log2 domain.  The head is the same for the wave's 32 queries, so the
+    // load is a scalar one (it does not touch the vector-memory counter the copies are tracked with).
+    float slope2 = 0.f;
+    if constexpr (ALIBI) slope2 = p.alibi[__builtin_amdgcn_readfirstlane(qt[0].head)] * 1.4426950408889634f;
+    static_assert(!ALIBI || NQT == 1, "one head, hence one slope, per wave");
 
     const size_t kv_row_stride = (size_t)p.Hkv * D;  // elements
     const uint16_t *k_base = PAGED ? nullptr : p.k + (size_t)seq.kv_begin * kv_row_stride + (size_t)kvh * D;
@@ -299,7 +307,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
         // consecutive positions, so one pair index is a contiguous 256-byte read for them)
         float2 cs[NQT][KB / 2][8];
 #pragma unroll
-        for (int x = 0; x < NQT; ++x) {
+        for (int x = 0; x < NQT && !ALIBI; ++x) {
             int tpos = qt[x].qpos;
             tpos = tpos < 0 ? 0 : (tpos >= p.max_pos ? p.max_pos - 1 : tpos);
             const float2 *tcol = p.rope_t + tpos;
@@ -323,8 +331,13 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
                     const uint32_t wl = lo[e >> 1], wh = hi[e >> 1];
                     const float xl = bf16_bits_to_f32((e & 1) ? (wl >> 16) : (wl & 0xffffu));
                     const float xh = bf16_bits_to_f32((e & 1) ? (wh >> 16) : (wh & 0xffffu));
-                    olo[e] = (__bf16)((xl * cs[x][kb][e].x - xh * cs[x][kb][e].y) * p.q_scale);
-                    ohi[e] = (__bf16)((xh * cs[x][kb][e].x + xl * cs[x][kb][e].y) * p.q_scale);
+                    if constexpr (ALIBI) {   // Q as it is, scaled
+                        olo[e] = (__bf16)(xl * p.q_scale);
+                        ohi[e] = (__bf16)(xh * p.q_scale);
+                    } else {
+                        olo[e] = (__bf16)((xl * cs[x][kb][e].x - xh * cs[x][kb][e].y) * p.q_scale);
+                        ohi[e] = (__bf16)((xh * cs[x][kb][e].x + xl * cs[x][kb][e].y) * p.q_scale);
+                    }
                 }
                 qf[x][kb] = olo;
                 qf[x][kb + KB / 2] = ohi;
@@ -336,6 +349,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
 #pragma unroll
     for (int x = 1; x < NQT; ++x) min_qpos = pc_imin(min_qpos, qt[x].qpos);
     const int wave_min_qpos = wave_min_i32(min_qpos);
+    const int bias_ref = wave_min_qpos;   // ALIBI: origin of the per-key bias (an idle wave's value is never used)
 
     // ---- per-lane LDS offsets of the MFMA operand fragments
     // K (A operand of K.Q): key = col of the sub-tile, chunk 2*kb+hh, swizzled by key & 15
@@ -584,6 +598,23 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
         }
     };
 
+    // ALIBI: s += slope * (pos_k - ref) in the log2 domain, ref = the wave's smallest query position.  The
+    // term -slope * (pos_q - ref) that completes -slope * (pos_q - pos_k) is the same for every key of a
+    // query and cancels in the softmax, so only a per-key value is added.  Differences are taken in
+    // integers first: the bias is exact where it is small, i.e. for the keys that carry weight.
+    auto apply_bias = [&](f32x16 (&s)[NQT], int buf, int sub) {
+        const lds_u8 *pp = lds + LDS_POS + buf * KT * 4;
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+            const int key0 = sub * 32 + 8 * i4 + 4 * hh;
+            const u32x4 kp = *reinterpret_cast<const lds_u32x4 *>(pp + key0 * 4);
+#pragma unroll
+            for (int x = 0; x < NQT; ++x)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) s[x][i4 * 4 + e] += slope2 * (float)((int)kp[e] - bias_ref);
+        }
+    };
+
     auto rescale = [&]() {
         bool need = false;
 #pragma unroll
@@ -667,12 +698,14 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
             __syncthreads();
             const bool mask_next = has_next ? tile_needs_mask(t + 1) : false;
 
+            if constexpr (ALIBI) apply_bias(sc[0], buf, 0);
             if (mask_cur) apply_mask(sc[0], buf, 0, n_valid);
             rescale();
             // P.V of tile t-1's second half | K.Q of this tile's second half | softmax of its first half;
             // the copies of tile t+3 are issued here
             step(pf[1], k_cur + 32 * ROW_BYTES, sc[1], sc[0], pf[0], v_cur, true, t + 3, false, 0);
 
+            if constexpr (ALIBI) apply_bias(sc[1], buf, 1);
             if (mask_cur) apply_mask(sc[1], buf, 1, n_valid);
             rescale();
             // P.V of this tile's first half | K.Q of tile t+1's first half | softmax of this tile's second half;
@@ -756,11 +789,11 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
     }
 }
 
-template <int NQT, int NW, bool PAGED, typename Tab>
+template <int NQT, int NW, bool PAGED, bool ALIBI, typename Tab>
 int launch_one(pc_ctx *ctx, AttnParams &p, int n_blocks, hipStream_t stream, const Tab &tab)
 {
     static bool attr_set[16] = {false};
-    auto kern = attn_bf16_dma_kernel<NQT, NW, PAGED>;
+    auto kern = attn_bf16_dma_kernel<NQT, NW, PAGED, ALIBI>;
     if (!attr_set[ctx->device & 15]) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 LDS_TOTAL) != hipSuccess)
@@ -775,8 +808,12 @@ int launch_one(pc_ctx *ctx, AttnParams &p, int n_blocks, hipStream_t stream, con
 
 int launch_attn_bf16_wide(pc_ctx *ctx, attn::AttnParams &p, int n_blocks, hipStream_t stream, const KvSegTable *tab)
 {
-    if (tab) return launch_one<1, 8, true>(ctx, p, n_blocks, stream, *tab);
-    return launch_one<1, 8, false>(ctx, p, n_blocks, stream, NoSegTable{0});
+    if (p.alibi) {
+        if (tab) return launch_one<1, 8, true, true>(ctx, p, n_blocks, stream, *tab);
+        return launch_one<1, 8, false, true>(ctx, p, n_blocks, stream, NoSegTable{0});
+    }
+    if (tab) return launch_one<1, 8, true, false>(ctx, p, n_blocks, stream, *tab);
+    return launch_one<1, 8, false, false>(ctx, p, n_blocks, stream, NoSegTable{0});
 }
 
 }  // namespace pc

@@ -35,6 +35,7 @@ struct F32Params {
     const int32_t *kv_pos;
     float *out;
     const float2 *rope;
+    const float *alibi;  // per-head slopes, or nullptr: rotation
     int max_pos, Hq, Hkv, d;
     int q_lo, q_hi;  // query rows covered by this launch
     float scale;
@@ -63,7 +64,11 @@ __global__ __launch_bounds__(kWaves * 64) void attn_f32_kernel(const F32Params p
 
     // rotate the query at its position ID, fold in 1/sqrt(d)
     const int qpos = active ? p.q_pos[q_row] : 0;
-    if (active) {
+    const float slope = (active && p.alibi) ? p.alibi[h] : 0.f;
+    if (active && p.alibi) {   // linear bias (Sec. 4.2): the query is used as it is
+        const float *qr = p.q + ((size_t)q_row * p.Hq + h) * d;
+        for (int i = lane; i < d; i += 64) s_q[wave][i] = qr[i] * p.scale;
+    } else if (active) {
         int tp = qpos < 0 ? 0 : (qpos >= p.max_pos ? p.max_pos - 1 : qpos);
         const float2 *trow = p.rope + (size_t)tp * half;
         const float *qr = p.q + ((size_t)q_row * p.Hq + h) * d;
@@ -94,7 +99,7 @@ __global__ __launch_bounds__(kWaves * 64) void attn_f32_kernel(const F32Params p
             const float *kr = kb + (size_t)j * row_stride;
             float dot = 0.f;
             for (int c = 0; c < d; ++c) dot = fmaf(s_q[wave][c], kr[c], dot);
-            s = dot;
+            s = dot - slope * (float)(qpos - pb[j]);   // slope 0 under rotation
         }
         const float tmax = wave_max_f(s);
         if (tmax == -INFINITY) continue;  // no visible key in these 64 (uniform)
@@ -142,6 +147,7 @@ int launch_attn_f32(pc_ctx *ctx, const AttnBatch &batch, const float *q, const i
     F32Params p;
     p.q = q; p.q_pos = q_pos; p.k = k; p.v = v; p.kv_pos = kv_pos; p.out = out;
     p.rope = ctx->rope_table;
+    p.alibi = ctx->use_alibi ? ctx->alibi : nullptr;
     p.max_pos = ctx->cfg.max_pos;
     p.Hq = ctx->cfg.n_q_heads; p.Hkv = ctx->cfg.n_kv_heads; p.d = d;
     p.q_lo = q_lo; p.q_hi = q_hi;

@@ -66,6 +66,9 @@ struct pc_ctx {
     int32_t *iota = nullptr;  // device, 0, 1, .. max_pos-1: position IDs of module rows read in place
     float2 *rope_table_t = nullptr;  // the same values as [head_dim/2][max_pos]: coalesced when lanes hold consecutive positions
 
+    float *alibi = nullptr;    // device [n_q_heads] slopes of the linear bias (Sec. 4.2); allocated always
+    bool use_alibi = false;    // position encoding in force: false = rotation (RoPE), true = linear bias (ALiBi)
+
     float *scratch = nullptr;  // device, split-KV partials
     size_t scratch_bytes = 0;
 

@@ -61,10 +61,10 @@ int launch_gather_append(pc_ctx *ctx, const FusedKvArgs &args, uint8_t *out_k, u
     if (ctx->cfg.dtype == PC_F32)
         return launch_kernel(ctx, kProfGather, gather_append_kernel<float>, dim3(blocks), dim3(kv::kThreads), 0, stream,
                              args, out_k, out_v, out_pos, static_cast<const float *>(k_new),
-                             static_cast<const float *>(v_new), q_pos, n_kv_heads, head_dim, ctx->rope_table, max_pos);
+                             static_cast<const float *>(v_new), q_pos, n_kv_heads, head_dim, ctx->use_alibi ? nullptr : ctx->rope_table, max_pos);
     return launch_kernel(ctx, kProfGather, gather_append_kernel<uint16_t>, dim3(blocks), dim3(kv::kThreads), 0, stream,
                          args, out_k, out_v, out_pos, static_cast<const uint16_t *>(k_new),
-                         static_cast<const uint16_t *>(v_new), q_pos, n_kv_heads, head_dim, ctx->rope_table, max_pos);
+                         static_cast<const uint16_t *>(v_new), q_pos, n_kv_heads, head_dim, ctx->use_alibi ? nullptr : ctx->rope_table, max_pos);
 }
 
 }  // namespace pc

@@ -144,11 +144,24 @@ __device__ __forceinline__ void append_row(const AppendSeg *seg, int n_segs, int
     const int half = d >> 1;
     const int row_elems = n_kv_heads * d;
     const int p = mode >= 0 ? mode + r : q_pos[src];
-    const float2 *trow = table + (size_t)clamp_pos(p, max_pos) * half;
     const T *ks = k_new + (size_t)src * row_elems;
     const T *vs = v_new + (size_t)src * row_elems;
     T *kd = asm_k + (size_t)dst * row_elems;
     T *vd = asm_v + (size_t)dst * row_elems;
+    if (table == nullptr) {   // linear-bias models (Sec. 4.2, ALiBi): keys carry no position, both rows are copies
+        if ((row_elems * sizeof(T)) & 15) {
+            for (int e = threadIdx.x; e < row_elems; e += kThreads) { kd[e] = ks[e]; vd[e] = vs[e]; }
+        } else {
+            const int n_vec = (int)((size_t)row_elems * sizeof(T) >> 4);
+            for (int i = threadIdx.x; i < n_vec; i += kThreads) {
+                reinterpret_cast<u32x4 *>(kd)[i] = reinterpret_cast<const u32x4 *>(ks)[i];
+                reinterpret_cast<u32x4 *>(vd)[i] = reinterpret_cast<const u32x4 *>(vs)[i];
+            }
+        }
+        if (threadIdx.x == 0) asm_pos[dst] = p;
+        return;
+    }
+    const float2 *trow = table + (size_t)clamp_pos(p, max_pos) * half;
     if (d & 15) {   // odd head sizes (fp32 only): element by element
         for (int e = threadIdx.x; e < n_kv_heads * half; e += kThreads) {
             const int h = e / half, i = e % half;

@@ -66,7 +66,7 @@ int launch_append(pc_ctx *ctx, const AppendArgs &args, const void *k_new, const 
 {
     if (args.total_rows <= 0) return PC_OK;
     const int n_kv_heads = ctx->cfg.n_kv_heads, head_dim = ctx->cfg.head_dim, max_pos = ctx->cfg.max_pos;
-    const float2 *table = ctx->rope_table;
+    const float2 *table = ctx->use_alibi ? nullptr : ctx->rope_table;   // linear-bias models store keys unrotated
     if (ctx->cfg.dtype == PC_F32)
         return launch_kernel(ctx, kProfAppend, append_kernel<float>, dim3(args.total_rows), dim3(kv::kThreads), 0, stream, args,
                              static_cast<const float *>(k_new), static_cast<const float *>(v_new), q_pos,

@@ -6,6 +6,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <cmath>
 #include <new>
 
 #include "common.h"
@@ -227,6 +228,7 @@ int pc_create(const pc_config *cfg, pc_ctx **out_ctx)
                 for (int i = 0; i < half; ++i) host_t[(size_t)i * cfg->max_pos + p] = host[(size_t)p * half + i];
             ok = hipMemcpy(ctx->rope_table_t, host_t.data(), n_entries * sizeof(float2), hipMemcpyHostToDevice) == hipSuccess;
         }
+        if (ok) ok = hipMalloc(reinterpret_cast<void **>(&ctx->alibi), (size_t)cfg->n_q_heads * sizeof(float)) == hipSuccess;
         if (ok) ok = hipMalloc(reinterpret_cast<void **>(&ctx->iota), (size_t)cfg->max_pos * sizeof(int32_t)) == hipSuccess;
         if (ok) {
             std::vector<int32_t> ids(cfg->max_pos);
@@ -241,6 +243,7 @@ int pc_create(const pc_config *cfg, pc_ctx **out_ctx)
         if (ctx->rope_table) (void)hipFree(ctx->rope_table);
         if (ctx->rope_table_t) (void)hipFree(ctx->rope_table_t);
         if (ctx->iota) (void)hipFree(ctx->iota);
+        if (ctx->alibi) (void)hipFree(ctx->alibi);
         delete ctx;
         return PC_E_HIP;
     }
@@ -313,6 +316,7 @@ int pc_destroy(pc_ctx *ctx)
     if (ctx->rope_table) (void)hipFree(ctx->rope_table);
     if (ctx->rope_table_t) (void)hipFree(ctx->rope_table_t);
     if (ctx->iota) (void)hipFree(ctx->iota);
+    if (ctx->alibi) (void)hipFree(ctx->alibi);
     if (ctx->host_pool) (void)hipHostFree(ctx->host_pool);
     delete ctx;
     return PC_OK;
@@ -353,6 +357,38 @@ int pc_store_module(pc_ctx *ctx, int layer, int module_id, const void *K, const 
         table.emplace(module_id, e);
         ctx->pool_used = e.v_offset + bytes;
     }
+    return PC_OK;
+}
+
+int pc_alibi_slopes(int n_heads, float *slopes)
+{
+    if (n_heads <= 0 || !slopes) return PC_E_BADARG;
+    // largest power of two not above n_heads gets the sequence 2^(-8 i / p), i = 1..p; the remaining
+    // heads take the odd members of the sequence for 2p
+    int p = 1;
+    while (p * 2 <= n_heads) p *= 2;
+    for (int h = 0; h < n_heads; ++h) {
+        const double e = h < p ? 8.0 * (h + 1) / p : 4.0 * (2 * (h - p) + 1) / p;
+        slopes[h] = (float)exp2(-e);
+    }
+    return PC_OK;
+}
+
+int pc_set_alibi(pc_ctx *ctx, const float *slopes)
+{
+    if (!ctx) return PC_E_BADARG;
+    if (!slopes) {
+        ctx->use_alibi = false;
+        return PC_OK;
+    }
+    for (int h = 0; h < ctx->cfg.n_q_heads; ++h)
+        if (!(slopes[h] >= 0.f) || !std::isfinite(slopes[h])) return PC_E_BADARG;
+    if (hipSetDevice(ctx->device) != hipSuccess ||
+        hipMemcpy(ctx->alibi, slopes, (size_t)ctx->cfg.n_q_heads * sizeof(float), hipMemcpyHostToDevice) != hipSuccess) {
+        (void)hipGetLastError();
+        return PC_E_HIP;
+    }
+    ctx->use_alibi = true;
     return PC_OK;
 }
 

@@ -636,6 +636,106 @@ def test_host_tier_error_paths():
         r.close()
 
 
+# ------------------------------------------------------------------ linear bias on position IDs (Sec. 4.2, ALiBi)
+def _alibi_run(w, layer, q_sample, in_place=False, slopes=None):
+    """Modules and new tokens hold unrotated keys; the context adds -slope*(pos_q - pos_k) to the scores.
+    Expected: the oracle's attn_alibi over its own concatenation."""
+    c = build_case(w, layer, encode_keys=False)
+    r = GpuRunner(c)
+    dev = r.dev
+    if slopes is None:
+        slopes = pcb.pc_alibi_slopes(w.n_q_heads)
+        assert np.allclose(slopes, oracle.alibi_slopes(w.n_q_heads), rtol=1e-7, atol=0)
+    slopes = np.asarray(slopes, dtype=np.float32)
+    r.pc.pc_set_alibi(slopes)
+    B = len(c.prompts)
+    n_mod = [sum(w.sizes[m] for m in p.module_ids) for p in c.prompts]
+    n_new = [len(p.q_pos) for p in c.prompts]
+    lens = [a + b for a, b in zip(n_mod, n_new)]
+    kv_off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    q_off = np.concatenate([[0], np.cumsum(n_new)]).astype(np.int64)
+    Q = torch.cat([p.Q for p in c.prompts]).to(dev)
+    Kn = torch.cat([p.K_new for p in c.prompts]).to(dev)
+    Vn = torch.cat([p.V_new for p in c.prompts]).to(dev)
+    qp = torch.from_numpy(np.concatenate([p.q_pos for p in c.prompts])).to(dev)
+    ids = [p.module_ids for p in c.prompts]
+    out = torch.full((int(q_off[-1]), w.n_q_heads, w.head_dim), float("nan"), dtype=w.torch_dtype, device=dev)
+    rows = int(q_off[-1]) if in_place else int(kv_off[-1])
+    bK = torch.full((rows, w.n_kv_heads, w.head_dim), float("nan"), dtype=w.torch_dtype, device=dev)
+    bV = torch.full_like(bK, float("nan"))
+    bP = torch.full((rows,), -7, dtype=torch.int32, device=dev)
+    if in_place:
+        r.pc.pc_append_kv_batched(layer, Kn, Vn, qp, q_off, bK, bV, bP, q_off, [0] * B)
+        r.pc.pc_prefill_attn_shared_batched(layer, Q, qp, q_off, ids, bK, bV, out)
+    else:
+        r.pc.pc_assemble_append_kv_batched(layer, ids, Kn, Vn, qp, q_off, bK, bV, bP, kv_off)
+        r.pc.pc_prefill_attn_batched(layer, Q, qp, q_off, bK, bV, bP, kv_off, lens, out)
+    torch.cuda.synchronize()
+    launch = r.pc.pc_last_attn_launch()
+    hK, o = bK.cpu(), out.cpu()
+    r.close()
+    assert not torch.isnan(o).any()
+    rng = np.random.default_rng(9)
+    for b in range(B):
+        if n_new[b] == 0:
+            continue
+        pcx = c.prompts[b]
+        # the new tokens' keys are stored as they came, bit for bit
+        tail = hK[q_off[b]:q_off[b + 1]] if in_place else hK[kv_off[b] + n_mod[b]:kv_off[b + 1]]
+        assert np.array_equal(as_words(tail), as_words(pcx.K_new)), "keys must not be rotated under the linear bias"
+        Ks = [to_f64(c.mod_K[m]) for m in pcx.module_ids] + [to_f64(pcx.K_new)]
+        Vs = [to_f64(c.mod_V[m]) for m in pcx.module_ids] + [to_f64(pcx.V_new)]
+        P = np.concatenate([np.arange(c.starts[m], c.starts[m] + w.sizes[m]) for m in pcx.module_ids] + [pcx.q_pos]).astype(np.int32)
+        rows_q = np.arange(n_new[b])
+        if q_sample and n_new[b] > q_sample:
+            rows_q = np.unique(np.concatenate([[0, n_new[b] - 1], rng.choice(n_new[b], size=q_sample - 2, replace=False)]))
+        ref = oracle.attn_alibi(to_f64(pcx.Q)[rows_q], pcx.q_pos[rows_q], np.concatenate(Ks), np.concatenate(Vs), P,
+                                slopes.astype(np.float64))
+        err, rel = attn_errors(o[q_off[b]:q_off[b + 1]][rows_q], ref)
+        print(f"[{w.name}/alibi{'/in-place' if in_place else ''}] prompt {b}: max abs err {err:.3e}, rel L2 {rel:.3e}, "
+              f"|ref|max {np.abs(ref).max():.3e}, launch={launch}", flush=True)
+        assert err <= TOL_ABS[w.dtype] * max(1.0, float(np.abs(ref).max())), (err, rel)
+        assert rel <= TOL_REL[w.dtype], (err, rel)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("in_place", [False, True])
+def test_alibi_small_ragged_batch(dtype, in_place):
+    if dtype == "f32" and in_place:
+        pytest.skip("modules are read in place by the bf16 kernel only")
+    hq, hkv, d = (8, 2, 128) if dtype == "bf16" else (6, 2, 64)
+    w = W.custom("alibi_small", dtype, hq, hkv, d, [300, 64, 90, 70, 120, 33], [-1, 0, 0, 0, 1, 1],
+                 [W.Prompt([0, 1, 4], 40), W.Prompt([4, 2, 0], 17), W.Prompt([], 9), W.Prompt([3, 0, 5], 64),
+                  W.Prompt([0], 1), W.Prompt([5], 70)], max_pos=1024)
+    _alibi_run(w, 0, None, in_place=in_place)
+
+
+def test_alibi_text_inside_a_gap_and_flat_slopes():
+    """Uncached text placed after the first module sees only earlier positions; slope 0 on some heads must give
+    plain (position-free) attention there."""
+    w = W.custom("alibi_gap", "bf16", 8, 4, 128, [128, 200, 96], None,
+                 [W.Prompt([0, 2], 24, gap_after=0, n_gap=40), W.Prompt([2, 1, 0], 33)], max_pos=1024)
+    _alibi_run(w, 0, None, slopes=[0.0, 0.5, 0.0, 0.01, 1.5, 0.25, 0.0, 0.003])
+
+
+def test_alibi_bf16_head_dim_64_is_refused():
+    w = W.custom("alibi_d64", "bf16", 8, 8, 64, [64], None, [W.Prompt([0], 8)], max_pos=256)
+    c = build_case(w, 0, encode_keys=False)
+    r = GpuRunner(c)
+    try:
+        r.pc.pc_set_alibi(pcb.pc_alibi_slopes(8))
+        with pytest.raises(pcb.PcError) as e:
+            r.serve(0)
+        assert e.value.status == -9
+        with pytest.raises(pcb.PcError) as e:
+            r.pc.pc_set_alibi([0.5] * 7 + [-1.0])
+        assert e.value.status == -1
+        r.pc.pc_set_alibi(None)          # back to rotation: the same call now works
+        r.serve(0)
+    finally:
+        r.close()
+
+
 # ------------------------------------------------------------------ run-to-run determinism
 def _determinism_run(w, in_place, n_runs=60):
     """The same attention launched many times back to back, with no host synchronisation between the
@@ -732,3 +832,8 @@ def test_config5_batched_serving_modules_in_place_full_size_sampled():
 def test_config3_long_doc_8k_host_tier_full_size_sampled(mode):
     w = W.long_doc_8k()
     _batched_run(w, 0, 12, fused=True, host_modules=w.used_module_ids(), host_mode=mode)
+
+
+@pytest.mark.parametrize("in_place", [False, True])
+def test_config3_long_doc_8k_alibi_full_size_sampled(in_place):
+    _alibi_run(W.long_doc_8k(), 31, 12, in_place=in_place)
