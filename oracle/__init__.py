@@ -226,6 +226,28 @@ def fill_param(K, V, pos, row0: int, length: int, K_arg_raw, V_arg, base: float 
     return K, V, pos
 
 
+def resolve_scaffolds(import_ids: Sequence[int], scaffolds: Sequence[tuple]) -> list:
+    """Scaffolding (Sec. 3.3, "attention masking effect"): a scaffold is a set of modules that was also encoded
+    jointly, so that its members share one attention span.  When a prompt imports every member of a
+    scaffold, the jointly encoded states override the members' own.
+
+    scaffolds: sequence of (member_ids, override_ids), override_ids[i] naming the stored states that stand in
+    for member_ids[i].  Returns the import list with each overridden id replaced where it stood.  Scaffolds
+    are taken in the order given; one that would touch a member an earlier scaffold has already overridden
+    is skipped (the paper does not say; first complete scaffold wins).
+    """
+    ids = list(import_ids)
+    imported = set(ids)
+    taken = set()
+    for members, overrides in scaffolds:
+        assert len(members) == len(overrides) and len(members) > 0
+        if all(m in imported for m in members) and not any(m in taken for m in members):
+            for m, o in zip(members, overrides):
+                ids = [o if x == m else x for x in ids]
+                taken.add(m)
+    return ids
+
+
 def bytes_per_token(n_layers: int, n_kv_heads: int, head_dim: int, elem_bytes: int) -> int:
     """K+V bytes one cached token occupies over all layers (Table 2's closed form)."""
     return int(_load().orc_bytes_per_token(n_layers, n_kv_heads, head_dim, elem_bytes))

@@ -62,6 +62,26 @@ class ToyModel:
             h = h + o.reshape(n, -1) @ self.Wo[layer]
         return states
 
+    # ---- scaffolding (Sec. 3.3): several modules encoded together, sharing one attention span
+    def encode_scaffold(self, members):
+        """members: list of (tokens, start_pos).  The members' tokens run as ONE module at their own schema
+        positions; returns, per member, per-layer (K encoded, V) cut out of the joint result."""
+        toks = np.concatenate([np.asarray(t) for t, _ in members])
+        pos = np.concatenate([np.arange(s0, s0 + len(t)) for t, s0 in members]).astype(np.int32)
+        same = np.zeros(len(toks), dtype=np.int32)
+        h = self.emb[toks]
+        joint = []
+        for layer in range(self.L):
+            q, k, v = self._qkv(layer, h)
+            o, k_enc = full_masked(q, k, v, pos, same, self.base)
+            joint.append((k_enc, v))
+            h = h + o.reshape(len(toks), -1) @ self.Wo[layer]
+        out, row = [], 0
+        for t, _ in members:
+            out.append([(k[row:row + len(t)], v[row:row + len(t)]) for k, v in joint])
+            row += len(t)
+        return out
+
     # ---- path B, step 2: cached inference (Sec. 3.4)
     def forward_cached(self, module_states, module_starts, new_tokens, new_pos) -> np.ndarray:
         """module_states[m][layer] = (K_enc, V); modules are concatenated in the order given."""

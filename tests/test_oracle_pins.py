@@ -564,3 +564,59 @@ def test_alibi_depends_on_position_differences_only_and_reduces_to_plain_attenti
     flat = oracle.attn_alibi(np.zeros((1, Hq, d)), q_pos[:1], K, Vi, k_pos, np.full(Hq, 0.01))
     steep = oracle.attn_alibi(np.zeros((1, Hq, d)), q_pos[:1], K, Vi, k_pos, np.full(Hq, 2.0))
     assert np.all(steep > flat) and np.all(steep <= 22.0)
+
+
+# ------------------------------------------------------------------ scaffolding (Sec. 3.3)
+def _parse_scaffolds(text):
+    out = []
+    for part in text.split("/"):
+        m, o = part.strip().split(">")
+        out.append(([int(t) for t in m.split(",")], [int(t) for t in o.split(",")]))
+    return out
+
+
+def test_scaffold_resolution_follows_the_worked_examples():
+    for line in open(os.path.join(GOLDEN, "scaffold_examples.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        imports, scaffolds, want = line.rstrip("\n").split(";")
+        got = oracle.resolve_scaffolds([int(t) for t in imports.split()], _parse_scaffolds(scaffolds))
+        assert got == [int(t) for t in want.split()], line
+
+
+@pytest.mark.parametrize("case", ["adjacent", "module_between", "not_all_imported"])
+def test_toy_transformer_scaffold_equals_pass_with_a_shared_span(case):
+    """Serving with a scaffold's jointly encoded states equals ONE pass over the prompt in which the scaffold's
+    members see each other (and every other module still sees only itself).  If a member is missing from the
+    prompt, nothing is overridden and the ordinary module-local equivalence holds."""
+    model = ToyModel(seed=6)
+    rng = np.random.default_rng(60)
+    sizes = [6, 7, 5, 4]
+    starts, _ = oracle.layout(sizes)
+    scaffold_members = {"adjacent": [0, 1], "module_between": [0, 2], "not_all_imported": [0, 3]}[case]
+    imported = [0, 1, 2]
+    toks = {m: rng.integers(0, 97, size=sizes[m]) for m in range(4)}
+    own = {m: model.encode_module(toks[m], starts[m]) for m in range(4)}
+    joint = model.encode_scaffold([(toks[m], starts[m]) for m in scaffold_members])
+    store = dict(own)
+    for m, st in zip(scaffold_members, joint):
+        store[100 + m] = st
+    resolved = oracle.resolve_scaffolds(imported, [(scaffold_members, [100 + m for m in scaffold_members])])
+    assert (resolved != imported) == (case != "not_all_imported")
+    new_pos = oracle.text_positions(starts[2], sizes[2], 4)
+    new_toks = rng.integers(0, 97, size=4)
+    start_of = lambda i: starts[i - 100] if i >= 100 else starts[i]
+    hB = model.forward_cached([store[i] for i in resolved], [start_of(i) for i in resolved], new_toks, new_pos)
+    # one pass: members of a complete scaffold share a span id
+    span = {m: m for m in imported}
+    if case != "not_all_imported":
+        for m in scaffold_members:
+            span[m] = 50
+    tokens = np.concatenate([toks[m] for m in imported] + [new_toks])
+    pos = np.concatenate([np.arange(starts[m], starts[m] + sizes[m]) for m in imported] + [new_pos]).astype(np.int32)
+    mod = np.concatenate([np.full(sizes[m], span[m]) for m in imported] + [np.full(4, -1)]).astype(np.int32)
+    hA = model.forward_full_masked(tokens, pos, mod)[-4:]
+    assert np.abs(hA - hB).max() < 1e-11
+    if case != "not_all_imported":   # and the override matters: the members' own states give something else
+        hC = model.forward_cached([own[i] for i in imported], [starts[i] for i in imported], new_toks, new_pos)
+        assert np.abs(hA - hC).max() > 1e-4
