@@ -268,6 +268,31 @@ int pc_prefill_attn_batched(pc_ctx *ctx, int layer, const void *Q_new, const int
                             void *out, void *stream);
 
 /*
+ * Sec. 3.3 ("attention masking effect"), scaffolding: a scaffold is a set of prompt modules
+ * that was ALSO encoded jointly, so that its members share one attention span.  When a prompt
+ * imports every member of a scaffold, the jointly encoded states override the members' own.
+ * To this library the joint encoding is one more stored module per member: override_ids[i]
+ * names the states (stored with pc_store_module / pc_store_module_host, same length and first
+ * position ID as member_ids[i]) that stand in for member_ids[i].
+ *
+ * pc_define_scaffold     registers one scaffold (host int arrays of n_members ids, members
+ *                        distinct).  From then on every call that takes import lists
+ *                        (pc_assemble_kv*, pc_assemble_append_kv_batched,
+ *                        pc_prefill_attn_shared_batched) applies the rule per prompt: scaffolds
+ *                        in definition order; one that would touch a member an earlier scaffold
+ *                        has overridden is skipped.  An override id that was never stored for the
+ *                        layer gives PC_E_UNKNOWN_MODULE at that call, one whose length or first
+ *                        position differs from its member's PC_E_SCHEMA.
+ * pc_resolve_scaffolds   the rule itself on host integers, no context: scaffold s has members
+ *                        member_ids[scaffold_offsets[s] .. scaffold_offsets[s+1]-1] and the
+ *                        override ids at the same indices; out_ids[n_ids] receives the import list
+ *                        with the overridden ids replaced where they stood.
+ */
+int pc_define_scaffold(pc_ctx *ctx, int n_members, const int *member_ids, const int *override_ids);
+int pc_resolve_scaffolds(int n_ids, const int *ids, int n_scaffolds, const int *scaffold_offsets,
+                         const int *member_ids, const int *override_ids, int *out_ids);
+
+/*
  * Sec. 4.2, ALiBi: models that encode position as a linear bias on the attention scores
  * instead of a rotation.  The bias follows the given position IDs:
  *     score(q, k) = Q.K / sqrt(d)  -  slope[head] * (pos_q - pos_k),   visible iff pos_k <= pos_q.

@@ -26,6 +26,7 @@ EXPORTS = [
     "pc_module_info", "pc_pool_usage", "pc_last_attn_launch", "pc_profile_enable", "pc_profile_read",
     "pc_profile_read_each", "pc_set_module_params", "pc_fill_params",
     "pc_host_pool_reserve", "pc_store_module_host", "pc_set_host_copy_mode", "pc_set_alibi", "pc_alibi_slopes",
+    "pc_define_scaffold", "pc_resolve_scaffolds",
 ]
 PROF_GATHER, PROF_APPEND, PROF_ATTN, PROF_COMBINE, PROF_ROPE = range(5)
 PC_POS_NONE = 0x7FFFFFFF
@@ -78,6 +79,8 @@ def lib() -> ctypes.CDLL:
     L.pc_set_host_copy_mode.argtypes = [vp, i]
     L.pc_set_alibi.argtypes = [vp, vp]
     L.pc_alibi_slopes.argtypes = [i, vp]
+    L.pc_define_scaffold.argtypes = [vp, i, vp, vp]
+    L.pc_resolve_scaffolds.argtypes = [i, vp, i, vp, vp, vp, vp]
     L.pc_set_module_params.argtypes = [vp, i, i, vp, vp]
     L.pc_fill_params.argtypes = [vp, i, vp, i, i, vp, vp, vp, vp, vp, vp, vp, vp, i, vp]
     L.pc_schema_layout.argtypes = [i, vp, vp, vp]
@@ -98,6 +101,18 @@ def lib() -> ctypes.CDLL:
             fn.restype = ctypes.c_int
     _lib = L
     return L
+
+
+def pc_resolve_scaffolds(import_ids: Sequence[int], scaffolds: Sequence[tuple]) -> List[int]:
+    """scaffolds: sequence of (member_ids, override_ids); returns the import list with scaffolds applied."""
+    ids = _ints(import_ids)
+    offs = _ints(np.concatenate([[0], np.cumsum([len(m) for m, _ in scaffolds])]))
+    mem = _ints([x for m, _ in scaffolds for x in m])
+    ovr = _ints([x for _, o in scaffolds for x in o])
+    out = np.zeros(max(len(ids), 1), dtype=np.intc)
+    _check(lib().pc_resolve_scaffolds(len(ids), _np_ptr(ids), len(scaffolds), _np_ptr(offs), _np_ptr(mem), _np_ptr(ovr),
+                                      _np_ptr(out)), "pc_resolve_scaffolds")
+    return [int(x) for x in out[:len(ids)]]
 
 
 def pc_alibi_slopes(n_heads: int) -> np.ndarray:
@@ -301,6 +316,11 @@ class PromptCache:
 
     def pc_set_host_copy_mode(self, mode: int) -> None:
         _check(lib().pc_set_host_copy_mode(self._ctx, int(mode)), "pc_set_host_copy_mode")
+
+    def pc_define_scaffold(self, member_ids: Sequence[int], override_ids: Sequence[int]) -> None:
+        m, o = _ints(member_ids), _ints(override_ids)
+        assert len(m) == len(o)
+        _check(lib().pc_define_scaffold(self._ctx, len(m), _np_ptr(m), _np_ptr(o)), "pc_define_scaffold")
 
     def pc_set_alibi(self, slopes) -> None:
         """slopes: n_q_heads floats (host), or None to return to rotary encoding."""

@@ -24,6 +24,12 @@ struct ModuleEntry {
     bool host = false;   // offsets are into the pinned host pool (Sec. 4.1, modules kept in CPU memory)
 };
 
+// A scaffold (Sec. 3.3): modules that were also encoded jointly; override[i] names the stored states that
+// replace member[i] when a prompt imports every member.
+struct Scaffold {
+    std::vector<int> member, override_id;
+};
+
 // A parameter of a module (Sec. 3.2.2): rows [offset, offset+len) of the module hold placeholder states.
 struct ParamSlot {
     int offset;
@@ -61,6 +67,7 @@ struct pc_ctx {
     int host_copy_mode = PC_HOST_READ_KERNEL;
     std::vector<std::unordered_map<int, pc::ModuleEntry>> modules;  // per layer
     std::unordered_map<int, std::vector<pc::ParamSlot>> params;     // per module id (schema level, all layers)
+    std::vector<pc::Scaffold> scaffolds;                            // in definition order (schema level)
 
     float2 *rope_table = nullptr;  // device, [max_pos][head_dim/2] (cos, sin)
     int32_t *iota = nullptr;  // device, 0, 1, .. max_pos-1: position IDs of module rows read in place

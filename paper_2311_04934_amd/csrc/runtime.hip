@@ -58,12 +58,58 @@ int check_ranges(int n, const int *starts, const int *lens, int max_pos)
     return PC_OK;
 }
 
+// Scaffolding (Sec. 3.3): replace, in place, the ids of every scaffold whose members are all in the list by
+// the ids of its jointly encoded states.  Scaffolds are taken in definition order; one that would touch a
+// member an earlier scaffold has overridden is skipped.
+void apply_scaffolds(const std::vector<Scaffold> &scaffolds, std::vector<int> &ids, std::vector<int> *replaced_from = nullptr)
+{
+    if (scaffolds.empty() || ids.empty()) return;
+    const std::vector<int> imported(ids);
+    std::vector<int> taken;
+    auto has = [](const std::vector<int> &v, int x) { return std::find(v.begin(), v.end(), x) != v.end(); };
+    for (const Scaffold &sc : scaffolds) {
+        bool complete = true;
+        for (int m : sc.member) complete = complete && has(imported, m) && !has(taken, m);
+        if (!complete) continue;
+        for (size_t i = 0; i < sc.member.size(); ++i) {
+            for (size_t j = 0; j < ids.size(); ++j)
+                if (imported[j] == sc.member[i] && !has(taken, imported[j])) ids[j] = sc.override_id[i];
+            taken.push_back(sc.member[i]);
+        }
+    }
+    if (replaced_from) *replaced_from = imported;
+}
+
+// A prompt's import list with scaffolds applied; the override states must mirror their member
+// (same length, same first position ID), which is checked against the member when it is stored too.
+int resolve_imports(const pc_ctx *ctx, int layer, const int *ids, int n, std::vector<int> &out)
+{
+    out.assign(ids, ids + n);
+    if (ctx->scaffolds.empty()) return PC_OK;
+    std::vector<int> from;
+    apply_scaffolds(ctx->scaffolds, out, &from);
+    const auto &table = ctx->modules[layer];
+    for (int i = 0; i < n; ++i) {
+        if (out[i] == from[i]) continue;
+        auto o = table.find(out[i]);
+        if (o == table.end()) return PC_E_UNKNOWN_MODULE;
+        auto m = table.find(from[i]);
+        if (m != table.end() && (m->second.n_tokens != o->second.n_tokens || m->second.start_pos != o->second.start_pos))
+            return PC_E_SCHEMA;
+    }
+    return PC_OK;
+}
+
 // Resolve one prompt's imports into gather segments appended to `segs`.
 // dst_row0: first output row of this prompt; capacity: rows available to it.
 int plan_prompt(const pc_ctx *ctx, int layer, const int *ids, int n, int dst_row0, int capacity,
                 std::vector<GatherSeg> &segs, int *n_rows_out)
 {
     const auto &table = ctx->modules[layer];
+    std::vector<int> resolved;
+    int rrc = resolve_imports(ctx, layer, ids, n, resolved);
+    if (rrc != PC_OK) return rrc;
+    ids = resolved.data();
     std::vector<int> starts(n), lens(n);
     long rows = 0;
     for (int i = 0; i < n; ++i) {
@@ -357,6 +403,39 @@ int pc_store_module(pc_ctx *ctx, int layer, int module_id, const void *K, const 
         table.emplace(module_id, e);
         ctx->pool_used = e.v_offset + bytes;
     }
+    return PC_OK;
+}
+
+int pc_resolve_scaffolds(int n_ids, const int *ids, int n_scaffolds, const int *scaffold_offsets, const int *member_ids,
+                         const int *override_ids, int *out_ids)
+{
+    if (n_ids < 0 || n_scaffolds < 0 || (n_ids > 0 && (!ids || !out_ids))) return PC_E_BADARG;
+    if (n_scaffolds > 0 && (!scaffold_offsets || !member_ids || !override_ids)) return PC_E_BADARG;
+    std::vector<Scaffold> sc(n_scaffolds);
+    for (int s = 0; s < n_scaffolds; ++s) {
+        const int lo = scaffold_offsets[s], hi = scaffold_offsets[s + 1];
+        if (lo < 0 || hi <= lo) return PC_E_BADARG;
+        sc[s].member.assign(member_ids + lo, member_ids + hi);
+        sc[s].override_id.assign(override_ids + lo, override_ids + hi);
+    }
+    std::vector<int> v(ids, ids + n_ids);
+    apply_scaffolds(sc, v);
+    for (int i = 0; i < n_ids; ++i) out_ids[i] = v[i];
+    return PC_OK;
+}
+
+int pc_define_scaffold(pc_ctx *ctx, int n_members, const int *member_ids, const int *override_ids)
+{
+    if (!ctx || n_members <= 0 || !member_ids || !override_ids) return PC_E_BADARG;
+    Scaffold sc;
+    for (int i = 0; i < n_members; ++i) {
+        if (member_ids[i] < 0 || override_ids[i] < 0) return PC_E_BADARG;
+        for (int j = 0; j < i; ++j)
+            if (member_ids[j] == member_ids[i]) return PC_E_BADARG;
+        sc.member.push_back(member_ids[i]);
+        sc.override_id.push_back(override_ids[i]);
+    }
+    ctx->scaffolds.push_back(sc);
     return PC_OK;
 }
 
@@ -723,12 +802,18 @@ int pc_prefill_attn_shared_batched(pc_ctx *ctx, int layer, const void *Q_new, co
     const auto &table = ctx->modules[layer];
     const uint8_t *kt = static_cast<const uint8_t *>(K_tail), *vt = static_cast<const uint8_t *>(V_tail);
     // every prompt is checked before the first launch, so that an error leaves `out` untouched
+    std::vector<int> ids_all;   // every prompt's imports with scaffolds applied, same offsets as the caller's list
     for (int b = 0; b < n_prompts; ++b) {
         const int nm = mod_offsets[b + 1] - mod_offsets[b], nq = q_offsets[b + 1] - q_offsets[b];
         if (nm + 1 > kMaxKvSegs || (size_t)nq * ctx->row_bytes >= ((size_t)1 << 32)) return PC_E_UNSUPPORTED;
+        std::vector<int> res;
+        int rrc = resolve_imports(ctx, layer, module_ids_flat + mod_offsets[b], nm, res);
+        if (rrc != PC_OK) return rrc;
+        if ((int)ids_all.size() != mod_offsets[b] - mod_offsets[0]) return PC_E_BADARG;
+        ids_all.insert(ids_all.end(), res.begin(), res.end());
         std::vector<int> starts(nm), lens(nm);
         for (int i = 0; i < nm; ++i) {
-            auto it = table.find(module_ids_flat[mod_offsets[b] + i]);
+            auto it = table.find(res[i]);
             if (it == table.end()) return PC_E_UNKNOWN_MODULE;
             starts[i] = it->second.start_pos;
             lens[i] = it->second.n_tokens;
@@ -751,7 +836,7 @@ int pc_prefill_attn_shared_batched(pc_ctx *ctx, int layer, const void *Q_new, co
             const int seg0 = n_seg;
             int rows = 0;
             for (int i = 0; i < nm; ++i) {
-                const ModuleEntry &m = table.find(module_ids_flat[mod_offsets[b] + i])->second;
+                const ModuleEntry &m = table.find(ids_all[mod_offsets[b] - mod_offsets[0] + i])->second;
                 if (m.n_tokens == 0) continue;
                 tab.seg[n_seg++] = KvSeg{ctx->pool + m.k_offset, ctx->pool + m.v_offset, ctx->iota + m.start_pos, rows, 0};
                 rows += m.n_tokens;

@@ -124,3 +124,26 @@ def test_create_rejects_bad_configs_before_touching_the_gpu():
     assert create(dtype=7) == -9
     assert create(max_pos=0) == -1
     assert create(n_layers=0) == -1
+
+
+def test_scaffold_resolution_matches_the_oracle_rule():
+    """Host integers only: the library's rule against the oracle's on the worked examples and on random cases."""
+    golden = os.path.join(os.path.dirname(__file__), "golden", "scaffold_examples.txt")
+    for line in open(golden):
+        if line.startswith("#") or not line.strip():
+            continue
+        imports, scaffolds, want = line.rstrip("\n").split(";")
+        sc = []
+        for part in scaffolds.split("/"):
+            m, o = part.strip().split(">")
+            sc.append(([int(t) for t in m.split(",")], [int(t) for t in o.split(",")]))
+        assert pcb.pc_resolve_scaffolds([int(t) for t in imports.split()], sc) == [int(t) for t in want.split()], line
+    rng = np.random.default_rng(70)
+    for _ in range(300):
+        n_mod = int(rng.integers(1, 9))
+        imports = [int(x) for x in rng.permutation(n_mod)[:int(rng.integers(0, n_mod + 1))]]
+        sc = []
+        for s in range(int(rng.integers(0, 4))):
+            members = [int(x) for x in rng.permutation(n_mod)[:int(rng.integers(1, min(n_mod, 4) + 1))]]
+            sc.append((members, [100 * (s + 1) + m for m in members]))
+        assert pcb.pc_resolve_scaffolds(imports, sc) == oracle.resolve_scaffolds(imports, sc), (imports, sc)

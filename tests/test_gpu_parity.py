@@ -736,6 +736,91 @@ def test_alibi_bf16_head_dim_64_is_refused():
         r.close()
 
 
+# ------------------------------------------------------------------ scaffolds (Sec. 3.3)
+@pytest.mark.parametrize("in_place", [False, True])
+def test_scaffold_states_override_members_when_all_are_imported(in_place):
+    """Modules 0 and 2 form a scaffold whose jointly encoded states are stored as modules 6 and 7 (same lengths
+    and positions, different values).  Prompts that import both get 6 and 7 in their place, the others the
+    members' own states.  Expected rows and attention: the oracle's concatenation of the oracle-resolved list."""
+    sizes = [96, 64, 130, 40, 70, 33, 96, 130]
+    w = W.custom("scaffold", "bf16", 8, 2, 128, sizes, None,
+                 [W.Prompt([0, 1, 2], 40), W.Prompt([2, 0], 17), W.Prompt([0, 1], 20), W.Prompt([2, 3], 9),
+                  W.Prompt([6, 7, 1], 5)], max_pos=2048)
+    c = build_case(w, 0)
+    # the override states sit at their members' schema positions
+    c.starts[6], c.starts[7] = c.starts[0], c.starts[2]
+    for m, member in ((6, 0), (7, 2)):
+        pos = np.arange(c.starts[member], c.starts[member] + sizes[member], dtype=np.int32)
+        k_raw, v = W.module_raw_kv(w, 0, m)
+        c.mod_K[m] = torch.from_numpy(oracle.rope(to_f64(k_raw), pos, w.rope_base)).to(w.torch_dtype)
+        c.mod_V[m] = v
+    scaffolds = [([0, 2], [6, 7])]
+    r = GpuRunner.__new__(GpuRunner)
+    r.c, r.dev = c, torch.device("cuda:0")
+    r.pc = pcb.PromptCache.for_workload(w, n_layers=1)
+    for m in sorted(c.mod_K):
+        r.pc.pc_store_module(0, m, c.mod_K[m].to(r.dev), c.mod_V[m].to(r.dev), c.starts[m])
+    r.pc.pc_define_scaffold(*scaffolds[0])
+    dev = r.dev
+    prompts = c.prompts[:4]          # the last workload prompt only makes the generator produce modules 6 and 7
+    B = len(prompts)
+    resolved = [oracle.resolve_scaffolds(p.module_ids, scaffolds) for p in prompts]
+    assert resolved[0] == [6, 1, 7] and resolved[1] == [7, 6] and resolved[2] == [0, 1] and resolved[3] == [2, 3]
+    n_mod = [sum(sizes[m] for m in p.module_ids) for p in prompts]
+    n_new = [len(p.q_pos) for p in prompts]
+    lens = [a + b for a, b in zip(n_mod, n_new)]
+    kv_off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    q_off = np.concatenate([[0], np.cumsum(n_new)]).astype(np.int64)
+    Q = torch.cat([p.Q for p in prompts]).to(dev)
+    Kn = torch.cat([p.K_new for p in prompts]).to(dev)
+    Vn = torch.cat([p.V_new for p in prompts]).to(dev)
+    qp = torch.from_numpy(np.concatenate([p.q_pos for p in prompts])).to(dev)
+    ids = [p.module_ids for p in prompts]
+    out = torch.full((int(q_off[-1]), 8, 128), float("nan"), dtype=torch.bfloat16, device=dev)
+    try:
+        if in_place:
+            tK = torch.empty((int(q_off[-1]), 2, 128), dtype=torch.bfloat16, device=dev)
+            tV, tP = torch.empty_like(tK), torch.empty((int(q_off[-1]),), dtype=torch.int32, device=dev)
+            r.pc.pc_append_kv_batched(0, Kn, Vn, qp, q_off, tK, tV, tP, q_off, [0] * B)
+            r.pc.pc_prefill_attn_shared_batched(0, Q, qp, q_off, ids, tK, tV, out)
+        else:
+            aK = torch.full((int(kv_off[-1]), 2, 128), float("nan"), dtype=torch.bfloat16, device=dev)
+            aV, aP = torch.full_like(aK, float("nan")), torch.full((int(kv_off[-1]),), -7, dtype=torch.int32, device=dev)
+            r.pc.pc_assemble_append_kv_batched(0, ids, Kn, Vn, qp, q_off, aK, aV, aP, kv_off)
+            r.pc.pc_prefill_attn_batched(0, Q, qp, q_off, aK, aV, aP, kv_off, lens, out)
+        torch.cuda.synchronize()
+        o = out.cpu()
+        for b, p in enumerate(prompts):
+            Ks = [as_words(c.mod_K[m]) for m in resolved[b]]
+            Vs = [as_words(c.mod_V[m]) for m in resolved[b]]
+            oK, oV, oP = oracle.assemble(Ks, Vs, [c.starts[m] for m in resolved[b]])
+            if not in_place:
+                rows = slice(int(kv_off[b]), int(kv_off[b]) + n_mod[b])
+                assert np.array_equal(as_words(aK[rows].cpu()), oK) and np.array_equal(as_words(aV[rows].cpu()), oV)
+                assert np.array_equal(aP[rows].cpu().numpy(), oP)
+            fK, fV, fP = oracle.assemble([to_f64(c.mod_K[m]) for m in resolved[b]], [to_f64(c.mod_V[m]) for m in resolved[b]],
+                                         [c.starts[m] for m in resolved[b]])
+            K = np.concatenate([fK, oracle.rope(to_f64(p.K_new), p.q_pos, w.rope_base)])
+            V = np.concatenate([fV, to_f64(p.V_new)])
+            ref = oracle.attn(to_f64(p.Q), p.q_pos, K, V, np.concatenate([fP, p.q_pos]).astype(np.int32), w.rope_base)
+            err, rel = attn_errors(o[q_off[b]:q_off[b + 1]], ref)
+            print(f"[scaffold{'/in-place' if in_place else ''}] prompt {b} -> {resolved[b]}: max abs err {err:.3e}, rel L2 {rel:.3e}", flush=True)
+            assert err <= TOL_ABS["bf16"] and rel <= TOL_REL["bf16"]
+        # an override that does not mirror its member is refused, and so is one that was never stored
+        r.pc.pc_define_scaffold([1, 3], [2, 0])          # lengths 64/40 against 130/96
+        with pytest.raises(pcb.PcError) as e:
+            r.pc.pc_assemble_kv(0, [1, 3], aK if not in_place else tK, aV if not in_place else tV,
+                                aP if not in_place else tP)
+        assert e.value.status == -11
+        r.pc.pc_define_scaffold([6, 7], [50, 51])
+        with pytest.raises(pcb.PcError) as e:
+            r.pc.pc_assemble_kv(0, [6, 7], aK if not in_place else tK, aV if not in_place else tV,
+                                aP if not in_place else tP)
+        assert e.value.status == -3
+    finally:
+        r.close()
+
+
 # ------------------------------------------------------------------ run-to-run determinism
 def _determinism_run(w, in_place, n_runs=60):
     """The same attention launched many times back to back, with no host synchronisation between the
