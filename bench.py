@@ -80,6 +80,98 @@ def oracle_layer_step(w, starts, layer, prompt_index, n_queries=None):
     return secs, flops, f"layer {layer}, prompt {prompt_index} of {w.name}: {which} uncached tokens x {w.n_q_heads} heads over {T + p.n_new} keys"
 
 
+def length_sweep(args) -> int:
+    """Sec. 5.4 / Fig. 5 in shape: everything cached, sequence length 1K..16K, Llama-7B attention shape.
+    Per layer: time to bring the cached states in (a copy, linear in the length: from HBM, and from pinned
+    host memory) against the time to recompute attention over the whole prompt (quadratic).  Prints one JSON line."""
+    import numpy as np
+    import torch
+    from paper_2311_04934_amd import binding as pcb
+    from paper_2311_04934_amd import workloads as W
+
+    dev = torch.device("cuda:0")
+    n_new = 64
+    rows = []
+    for N in (1024, 2048, 4096, 8192, 16384):
+        row_bytes = 32 * 128 * 2
+        layers = max(2, min(64, (1 << 30) // (2 * N * row_bytes)))       # > 1 GB of module states: no cache reuse
+        w = W.custom(f"sweep_{N}", "bf16", 32, 32, 128, [N], None, [W.Prompt([0], n_new)], n_layers=layers, max_pos=32768)
+        res = {"tokens": N, "layers_cycled": layers}
+        mods = [W.module_raw_kv(w, layer, 0) for layer in range(layers)]
+        for tier in ("hbm", "host"):
+            pc = pcb.PromptCache.for_workload(w)
+            if tier == "host":
+                pc.pc_host_pool_reserve(layers * 2 * (N * row_bytes + 512))
+            for layer in range(layers):
+                k, v = mods[layer]
+                if tier == "host":
+                    pc.pc_store_module_host(layer, 0, k.contiguous(), v.contiguous(), 0)
+                else:
+                    pc.pc_store_module(layer, 0, k.to(dev), v.to(dev), 0)
+            torch.cuda.synchronize()
+            total = N + n_new
+            aK = torch.empty((total, 32, 128), dtype=torch.bfloat16, device=dev)
+            aV, aP = torch.empty_like(aK), torch.empty((total,), dtype=torch.int32, device=dev)
+            q, kn, vn = W.new_token_qkv(w, 0, 0, n_new)
+            q, kn, vn = q.to(dev), kn.to(dev), vn.to(dev)
+            qp = torch.arange(N, total, dtype=torch.int32, device=dev)
+            out = torch.empty_like(q)
+            reps = 2 if tier == "host" else 4
+
+            def cached_pass():
+                for layer in range(layers):
+                    pc.pc_assemble_append_kv_batched(layer, [[0]], kn, vn, qp, [0, n_new], aK, aV, aP, [0, total])
+                    pc.pc_prefill_attn_batched(layer, q, qp, [0, n_new], aK, aV, aP, [0, total], [total], out)
+
+            cached_pass()
+            torch.cuda.synchronize()
+            pc.pc_profile_enable(reps * layers)
+            for _ in range(reps):
+                cached_pass()
+            torch.cuda.synchronize()
+            us = {}
+            for name, kind in (("gather", pcb.PROF_GATHER), ("attn", pcb.PROF_ATTN), ("combine", pcb.PROF_COMBINE)):
+                n, ms = pc.pc_profile_read(kind)
+                us[name] = ms / n * 1e3 if n else 0.0
+            pc.pc_profile_enable(0)
+            copy_bytes = 2 * N * row_bytes
+            if tier == "hbm":
+                res["copy_d2d_us"] = round(us["gather"], 2)
+                res["copy_d2d_GBps"] = round(2 * copy_bytes / (us["gather"] * 1e-6) / 1e9, 1)     # read + write
+                res["cached_attn_us"] = round(us["attn"] + us["combine"], 2)
+                # recomputing: the same kernel over all N + n_new tokens as queries, ordinary causal mask
+                Qf = torch.randn((total, 32, 128), generator=torch.Generator().manual_seed(7)).to(torch.bfloat16).to(dev)
+                pos_f = torch.arange(total, dtype=torch.int32, device=dev)
+                out_f = torch.empty_like(Qf)
+                pc.pc_prefill_attn(0, Qf, pos_f, aK, aV, pos_f, total, out_f)
+                torch.cuda.synchronize()
+                pc.pc_profile_enable(8)
+                for _ in range(2):
+                    pc.pc_prefill_attn(0, Qf, pos_f, aK, aV, pos_f, total, out_f)
+                torch.cuda.synchronize()
+                n, ms = pc.pc_profile_read(pcb.PROF_ATTN)
+                n2, ms2 = pc.pc_profile_read(pcb.PROF_COMBINE)
+                pc.pc_profile_enable(0)
+                res["full_prefill_attn_us"] = round((ms + ms2) / n * 1e3, 1)
+                del Qf, out_f
+            else:
+                res["copy_h2d_us"] = round(us["gather"], 1)
+                res["copy_h2d_GBps"] = round(copy_bytes / (us["gather"] * 1e-6) / 1e9, 1)
+            pc.close()
+            del aK, aV, aP
+            torch.cuda.empty_cache()
+        res["speedup_hbm"] = round(res["full_prefill_attn_us"] / (res["copy_d2d_us"] + res["cached_attn_us"]), 1)
+        res["speedup_host"] = round(res["full_prefill_attn_us"] / (res["copy_h2d_us"] + res["cached_attn_us"]), 2)
+        rows.append(res)
+        print(f"# {res}", file=sys.stderr, flush=True)
+    print(json.dumps({"metric": "per-layer time to serve a fully cached prompt vs recomputing its attention, by length",
+                      "unit": "us per layer", "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": "length_sweep", "n_q_heads": 32, "n_kv_heads": 32, "head_dim": 128,
+                                 "uncached_tokens": n_new},
+                      "sweep": rows}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -99,6 +191,8 @@ def main() -> int:
     ap.add_argument("--host-tier", choices=["kernel", "engine"], default=None,
                     help="keep the modules in pinned host memory (Sec. 4.1) and bring them in at every use: 'kernel' = "
                          "the assembly kernel loads them over the host link, 'engine' = copy-engine transfers")
+    ap.add_argument("--length-sweep", action="store_true",
+                    help="instead of the step benchmark: copy time vs attention recompute time for 1K..16K cached tokens")
     ap.add_argument("--alibi", action="store_true",
                     help="position as a linear bias on the scores (Sec. 4.2, ALiBi) instead of a rotation; no CPU baseline")
     ap.add_argument("--overlap", action="store_true",
@@ -119,6 +213,8 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
+    if args.length_sweep:
+        return length_sweep(args)
     dev = torch.device("cuda:0")
     L = args.layers
     w = W.by_name(args.workload, n_layers=L)
