@@ -48,7 +48,8 @@ constexpr int LDS_K = 0;
 constexpr int LDS_V = NBUF * TILE_BYTES;                     // 64 KiB: raw V, [key][d], swizzled chunks
 constexpr int LDS_VT = LDS_V + NVRAW * TILE_BYTES;           // 112 KiB: V^T fragments, 16 x 1 KiB per tile
 constexpr int LDS_POS = LDS_VT + NVT * TILE_BYTES;           // 144 KiB
-constexpr int LDS_MAIN = LDS_POS + NBUF * KT * 4;
+constexpr int LDS_BIAS = LDS_POS + NBUF * KT * 4;          // linear-bias variant: per wave, 2 tiles x 64 floats
+constexpr int LDS_MAIN = LDS_BIAS + kWideRowTilesPerWg * 2 * KT * 4;
 constexpr int EPI_STRIDE = D * 4 + 16;           // fp32 row of O plus a 16-byte pad
 constexpr int LDS_EPI = 256 * EPI_STRIDE;        // 256 query rows per workgroup
 constexpr int LDS_TOTAL = LDS_MAIN > LDS_EPI ? LDS_MAIN : LDS_EPI;
@@ -471,7 +472,8 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
     // between slots so that this order survives; the empty asm statements keep each value's
     // computation in its slot.
     auto step = [&](const bf16x8 (&pp)[NQT][2], const lds_u8 *kbase, f32x16 (&snext)[NQT], const f32x16 (&s)[NQT],
-                    bf16x8 (&pout)[NQT][2], const lds_u8 *vnext, bool do_dma, int dma_tile, bool do_tr, int tr_tile) {
+                    bf16x8 (&pout)[NQT][2], const lds_u8 *vnext, bool do_dma, int dma_tile, bool do_tr, int tr_tile,
+                    const lds_u8 *bias_next) {
         bf16x8 kf[KB];
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) kf[kb] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const lds_u32x4 *>(kbase + koff[kb]));
@@ -479,6 +481,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
         float m_use[NQT], psum[NQT], pe_even[NQT], pe_prev[NQT], dnext[NQT], mxa[NQT][5], mx[NQT], m_new[NQT];
         u32x4 pw[NQT][2];
         const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        f32x16 bias_c = zero;
         int e_done = 0;   // softmax elements finished so far (compile-time after unrolling)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
@@ -488,7 +491,19 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
                     o_acc[x][i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i], pp[x][i / DB], o_acc[x][i % DB], 0, 0, 0);
                 } else {
                     const int kb = i - 2 * DB;
-                    snext[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb], qf[x][kb], kb == 0 ? zero : snext[x], 0, 0, 0);
+                    snext[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb], qf[x][kb], kb == 0 ? (ALIBI ? bias_c : zero) : snext[x], 0, 0, 0);
+                }
+            }
+            // ALIBI: the per-key bias of the sub-tile whose scores start at slot 8 enters as the initial
+            // accumulator of its K.Q chain, so it costs four LDS reads and no arithmetic
+            if constexpr (ALIBI) {
+                if (i == 2 * DB - 2) {
+#pragma unroll
+                    for (int i4 = 0; i4 < 4; ++i4) {
+                        const f32x4 b = *reinterpret_cast<const __attribute__((address_space(3))) f32x4 *>(bias_next + (8 * i4 + 4 * hh) * 4);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) bias_c[i4 * 4 + e] = b[e];
+                    }
                 }
             }
             // ---- softmax share of this slot
@@ -600,18 +615,30 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
 
     // ALIBI: s += slope * (pos_k - ref) in the log2 domain, ref = the wave's smallest query position.  The
     // term -slope * (pos_q - ref) that completes -slope * (pos_q - pos_k) is the same for every key of a
-    // query and cancels in the softmax, so only a per-key value is added.  Differences are taken in
-    // integers first: the bias is exact where it is small, i.e. for the keys that carry weight.
-    auto apply_bias = [&](f32x16 (&s)[NQT], int buf, int sub) {
-        const lds_u8 *pp = lds + LDS_POS + buf * KT * 4;
+    // query and cancels in the softmax, so only a per-key value is added.  The difference is taken in
+    // integers first: the bias is exact where it is small, i.e. for the keys that carry weight.  The wave
+    // computes the 64 values of a tile once, one key per lane (tile_needs_mask has the position in that
+    // layout anyway), and passes them to itself through a private strip of LDS to get them into the
+    // score layout: per half tile that leaves 16 additions.
+    auto store_bias = [&](int t, int kpos) {
+        if constexpr (ALIBI) {
+            const float b = slope2 * (float)(kpos - bias_ref);
+            *reinterpret_cast<__attribute__((address_space(3))) float *>(lds + LDS_BIAS + (wave * 2 + (t & 1)) * KT * 4 + lane * 4) = b;
+        }
+    };
+    auto bias_strip = [&](int t, int sub) -> const lds_u8 * {
+        return lds + LDS_BIAS + (wave * 2 + (t & 1)) * KT * 4 + sub * 32 * 4;
+    };
+    auto apply_bias = [&](f32x16 (&s)[NQT], int t, int sub) {   // the first sub-tile only: its scores are computed outside a step
+        const lds_u8 *bp = lds + LDS_BIAS + (wave * 2 + (t & 1)) * KT * 4;
 #pragma unroll
         for (int i4 = 0; i4 < 4; ++i4) {
             const int key0 = sub * 32 + 8 * i4 + 4 * hh;
-            const u32x4 kp = *reinterpret_cast<const lds_u32x4 *>(pp + key0 * 4);
+            const f32x4 b = *reinterpret_cast<const __attribute__((address_space(3))) f32x4 *>(bp + key0 * 4);
 #pragma unroll
             for (int x = 0; x < NQT; ++x)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) s[x][i4 * 4 + e] += slope2 * (float)((int)kp[e] - bias_ref);
+                for (int e = 0; e < 4; ++e) s[x][i4 * 4 + e] += b[e];
         }
     };
 
@@ -635,6 +662,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
         const int buf = t & (NBUF - 1);
         const int n_valid = k_end - (k_begin + t * KT);
         const int kpos = *reinterpret_cast<const __attribute__((address_space(3))) int *>(lds + LDS_POS + buf * KT * 4 + lane * 4);
+        store_bias(t, kpos);
         return __any(kpos > wave_min_qpos) || n_valid < KT;
     };
 
@@ -663,6 +691,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
             }
 #pragma unroll
             for (int g = 0; g < 2 * DB; ++g) read_v(lds + LDS_VT, g);
+            if constexpr (ALIBI) apply_bias(sc[0], 0, 0);
         }
 
         // a wave without a row tile (fewer than 8 row tiles in this block) only helps with staging: its
@@ -698,19 +727,17 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
             __syncthreads();
             const bool mask_next = has_next ? tile_needs_mask(t + 1) : false;
 
-            if constexpr (ALIBI) apply_bias(sc[0], buf, 0);
             if (mask_cur) apply_mask(sc[0], buf, 0, n_valid);
             rescale();
             // P.V of tile t-1's second half | K.Q of this tile's second half | softmax of its first half;
             // the copies of tile t+3 are issued here
-            step(pf[1], k_cur + 32 * ROW_BYTES, sc[1], sc[0], pf[0], v_cur, true, t + 3, false, 0);
+            step(pf[1], k_cur + 32 * ROW_BYTES, sc[1], sc[0], pf[0], v_cur, true, t + 3, false, 0, bias_strip(t, 1));
 
-            if constexpr (ALIBI) apply_bias(sc[1], buf, 1);
             if (mask_cur) apply_mask(sc[1], buf, 1, n_valid);
             rescale();
             // P.V of this tile's first half | K.Q of tile t+1's first half | softmax of this tile's second half;
             // V of tile t+1 is brought into fragment order
-            step(pf[0], k_nxt, sc[0], sc[1], pf[1], v_cur + 8 * 1024, false, 0, true, t + 1);
+            step(pf[0], k_nxt, sc[0], sc[1], pf[1], v_cur + 8 * 1024, false, 0, true, t + 1, bias_strip(has_next ? t + 1 : t, 0));
             mask_cur = mask_next;
         }
         // drain: P.V of the very last sub-tile
