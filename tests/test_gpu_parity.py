@@ -821,6 +821,53 @@ def test_scaffold_states_override_members_when_all_are_imported(in_place):
         r.close()
 
 
+# ------------------------------------------------------------------ seeded random workloads
+def _random_workload(seed):
+    """Random schema (sizes 1..400, some unions), random imports in random buffer order, 1..150 new tokens,
+    sometimes text inside a gap; shapes alternate between the kernels (fp32, bf16 d=64, bf16 d=128 MHA/GQA)."""
+    rng = np.random.default_rng(1000 + seed)
+    dtype, hq, hkv, d = [("f32", 6, 2, 64), ("bf16", 8, 8, 64), ("bf16", 8, 2, 128), ("bf16", 4, 4, 128),
+                         ("bf16", 16, 2, 128), ("f32", 4, 4, 32)][seed % 6]
+    n_mod = int(rng.integers(3, 10))
+    sizes = [int(x) for x in rng.integers(1, 400, size=n_mod)]
+    union_ids, u = [], 0
+    i = 0
+    while i < n_mod:
+        if i + 1 < n_mod and rng.random() < 0.3:
+            k = int(rng.integers(2, min(3, n_mod - i) + 1))
+            union_ids += [u] * k
+            u += 1
+            i += k
+        else:
+            union_ids.append(-1)
+            i += 1
+    prompts = []
+    for _ in range(int(rng.integers(2, 6))):
+        picks, seen_unions = [], set()
+        for m in rng.permutation(n_mod):
+            m = int(m)
+            if rng.random() < 0.6 and union_ids[m] not in seen_unions:
+                picks.append(m)
+                if union_ids[m] >= 0:
+                    seen_unions.add(union_ids[m])
+        kw = {}
+        if picks and rng.random() < 0.3:
+            kw = dict(gap_after=picks[int(rng.integers(0, len(picks)))], n_gap=int(rng.integers(1, 20)))
+        prompts.append(W.Prompt(picks, int(rng.integers(1, 150)), **kw))
+    return W.custom(f"random_{seed}", dtype, hq, hkv, d, sizes, union_ids, prompts, max_pos=8192)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_workloads_packed_path(seed):
+    w = _random_workload(seed)
+    _batched_run(w, 0, None, fused=bool(seed & 1))
+
+
+@pytest.mark.parametrize("seed", [2, 3, 4, 8, 9, 10])
+def test_random_workloads_modules_in_place(seed):
+    _shared_run(_random_workload(seed), 0, None)
+
+
 # ------------------------------------------------------------------ run-to-run determinism
 def _determinism_run(w, in_place, n_runs=60):
     """The same attention launched many times back to back, with no host synchronisation between the
