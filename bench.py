@@ -195,6 +195,8 @@ def main() -> int:
                     help="instead of the step benchmark: copy time vs attention recompute time for 1K..16K cached tokens")
     ap.add_argument("--alibi", action="store_true",
                     help="position as a linear bias on the scores (Sec. 4.2, ALiBi) instead of a rotation; no CPU baseline")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step (all layers' launches) into a HIP graph and time K replays of it")
     ap.add_argument("--overlap", action="store_true",
                     help="assemble layer l+1 on a second stream while layer l's attention runs")
     args = ap.parse_args()
@@ -268,6 +270,11 @@ def main() -> int:
     import ctypes
     lib = pcb.lib()
     ctx = pc._ctx
+    if args.graph:   # a graph cannot be captured on the null stream: everything runs on a stream of its own
+        if args.overlap:
+            print("bench.py: --graph excludes --overlap", file=sys.stderr)
+            return 2
+        torch.cuda.set_stream(torch.cuda.Stream())
     stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream or None)
     # --overlap: KV assembly on a second stream (default priority), attention stays on the first
     copy_stream_t = torch.cuda.Stream() if args.overlap else None
@@ -346,9 +353,17 @@ def main() -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    run_step = step
+    if args.graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=torch.cuda.current_stream()):
+            step()
+        run_step = graph.replay
+        run_step()
+        torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        run_step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
@@ -395,7 +410,7 @@ def main() -> int:
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "kv_path": "modules read in place" if in_place else "packed copy",
                    "module_tier": ("host memory, " + ("loaded by the assembly kernel" if args.host_tier == "kernel" else "copy engine")) if args.host_tier else "HBM pool",
-                   "overlap": bool(args.overlap), "position_encoding": "alibi" if args.alibi else "rope", "layers": L, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
+                   "overlap": bool(args.overlap), "hip_graph": bool(args.graph), "position_encoding": "alibi" if args.alibi else "rope", "layers": L, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
                    "head_dim": w.head_dim, "prompts": B, "module_tokens": n_mod if B <= 4 else [n_mod[0], "..."],
                    "uncached_tokens": n_new[0], "attn_launch": {"kv_splits": launch[0], "workgroups": launch[1],
                                                               "waves_per_wg": launch[2]}},

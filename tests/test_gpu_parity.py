@@ -868,6 +868,58 @@ def test_random_workloads_modules_in_place(seed):
     _shared_run(_random_workload(seed), 0, None)
 
 
+# ------------------------------------------------------------------ HIP graph capture
+def test_step_replays_from_a_hip_graph():
+    """The request-path calls allocate nothing, clear nothing and never synchronise, so a caller may capture
+    them.  One captured step (assemble+append, attention with a KV split and its combine) is replayed several
+    times, with eager launches and synchronisations in between, and every replay must reproduce the eager bits."""
+    w = W.custom("graph", "bf16", 8, 2, 128, [700, 300, 260], None, [W.Prompt([0, 1, 2], 64), W.Prompt([2, 0], 40)],
+                 max_pos=4096)
+    c = build_case(w, 0)
+    r = GpuRunner(c)
+    dev = r.dev
+    n_mod = [sum(w.sizes[m] for m in p.module_ids) for p in c.prompts]
+    n_new = [len(p.q_pos) for p in c.prompts]
+    lens = [a + b for a, b in zip(n_mod, n_new)]
+    kv_off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    q_off = np.concatenate([[0], np.cumsum(n_new)]).astype(np.int64)
+    ids = [p.module_ids for p in c.prompts]
+    side = torch.cuda.Stream()
+    try:
+        with torch.cuda.stream(side):
+            Q = torch.cat([p.Q for p in c.prompts]).to(dev)
+            Kn = torch.cat([p.K_new for p in c.prompts]).to(dev)
+            Vn = torch.cat([p.V_new for p in c.prompts]).to(dev)
+            qp = torch.from_numpy(np.concatenate([p.q_pos for p in c.prompts])).to(dev)
+            aK = torch.zeros((int(kv_off[-1]), 2, 128), dtype=torch.bfloat16, device=dev)
+            aV, aP = torch.zeros_like(aK), torch.zeros((int(kv_off[-1]),), dtype=torch.int32, device=dev)
+            out = torch.zeros((int(q_off[-1]), 8, 128), dtype=torch.bfloat16, device=dev)
+
+            def step():
+                r.pc.pc_assemble_append_kv_batched(0, ids, Kn, Vn, qp, q_off, aK, aV, aP, kv_off, stream=side)
+                r.pc.pc_prefill_attn_batched(0, Q, qp, q_off, aK, aV, aP, kv_off, lens, out, stream=side)
+
+            step()
+            side.synchronize()
+            assert r.pc.pc_last_attn_launch()[0] > 1, "the case is meant to exercise the split + combine path"
+            want = (aK.clone(), aV.clone(), aP.clone(), out.clone())
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                step()
+            for rep in range(4):
+                for t in (aK, aV, aP, out):
+                    t.zero_()                      # eager work between the replays
+                side.synchronize()
+                g.replay()
+                side.synchronize()
+                for got, ref in zip((aK, aV, aP, out), want):
+                    assert torch.equal(got, ref), f"replay {rep} differs from the eager step"
+        res = dict(out=out.cpu()[:n_new[0]], launch=r.pc.pc_last_attn_launch())
+        check_attention(c, 0, res, None, "/graph")
+    finally:
+        r.close()
+
+
 # ------------------------------------------------------------------ run-to-run determinism
 def _determinism_run(w, in_place, n_runs=60):
     """The same attention launched many times back to back, with no host synchronisation between the
