@@ -4,12 +4,12 @@
 // the output is the packed concatenation in the order the prompt lists them, plus
 // one int32 position ID per row (start_pos + row index).  Bytes are copied verbatim.
 //
-// Work list: each module's rows are cut into tiles of `rows_per_tile` rows (about
-// 16 KiB of K and 16 KiB of V); the tiles of all segments form one flat list and
+// Work list: each module's rows are cut into tiles of `rows_per_tile` rows (32 KiB
+// of K and 32 KiB of V, twice that for very large launches); the tiles of all segments form one flat list and
 // workgroup b takes tile b.  The segment table travels in the kernel arguments, so
 // a call needs no host->device copy and no synchronisation.  Each lane moves
-// 16 bytes per access and issues all of its loads (K and V) before the first
-// store, which keeps ~32 KiB in flight per workgroup.
+// 16 bytes per access and issues all of its loads (K and V) of a pass before the first
+// store, which keeps 64 KiB in flight per workgroup.
 #include "kv_ops.h"
 
 namespace pc {

@@ -8,7 +8,7 @@ namespace kv {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kThreads = 256;
+constexpr int kThreads = 512;
 constexpr int kUnroll = 4;  // 16-byte accesses per lane per tensor per pass
 
 template <typename T>
