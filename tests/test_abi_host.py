@@ -147,3 +147,14 @@ def test_scaffold_resolution_matches_the_oracle_rule():
             members = [int(x) for x in rng.permutation(n_mod)[:int(rng.integers(1, min(n_mod, 4) + 1))]]
             sc.append((members, [100 * (s + 1) + m for m in members]))
         assert pcb.pc_resolve_scaffolds(imports, sc) == oracle.resolve_scaffolds(imports, sc), (imports, sc)
+
+
+def test_alibi_slope_helper_matches_the_oracle_and_the_published_values():
+    """Host helper, no context: the library's slope sequence against the oracle's (fp64) for many head counts."""
+    for n in [1, 2, 3, 4, 6, 8, 12, 16, 20, 32, 40, 64, 96, 128]:
+        got = pcb.pc_alibi_slopes(n)
+        want = oracle.alibi_slopes(n)
+        assert got.shape == (n,) and np.allclose(got, want, rtol=1e-7, atol=0), n
+    assert pcb.pc_alibi_slopes(8).tolist() == [2.0 ** -k for k in range(1, 9)]
+    with pytest.raises(pcb.PcError):
+        pcb.pc_alibi_slopes(0)
