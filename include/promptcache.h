@@ -359,8 +359,8 @@ int pc_set_host_copy_mode(pc_ctx *ctx, int mode);
  *                       tokens' keys ALREADY ROTATED to q_pos, and values, row q_offsets[b]+i
  *                       for prompt b's token i (what pc_append_kv_batched writes into an
  *                       empty buffer with kv_offsets = q_offsets and kv_lens = 0).
- * bf16 contexts with head_dim 128 only (PC_E_UNSUPPORTED otherwise), at most 63 modules per
- * prompt.  Inputs are read, never written; ownership stays with the caller.
+ * Every dtype and head_dim the packed path serves; at most 63 modules per prompt
+ * (PC_E_UNSUPPORTED beyond).  Inputs are read, never written; ownership stays with the caller.
  */
 int pc_prefill_attn_shared_batched(pc_ctx *ctx, int layer, const void *Q_new, const int32_t *q_pos,
                                    const int *q_offsets, int n_prompts, const int *module_ids_flat,

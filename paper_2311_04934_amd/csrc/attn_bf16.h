@@ -3,6 +3,7 @@
 #pragma once
 
 #include "common.h"
+#include "kv_seg.h"
 
 namespace pc {
 namespace attn {
@@ -79,22 +80,6 @@ __device__ __forceinline__ float sum_across_halves(float x)
 }
 
 }  // namespace attn
-
-// A prompt's KV as a list of row ranges read in place (module blocks of the pool, then the uncached
-// tokens' own rows) instead of one packed buffer.  Rows of segment s are the prompt's rows
-// [first_row, first_row of s+1); all three pointers address the segment's row 0.
-struct KvSeg {
-    const uint8_t *k;
-    const uint8_t *v;
-    const int32_t *pos;
-    int first_row;
-    int pad_;
-};
-constexpr int kMaxKvSegs = 64;
-struct KvSegTable {
-    int seg_begin[kMaxAttnSeqs + 1];   // prompt i owns seg[seg_begin[i] .. seg_begin[i+1])
-    KvSeg seg[kMaxKvSegs];
-};
 
 // DMA-staged kernel (attn_bf16_wide.hip): D = 128, 8 row tiles per workgroup, 1 row tile per wave.
 // tab != nullptr: K/V and positions are read through the segment table (p.k, p.v, p.kv_pos unused).

@@ -32,6 +32,8 @@
 //                index is laid out such that all row blocks of one (kv head, split)
 //                land on the same XCD and share its L2.
 
+#include <type_traits>
+
 #include "attn_bf16.h"
 
 namespace pc {
@@ -76,8 +78,14 @@ struct TileRegs {
     int pos;
 };
 
-template <int D, int NW>
-__global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p)
+struct NoTable {
+    int unused;
+};
+
+// PAGED: K, V and positions are read through the prompt's row ranges (p.k, p.v, p.kv_pos unused).
+template <int D, int NW, bool PAGED>
+__global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p,
+                                                            const std::conditional_t<PAGED, KvSegTable, NoTable> tab)
 {
     constexpr int NT = NW * 64;
     constexpr int KB = D / 16;              // MFMA k-blocks over the head dim (QK^T)
@@ -167,22 +175,42 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p)
     float l_run = 0.f;        // this lane's share of the running sum (halves added at the end)
 
     const size_t kv_row_stride = (size_t)p.Hkv * D;  // elements
-    const uint16_t *k_base = p.k + (size_t)seq.kv_begin * kv_row_stride + (size_t)kvh * D;
-    const uint16_t *v_base = p.v + (size_t)seq.kv_begin * kv_row_stride + (size_t)kvh * D;
-    const int32_t *pos_base = p.kv_pos + seq.kv_begin;
+    const uint16_t *k_base = PAGED ? nullptr : p.k + (size_t)seq.kv_begin * kv_row_stride + (size_t)kvh * D;
+    const uint16_t *v_base = PAGED ? nullptr : p.v + (size_t)seq.kv_begin * kv_row_stride + (size_t)kvh * D;
+    const int32_t *pos_base = PAGED ? nullptr : p.kv_pos + seq.kv_begin;
+    KvSegWalker walk;
+    if constexpr (PAGED) walk.init(&tab, seq_i);
+    // PAGED: first byte of row `rc` of this kv head in K and in V, and the row's position ID
+    auto row_ptrs = [&](int rc, int row_hi, const uint16_t *&kp, const uint16_t *&vp, const int32_t *&pp) {
+        if constexpr (PAGED) {
+            const uint8_t *k8, *v8;
+            walk.locate((uint32_t)rc, (uint32_t)row_hi, (uint32_t)(kv_row_stride * 2), (uint32_t)(kvh * D * 2), k8, v8, pp);
+            kp = reinterpret_cast<const uint16_t *>(k8);
+            vp = reinterpret_cast<const uint16_t *>(v8);
+        } else {
+            kp = k_base + (size_t)rc * kv_row_stride;
+            vp = v_base + (size_t)rc * kv_row_stride;
+            pp = pos_base + rc;
+        }
+    };
 
     // global -> registers.  Branch-free: rows at or past k_end are read from the last valid row
     // and then zeroed (position +inf), so all loads of a tile are in flight together.
     auto load_tile = [&](int t, Regs &r) {
         const int row0 = k_begin + t * KT;
         const int last = k_end - 1;
+        const int row_hi = row0 + KT < k_end ? row0 + KT : k_end;
+        if constexpr (PAGED) walk.advance_to((uint32_t)(row0 < last ? row0 : last));
+        const uint16_t *kp, *vp;
+        const int32_t *pp;
 #pragma unroll
         for (int it = 0; it < Regs::K_PER_T; ++it) {
             const int c = tid + it * NT;
             if (K_CHUNKS % NT == 0 || c < K_CHUNKS) {
                 const int row = row0 + c / (D / 8), ch = c % (D / 8);
                 const int rc = row < last ? row : last;
-                u32x4 val = *reinterpret_cast<const u32x4 *>(k_base + (size_t)rc * kv_row_stride + ch * 8);
+                row_ptrs(rc, row_hi, kp, vp, pp);
+                u32x4 val = *reinterpret_cast<const u32x4 *>(kp + ch * 8);
                 if (row > last) val = u32x4{0u, 0u, 0u, 0u};
                 r.k[it] = val;
             }
@@ -196,7 +224,8 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p)
                 for (int e = 0; e < 4; ++e) {
                     const int row = row0 + kg * 4 + e;
                     const int rc = row < last ? row : last;
-                    u32x2 val = *reinterpret_cast<const u32x2 *>(v_base + (size_t)rc * kv_row_stride + dc * 4);
+                    row_ptrs(rc, row_hi, kp, vp, pp);
+                    u32x2 val = *reinterpret_cast<const u32x2 *>(vp + dc * 4);
                     if (row > last) val = u32x2{0u, 0u};
                     r.v[it][e] = val;
                 }
@@ -205,7 +234,8 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p)
         {   // every wave reads the tile's 64 position IDs (one per lane); wave 0's copy is the one stored
             const int row = row0 + lane;
             const int rc = row < last ? row : last;
-            const int pv = pos_base[rc];
+            row_ptrs(rc, row_hi, kp, vp, pp);
+            const int pv = *pp;
             r.pos = row > last ? kPosInf : pv;
         }
     };
@@ -443,18 +473,18 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const uint16_t *part_
     *reinterpret_cast<bf16x8 *>(out + (size_t)row * D + ch * 8) = w8;
 }
 
-template <int D, int NW>
-int launch_variant(pc_ctx *ctx, AttnParams &p, int n_blocks, hipStream_t stream)
+template <int D, int NW, bool PAGED = false, typename Tab = NoTable>
+int launch_variant(pc_ctx *ctx, AttnParams &p, int n_blocks, hipStream_t stream, const Tab &tab = NoTable{0})
 {
     static bool attr_set[16] = {false};
-    auto kern = attn_bf16_kernel<D, NW>;
+    auto kern = attn_bf16_kernel<D, NW, PAGED>;
     const int smem = Lds<D>::TOTAL;
     if (!attr_set[ctx->device & 15]) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
             return PC_E_HIP;
         attr_set[ctx->device & 15] = true;
     }
-    return launch_kernel(ctx, kProfAttn, kern, dim3(n_blocks), dim3(NW * 64), smem, stream, p);
+    return launch_kernel(ctx, kProfAttn, kern, dim3(n_blocks), dim3(NW * 64), smem, stream, p, tab);
 }
 
 }  // namespace
@@ -482,7 +512,7 @@ int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const i
     const bool fits_u32 = max_kv * (long)Hkv * D * 2 < (1L << 32);   // the wide kernel uses 32-bit row offsets
     // a range table is read by the DMA-staged kernel only (32-bit offsets there are per range, checked by the caller)
     // the linear bias (ALiBi) is implemented in the DMA-staged kernel only
-    if ((tab || ctx->use_alibi) && D != 128) return PC_E_UNSUPPORTED;
+    if (ctx->use_alibi && D != 128) return PC_E_UNSUPPORTED;
     if (ctx->use_alibi && !tab && !fits_u32) return PC_E_UNSUPPORTED;
     bool wide = D == 128 && (tab || ctx->use_alibi || (max_row_tiles >= kWideMinRowTiles && fits_u32));
     const int NW = wide ? 4 : (max_row_tiles <= 4 ? 4 : 8);
@@ -536,6 +566,8 @@ int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const i
         waves_used = 8;
     } else if (D == 128) {
         rc = NW == 8 ? launch_variant<128, 8>(ctx, p, n_blocks, stream) : launch_variant<128, 4>(ctx, p, n_blocks, stream);
+    } else if (tab) {   // head_dim 64 read in place
+        rc = NW == 8 ? launch_variant<64, 8, true>(ctx, p, n_blocks, stream, *tab) : launch_variant<64, 4, true>(ctx, p, n_blocks, stream, *tab);
     } else {
         rc = NW == 8 ? launch_variant<64, 8>(ctx, p, n_blocks, stream) : launch_variant<64, 4>(ctx, p, n_blocks, stream);
     }

@@ -6,7 +6,10 @@
 // per lane for the score, then the lanes switch roles and each owns output
 // dimensions lane, lane+64, ... for the P.V accumulation.  Online softmax with the
 // running maximum and sum kept per wave.
+#include <type_traits>
+
 #include "common.h"
+#include "kv_seg.h"
 
 namespace pc {
 namespace {
@@ -42,7 +45,14 @@ struct F32Params {
     AttnBatch batch;
 };
 
-__global__ __launch_bounds__(kWaves * 64) void attn_f32_kernel(const F32Params p)
+struct NoTable {
+    int unused;
+};
+
+// PAGED: K, V and positions are read through the prompt's row ranges (p.k, p.v, p.kv_pos unused).
+template <bool PAGED>
+__global__ __launch_bounds__(kWaves * 64) void attn_f32_kernel(const F32Params p,
+                                                               const std::conditional_t<PAGED, KvSegTable, NoTable> tab)
 {
     __shared__ float s_q[kWaves][kMaxD];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -84,22 +94,41 @@ __global__ __launch_bounds__(kWaves * 64) void attn_f32_kernel(const F32Params p
     float *orow = p.out + ((size_t)q_row * p.Hq + h) * d;
 
     const size_t row_stride = (size_t)p.Hkv * d;
-    const float *kb = p.k + (size_t)seq.kv_begin * row_stride + (size_t)kvh * d;
-    const float *vb = p.v + (size_t)seq.kv_begin * row_stride + (size_t)kvh * d;
-    const int32_t *pb = p.kv_pos + seq.kv_begin;
+    const float *kb = PAGED ? nullptr : p.k + (size_t)seq.kv_begin * row_stride + (size_t)kvh * d;
+    const float *vb = PAGED ? nullptr : p.v + (size_t)seq.kv_begin * row_stride + (size_t)kvh * d;
+    const int32_t *pb = PAGED ? nullptr : p.kv_pos + seq.kv_begin;
+    KvSegWalker walk;
+    if constexpr (PAGED) walk.init(&tab, si);
 
     float m_run = -INFINITY, l_run = 0.f;
     float acc[kMaxD / 64] = {0.f, 0.f, 0.f, 0.f};
 
     for (int j0 = 0; j0 < seq.n_kv; j0 += 64) {
         const int j = j0 + lane;
-        const bool vis = j < seq.n_kv && pb[j] <= qpos;
+        const float *kr = nullptr, *vr_lane = nullptr;   // this lane's key: its K row and V row (head kvh)
+        int kpos = 0;
+        if constexpr (PAGED) {
+            walk.advance_to((uint32_t)j0);
+            const int jc = j < seq.n_kv ? j : seq.n_kv - 1;
+            const uint8_t *kp, *vp;
+            const int32_t *pp;
+            walk.locate((uint32_t)jc, (uint32_t)(j0 + 64 < seq.n_kv ? j0 + 64 : seq.n_kv), (uint32_t)(row_stride * sizeof(float)),
+                        (uint32_t)(kvh * d * sizeof(float)), kp, vp, pp);
+            kr = reinterpret_cast<const float *>(kp);
+            vr_lane = reinterpret_cast<const float *>(vp);
+            kpos = *pp;
+        } else {
+            const int jc = j < seq.n_kv ? j : seq.n_kv - 1;
+            kr = kb + (size_t)jc * row_stride;
+            vr_lane = vb + (size_t)jc * row_stride;
+            kpos = pb[jc];
+        }
+        const bool vis = j < seq.n_kv && kpos <= qpos;
         float s = -INFINITY;
         if (vis) {
-            const float *kr = kb + (size_t)j * row_stride;
             float dot = 0.f;
             for (int c = 0; c < d; ++c) dot = fmaf(s_q[wave][c], kr[c], dot);
-            s = dot - slope * (float)(qpos - pb[j]);   // slope 0 under rotation
+            s = dot - slope * (float)(qpos - kpos);   // slope 0 under rotation
         }
         const float tmax = wave_max_f(s);
         if (tmax == -INFINITY) continue;  // no visible key in these 64 (uniform)
@@ -114,7 +143,10 @@ __global__ __launch_bounds__(kWaves * 64) void attn_f32_kernel(const F32Params p
         for (int kk = 0; kk < n_here; ++kk) {
             const float pk = __shfl(pj, kk, 64);
             if (pk == 0.f) continue;  // uniform: masked or underflowed key contributes nothing
-            const float *vr = vb + (size_t)(j0 + kk) * row_stride;
+            // V row of key j0 + kk: lane kk holds its address
+            const uint64_t va = reinterpret_cast<uint64_t>(vr_lane);
+            const float *vr = reinterpret_cast<const float *>(
+                ((uint64_t)(uint32_t)__shfl((int)(va >> 32), kk, 64) << 32) | (uint32_t)__shfl((int)(uint32_t)va, kk, 64));
 #pragma unroll
             for (int u = 0; u < kMaxD / 64; ++u) {
                 const int c = lane + 64 * u;
@@ -133,7 +165,7 @@ __global__ __launch_bounds__(kWaves * 64) void attn_f32_kernel(const F32Params p
 }  // namespace
 
 int launch_attn_f32(pc_ctx *ctx, const AttnBatch &batch, const float *q, const int32_t *q_pos, const float *k,
-                    const float *v, const int32_t *kv_pos, float *out, hipStream_t stream)
+                    const float *v, const int32_t *kv_pos, float *out, hipStream_t stream, const KvSegTable *tab)
 {
     const int d = ctx->cfg.head_dim;
     if (d > kMaxD || (d & 1)) return PC_E_UNSUPPORTED;
@@ -158,7 +190,8 @@ int launch_attn_f32(pc_ctx *ctx, const AttnBatch &batch, const float *q, const i
     ctx->last_attn.n_splits = 1;
     ctx->last_attn.n_workgroups = blocks;
     ctx->last_attn.waves_per_wg = kWaves;
-    return launch_kernel(ctx, kProfAttn, attn_f32_kernel, dim3(blocks), dim3(kWaves * 64), 0, stream, p);
+    if (tab) return launch_kernel(ctx, kProfAttn, attn_f32_kernel<true>, dim3(blocks), dim3(kWaves * 64), 0, stream, p, *tab);
+    return launch_kernel(ctx, kProfAttn, attn_f32_kernel<false>, dim3(blocks), dim3(kWaves * 64), 0, stream, p, NoTable{0});
 }
 
 }  // namespace pc

@@ -159,10 +159,10 @@ struct AttnBatch {
     AttnSeq seq[kMaxAttnSeqs];
 };
 
-int launch_attn_f32(pc_ctx *ctx, const AttnBatch &batch, const float *q, const int32_t *q_pos, const float *k,
-                    const float *v, const int32_t *kv_pos, float *out, hipStream_t stream);
-
 struct KvSegTable;
+int launch_attn_f32(pc_ctx *ctx, const AttnBatch &batch, const float *q, const int32_t *q_pos, const float *k,
+                    const float *v, const int32_t *kv_pos, float *out, hipStream_t stream, const KvSegTable *tab = nullptr);
+
 int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const int32_t *q_pos, const void *k,
                      const void *v, const int32_t *kv_pos, void *out, hipStream_t stream, const KvSegTable *tab = nullptr);
 

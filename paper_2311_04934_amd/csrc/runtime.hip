@@ -797,7 +797,6 @@ int pc_prefill_attn_shared_batched(pc_ctx *ctx, int layer, const void *Q_new, co
 {
     if (!ctx || n_prompts < 0 || !q_offsets || !mod_offsets) return PC_E_BADARG;
     if (layer < 0 || layer >= ctx->cfg.n_layers) return PC_E_LAYER;
-    if (ctx->cfg.dtype != PC_BF16) return PC_E_UNSUPPORTED;
     long total_q = 0;
     for (int b = 0; b < n_prompts; ++b) {
         const int n = q_offsets[b + 1] - q_offsets[b], nm = mod_offsets[b + 1] - mod_offsets[b];
@@ -860,7 +859,10 @@ int pc_prefill_attn_shared_batched(pc_ctx *ctx, int layer, const void *Q_new, co
             ++ab.n_seqs;
         }
         tab.seg_begin[ab.n_seqs] = n_seg;
-        int rc = launch_attn_bf16(ctx, ab, Q_new, q_pos, nullptr, nullptr, nullptr, out, as_stream(stream), &tab);
+        int rc = ctx->cfg.dtype == PC_F32
+                     ? launch_attn_f32(ctx, ab, static_cast<const float *>(Q_new), q_pos, nullptr, nullptr, nullptr,
+                                       static_cast<float *>(out), as_stream(stream), &tab)
+                     : launch_attn_bf16(ctx, ab, Q_new, q_pos, nullptr, nullptr, nullptr, out, as_stream(stream), &tab);
         if (rc != PC_OK) return rc;
     }
     return PC_OK;

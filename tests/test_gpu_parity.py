@@ -552,21 +552,14 @@ def test_shared_modules_errors_touch_nothing():
         r.close()
 
 
-def test_shared_modules_fp32_context_is_refused():
-    w = W.tiny_fp32()
-    c = build_case(w, 0)
-    r = GpuRunner(c)
-    p0 = c.prompts[0]
-    dev = r.dev
-    n = len(p0.q_pos)
-    try:
-        with pytest.raises(pcb.PcError) as e:
-            r.pc.pc_prefill_attn_shared_batched(0, p0.Q.to(dev), torch.from_numpy(p0.q_pos).to(dev), [0, n],
-                                                [p0.module_ids], p0.K_new.to(dev), p0.V_new.to(dev),
-                                                torch.zeros_like(p0.Q, device=dev))
-        assert e.value.status == -9
-    finally:
-        r.close()
+@pytest.mark.parametrize("dtype,hq,hkv,d", [("f32", 6, 2, 64), ("f32", 4, 4, 32), ("bf16", 8, 8, 64), ("bf16", 8, 2, 64)])
+def test_shared_modules_other_kernels(dtype, hq, hkv, d):
+    """The fp32 kernel and the register-staged bf16 kernel (head_dim 64) read the modules in place as well:
+    odd module sizes, ranges that start and end inside 64-key tiles, a prompt without modules."""
+    w = W.custom(f"shared_{dtype}_{d}", dtype, hq, hkv, d, [300, 64, 90, 70, 120, 33, 5, 1, 7], [-1, 0, 0, 0, 1, 1, -1, -1, -1],
+                 [W.Prompt([0, 1, 4], 40), W.Prompt([4, 2, 0], 17), W.Prompt([], 9), W.Prompt([3, 0, 5], 64),
+                  W.Prompt([0], 1), W.Prompt([6, 7, 8, 1, 5], 33), W.Prompt([8, 0, 7, 6], 130)], max_pos=1024)
+    _shared_run(w, 0, None)
 
 
 # ------------------------------------------------------------------ modules kept in host memory (Sec. 4.1)
@@ -701,8 +694,6 @@ def _alibi_run(w, layer, q_sample, in_place=False, slopes=None):
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("in_place", [False, True])
 def test_alibi_small_ragged_batch(dtype, in_place):
-    if dtype == "f32" and in_place:
-        pytest.skip("modules are read in place by the bf16 kernel only")
     hq, hkv, d = (8, 2, 128) if dtype == "bf16" else (6, 2, 64)
     w = W.custom("alibi_small", dtype, hq, hkv, d, [300, 64, 90, 70, 120, 33], [-1, 0, 0, 0, 1, 1],
                  [W.Prompt([0, 1, 4], 40), W.Prompt([4, 2, 0], 17), W.Prompt([], 9), W.Prompt([3, 0, 5], 64),
@@ -863,7 +854,7 @@ def test_random_workloads_packed_path(seed):
     _batched_run(w, 0, None, fused=bool(seed & 1))
 
 
-@pytest.mark.parametrize("seed", [2, 3, 4, 8, 9, 10])
+@pytest.mark.parametrize("seed", range(12))
 def test_random_workloads_modules_in_place(seed):
     _shared_run(_random_workload(seed), 0, None)
 
