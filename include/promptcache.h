@@ -303,8 +303,7 @@ int pc_resolve_scaffolds(int n_ids, const int *ids, int n_scaffolds, const int *
  *                  unrotated (modules must then be stored unrotated too).  slopes == NULL switches
  *                  back to rotation.  A set-up call: it copies synchronously and must not overlap
  *                  with attention calls in flight on the context.
- *                  bf16 contexts need head_dim 128 for attention in this mode
- *                  (PC_E_UNSUPPORTED from the attention calls otherwise); fp32: any even head_dim.
+ *                  Every dtype and head_dim the rotary path serves.
  * pc_alibi_slopes  the sequence that encoding's authors define (host helper, no context):
  *                  n a power of two: 2^(-8/n), 2^(-16/n), ...; otherwise the sequence of the
  *                  largest power of two below n followed by the odd members of the next one.

@@ -153,7 +153,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p,
                 uint32_t wl = lo[e >> 1], wh = hi[e >> 1];
                 float xl = bf16_bits_to_f32((e & 1) ? (wl >> 16) : (wl & 0xffffu));
                 float xh = bf16_bits_to_f32((e & 1) ? (wh >> 16) : (wh & 0xffffu));
-                float2 cs = trow[d0 + e];
+                float2 cs = p.alibi ? make_float2(1.f, 0.f) : trow[d0 + e];   // linear bias: Q is used as it is
                 olo[e] = (__bf16)((xl * cs.x - xh * cs.y) * p.q_scale);
                 ohi[e] = (__bf16)((xh * cs.x + xl * cs.y) * p.q_scale);
             }
@@ -161,6 +161,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p,
             qf[kb + KB / 2] = ohi;
         }
     }
+    const float slope2 = p.alibi ? p.alibi[head] * 1.4426950408889634f : 0.f;
     // position range of this wave's real queries (decides masking per key tile)
     const int wave_min_qpos = wave_min_i32(q_valid ? my_qpos : kPosInf);
     const int wave_max_qpos = wave_max_i32(q_valid ? my_qpos : -1);
@@ -295,6 +296,16 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p,
 
     // mask (if needed) + online softmax of one score tile; rescales O when the running max moved
     auto softmax = [&](f32x16 &s, const int32_t *sPos, int sub, bool need_mask, bf16x8 pf[2]) {
+        if (p.alibi) {
+            // linear bias on position IDs (Sec. 4.2): + slope * (pos_k - ref) in the log2 domain; the part that
+            // depends on the query only is constant per softmax row and is left out
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+                const u32x4 kp = *reinterpret_cast<const u32x4 *>(sPos + sub * 32 + 8 * i4 + 4 * hh);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) s[i4 * 4 + e] += slope2 * (float)((int)kp[e] - wave_min_qpos);
+            }
+        }
         if (need_mask) {
             // accumulator register i holds key 8*(i/4) + 4*hh + i%4 of the sub-tile
 #pragma unroll
@@ -511,10 +522,7 @@ int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const i
     for (int s = 0; s < batch.n_seqs; ++s) max_kv = batch.seq[s].n_kv > max_kv ? batch.seq[s].n_kv : max_kv;
     const bool fits_u32 = max_kv * (long)Hkv * D * 2 < (1L << 32);   // the wide kernel uses 32-bit row offsets
     // a range table is read by the DMA-staged kernel only (32-bit offsets there are per range, checked by the caller)
-    // the linear bias (ALiBi) is implemented in the DMA-staged kernel only
-    if (ctx->use_alibi && D != 128) return PC_E_UNSUPPORTED;
-    if (ctx->use_alibi && !tab && !fits_u32) return PC_E_UNSUPPORTED;
-    bool wide = D == 128 && (tab || ctx->use_alibi || (max_row_tiles >= kWideMinRowTiles && fits_u32));
+    bool wide = D == 128 && (tab || (max_row_tiles >= kWideMinRowTiles && fits_u32));
     const int NW = wide ? 4 : (max_row_tiles <= 4 ? 4 : 8);
     const int tiles_per_wg = wide ? kWideRowTilesPerWg : NW;
     const int rb_max = (max_row_tiles + tiles_per_wg - 1) / tiles_per_wg;

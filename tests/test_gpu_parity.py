@@ -709,20 +709,30 @@ def test_alibi_text_inside_a_gap_and_flat_slopes():
     _alibi_run(w, 0, None, slopes=[0.0, 0.5, 0.0, 0.01, 1.5, 0.25, 0.0, 0.003])
 
 
-def test_alibi_bf16_head_dim_64_is_refused():
-    w = W.custom("alibi_d64", "bf16", 8, 8, 64, [64], None, [W.Prompt([0], 8)], max_pos=256)
-    c = build_case(w, 0, encode_keys=False)
+@pytest.mark.parametrize("hq,hkv,d,in_place", [(8, 8, 64, False), (8, 2, 64, True), (4, 4, 128, False)])
+def test_alibi_register_staged_kernel(hq, hkv, d, in_place):
+    """head_dim 64, and head_dim 128 with few query rows per kv head: the kernel that stages K/V through registers."""
+    w = W.custom("alibi_narrow", "bf16", hq, hkv, d, [300, 64, 90, 70, 120, 33], [-1, 0, 0, 0, 1, 1],
+                 [W.Prompt([0, 1, 4], 40), W.Prompt([4, 2, 0], 17), W.Prompt([], 9), W.Prompt([3, 0, 5], 64),
+                  W.Prompt([0], 1)], max_pos=1024)
+    _alibi_run(w, 0, None, in_place=in_place)
+
+
+def test_alibi_argument_checks_and_switching_back():
+    w = W.custom("alibi_args", "bf16", 8, 8, 64, [64], None, [W.Prompt([0], 8)], max_pos=256)
+    c = build_case(w, 0)
     r = GpuRunner(c)
     try:
-        r.pc.pc_set_alibi(pcb.pc_alibi_slopes(8))
-        with pytest.raises(pcb.PcError) as e:
-            r.serve(0)
-        assert e.value.status == -9
         with pytest.raises(pcb.PcError) as e:
             r.pc.pc_set_alibi([0.5] * 7 + [-1.0])
         assert e.value.status == -1
-        r.pc.pc_set_alibi(None)          # back to rotation: the same call now works
-        r.serve(0)
+        with pytest.raises(pcb.PcError) as e:
+            r.pc.pc_set_alibi([0.5] * 7 + [float("nan")])
+        assert e.value.status == -1
+        r.pc.pc_set_alibi(pcb.pc_alibi_slopes(8))
+        r.pc.pc_set_alibi(None)          # back to rotation: results follow the rotary oracle again
+        res = r.serve(0)
+        check_attention(c, 0, res, None, "/rope after alibi")
     finally:
         r.close()
 
