@@ -426,7 +426,7 @@ def main() -> int:
         result["kernels_us_median_min"] = {k: [round(v["median_us"], 2), round(v["min_us"], 2)] for k, v in kern.items() if v["avg_us"]}
         result["assemble_GBps"] = round(gat_gbs, 1)
         result["attn_kernel_TFLOPs"] = round(attn_tf, 1)
-        result["roofline"] = {"kernel": ("attn_bf16_dma_kernel<1, 8, %s, %s>" % ("true" if in_place else "false", "true" if args.alibi else "false")) if (w.head_dim == 128 and launch[2] == 8 and launch[0] >= 1 and w.n_q_heads // w.n_kv_heads * ((n_new[0] + 31) // 32) >= 8) else "attn_bf16_kernel", "bound": "mfma", "achieved": round(attn_tf, 1),
+        result["roofline"] = {"kernel": ("attn_bf16_dma_kernel<1, 8, %s, %s>" % ("true" if in_place else "false", "true" if args.alibi else "false")) if (w.head_dim == 128 and (in_place or w.n_q_heads // w.n_kv_heads * ((max(n_new) + 31) // 32) >= 4)) else "attn_bf16_kernel", "bound": "mfma", "achieved": round(attn_tf, 1),
                               "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                               "frac": round(attn_tf / MFMA_BF16_PEAK_TFLOPS, 4),
                               "traffic": None if in_place else MEASURED_TRAFFIC.get((w.name, 32), {}).get("attn")}
