@@ -191,6 +191,8 @@ def main() -> int:
     ap.add_argument("--host-tier", choices=["kernel", "engine"], default=None,
                     help="keep the modules in pinned host memory (Sec. 4.1) and bring them in at every use: 'kernel' = "
                          "the assembly kernel loads them over the host link, 'engine' = copy-engine transfers")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="add what this machine sustains on a plain copy and on matrix instructions alone to the JSON line")
     ap.add_argument("--length-sweep", action="store_true",
                     help="instead of the step benchmark: copy time vs attention recompute time for 1K..16K cached tokens")
     ap.add_argument("--alibi", action="store_true",
@@ -447,6 +449,10 @@ def main() -> int:
                                                 "frac": round(h2d_layer / (g_us * 1e-6) / 1e9 / 64.0, 4) if args.host_tier == "kernel" else None})
         if "roofline" in result:
             result["roofline"]["traffic"] = None
+
+    if args.calibrate:
+        result["achievable"] = {"copy_GBps": round(pc.pc_calib_copy(1 << 30, 10), 1), "mfma_bf16_TFLOPs": round(pc.pc_calib_mfma(4000), 1),
+                                "note": "plain copy kernel over 1 GiB (read+write bytes); 8 waves per CU issuing only 32x32x16 bf16 MFMAs"}
 
     # ---------------- full prefill of the same prompt with the same kernel (ordinary causal mask), one layer
     if not args.no_full_prefill and B == 1 and not in_place:

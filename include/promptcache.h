@@ -394,6 +394,18 @@ long pc_bytes_per_token(int n_layers, int n_kv_heads, int head_dim, int dtype);
 /* Look a stored module up: PC_OK and its length/start, or PC_E_UNKNOWN_MODULE. */
 int pc_module_info(const pc_ctx *ctx, int layer, int module_id, int *n_tokens, int *start_pos);
 
+/*
+ * Calibration for benchmarks (synchronous, allocate and free their own buffers; not for the
+ * request path): what this machine sustains on the two roofs the kernels are held against.
+ *   pc_calib_copy   a plain device-to-device copy kernel over `bytes` bytes, `repeats` launches;
+ *                   *gb_per_s = read + written bytes per second.
+ *   pc_calib_mfma   one workgroup of 8 waves per CU, each wave issuing iters x 16
+ *                   v_mfma_f32_32x32x16_bf16 on independent accumulators and nothing else;
+ *                   *tflop_per_s = dense bf16 rate reached.
+ */
+int pc_calib_copy(pc_ctx *ctx, size_t bytes, int repeats, double *gb_per_s);
+int pc_calib_mfma(pc_ctx *ctx, int iters, double *tflop_per_s);
+
 /* Bytes of pool in use / total. */
 int pc_pool_usage(const pc_ctx *ctx, size_t *used, size_t *total);
 

@@ -26,7 +26,7 @@ EXPORTS = [
     "pc_module_info", "pc_pool_usage", "pc_last_attn_launch", "pc_profile_enable", "pc_profile_read",
     "pc_profile_read_each", "pc_set_module_params", "pc_fill_params",
     "pc_host_pool_reserve", "pc_store_module_host", "pc_set_host_copy_mode", "pc_set_alibi", "pc_alibi_slopes",
-    "pc_define_scaffold", "pc_resolve_scaffolds",
+    "pc_define_scaffold", "pc_resolve_scaffolds", "pc_calib_copy", "pc_calib_mfma",
 ]
 PROF_GATHER, PROF_APPEND, PROF_ATTN, PROF_COMBINE, PROF_ROPE = range(5)
 PC_POS_NONE = 0x7FFFFFFF
@@ -81,6 +81,8 @@ def lib() -> ctypes.CDLL:
     L.pc_alibi_slopes.argtypes = [i, vp]
     L.pc_define_scaffold.argtypes = [vp, i, vp, vp]
     L.pc_resolve_scaffolds.argtypes = [i, vp, i, vp, vp, vp, vp]
+    L.pc_calib_copy.argtypes = [vp, ctypes.c_size_t, i, ctypes.POINTER(ctypes.c_double)]
+    L.pc_calib_mfma.argtypes = [vp, i, ctypes.POINTER(ctypes.c_double)]
     L.pc_set_module_params.argtypes = [vp, i, i, vp, vp]
     L.pc_fill_params.argtypes = [vp, i, vp, i, i, vp, vp, vp, vp, vp, vp, vp, vp, i, vp]
     L.pc_schema_layout.argtypes = [i, vp, vp, vp]
@@ -316,6 +318,16 @@ class PromptCache:
 
     def pc_set_host_copy_mode(self, mode: int) -> None:
         _check(lib().pc_set_host_copy_mode(self._ctx, int(mode)), "pc_set_host_copy_mode")
+
+    def pc_calib_copy(self, n_bytes: int, repeats: int = 10) -> float:
+        v = ctypes.c_double(0.0)
+        _check(lib().pc_calib_copy(self._ctx, int(n_bytes), int(repeats), ctypes.byref(v)), "pc_calib_copy")
+        return v.value
+
+    def pc_calib_mfma(self, iters: int = 4000) -> float:
+        v = ctypes.c_double(0.0)
+        _check(lib().pc_calib_mfma(self._ctx, int(iters), ctypes.byref(v)), "pc_calib_mfma")
+        return v.value
 
     def pc_define_scaffold(self, member_ids: Sequence[int], override_ids: Sequence[int]) -> None:
         m, o = _ints(member_ids), _ints(override_ids)

@@ -18,7 +18,7 @@ INCLUDE = os.path.join(ROOT, "include")
 OBJDIR = os.path.join(ROOT, "_build")
 LIB = os.path.join(HERE, "libpromptcache.so")
 
-SOURCES = ["runtime.hip", "gather.hip", "rope.hip", "attn_f32.hip", "attn_bf16.hip", "attn_bf16_wide.hip"]
+SOURCES = ["runtime.hip", "gather.hip", "rope.hip", "attn_f32.hip", "attn_bf16.hip", "attn_bf16_wide.hip", "calib.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
