@@ -1,5 +1,5 @@
-// Declarations shared by the two bf16 attention kernels (narrow: 32 query rows per wave;
-// wide: 64 query rows per wave) and their launcher.
+// Declarations shared by the two bf16 attention kernels (register-staged: attn_bf16.hip; DMA-staged:
+// attn_bf16_wide.hip; both 32 query rows per wave) and their launcher.
 #pragma once
 
 #include "common.h"

@@ -517,7 +517,7 @@ int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const i
     }
     if (total_q == 0 || max_row_tiles == 0) return PC_OK;
 
-    // wide kernel: head_dim 128 and enough stacked query rows per kv head to fill 64-row waves
+    // DMA-staged kernel: every head_dim-128 call whose packed buffer fits 32-bit row offsets (or is read in place)
     long max_kv = 0;
     for (int s = 0; s < batch.n_seqs; ++s) max_kv = batch.seq[s].n_kv > max_kv ? batch.seq[s].n_kv : max_kv;
     const bool fits_u32 = max_kv * (long)Hkv * D * 2 < (1L << 32);   // the wide kernel uses 32-bit row offsets

@@ -128,7 +128,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
     const int k_end = k_begin + share < seq.n_kv ? k_begin + share : seq.n_kv;
     const int n_tiles = (k_end - k_begin + KT - 1) / KT;
 
-    // ---- this wave's two row tiles
+    // ---- this wave's row tile
     QTile qt[NQT];
 #pragma unroll
     for (int x = 0; x < NQT; ++x) {
