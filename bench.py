@@ -32,8 +32,12 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 # HBM bytes per launch from rocprofv3 FETCH_SIZE (x1.988, calibrated on a copy of known size) + WRITE_SIZE;
-# the summaries are kept under profiles/.  Only known for the default workload and launch mode.
-MEASURED_TRAFFIC = {("long_doc_8k", 32): {"attn": 52.4e6 + 17.3e6, "gather": 34.6e6 + 34.6e6}}
+# the summaries are kept under profiles/.  Only known for the default workload in the fused-launch, packed-copy mode
+# (keyed by where Q is rotated).
+# --q-rotation auto: the largest number of uncached tokens per step for which Q is rotated in the assembly launch
+ROTATE_ONCE_MAX_TOKENS = 1024
+MEASURED_TRAFFIC = {("long_doc_8k", "once"): {"attn": 51.3e6 + 17.3e6, "gather": 36.7e6 + 36.7e6},
+                    ("long_doc_8k", "attention"): {"attn": 52.4e6 + 17.3e6, "gather": 34.6e6 + 34.6e6}}
 
 
 def attn_flops(w, prompt_lens, n_new):
@@ -197,6 +201,12 @@ def main() -> int:
                     help="instead of the step benchmark: copy time vs attention recompute time for 1K..16K cached tokens")
     ap.add_argument("--alibi", action="store_true",
                     help="position as a linear bias on the scores (Sec. 4.2, ALiBi) instead of a rotation; no CPU baseline")
+    ap.add_argument("--q-rotation", choices=["auto", "once", "attention"], default="auto",
+                    help="once: Q is rotated once per token in the assembly launch (pc_assemble_append_rotate_batched + "
+                         "pc_prefill_attn_rotated_batched); attention: inside every attention workgroup "
+                         "(pc_assemble_append_kv_batched + pc_prefill_attn_batched); auto: once up to "
+                         f"{ROTATE_ONCE_MAX_TOKENS} uncached tokens per step (beyond that the extra pass over Q costs "
+                         "more HBM time than the attention workgroups save)")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step (all layers' launches) into a HIP graph and time K replays of it")
     ap.add_argument("--overlap", action="store_true",
@@ -289,6 +299,11 @@ def main() -> int:
     n_out = np.zeros(B, dtype=np.intc)
     hp = lambda a: ctypes.c_void_p(a.ctypes.data)
     calls = []
+    # default step: Q is rotated once per token in the assembly launch and attention takes it rotated
+    want_once = args.q_rotation == "once" or (args.q_rotation == "auto" and int(q_off[-1]) <= ROTATE_ONCE_MAX_TOKENS)
+    rot_once = want_once and not (args.separate_launches or args.overlap)
+    calls_rot = []
+    Q_rot = [torch.empty_like(q) for q in Q] if rot_once else None
     for layer in range(L):
         a_asm = (ctx, layer, hp(ids_flat), hp(mod_offs), B, P(asm_K[layer]), P(asm_V[layer]), P(asm_pos[layer]),
                  hp(kv_off_c), hp(n_out), asm_stream)
@@ -299,8 +314,15 @@ def main() -> int:
         a_fus = (ctx, layer, hp(ids_flat), hp(mod_offs), B, P(Kn[layer]), P(Vn[layer]), P(q_pos), hp(q_off_c),
                  P(asm_K[layer]), P(asm_V[layer]), P(asm_pos[layer]), hp(kv_off_c), hp(n_out), asm_stream)
         calls.append((a_asm, a_app, a_att, a_fus))
+        if rot_once and not args.modules_in_place:
+            a_fusr = (ctx, layer, hp(ids_flat), hp(mod_offs), B, P(Kn[layer]), P(Vn[layer]), P(Q[layer]), P(q_pos), hp(q_off_c),
+                      P(asm_K[layer]), P(asm_V[layer]), P(asm_pos[layer]), hp(kv_off_c), hp(n_out), P(Q_rot[layer]), asm_stream)
+            a_attr = (ctx, layer, P(Q_rot[layer]), P(q_pos), hp(q_off_c), B, P(asm_K[layer]), P(asm_V[layer]), P(asm_pos[layer]),
+                      hp(kv_off_c), hp(kv_len_c), P(out[layer]), stream)
+            calls_rot.append((a_fusr, a_attr))
     f_asm, f_app, f_att = lib.pc_assemble_kv_batched, lib.pc_append_kv_batched, lib.pc_prefill_attn_batched
     f_fus = lib.pc_assemble_append_kv_batched
+    f_fusr, f_attr = lib.pc_assemble_append_rotate_batched, lib.pc_prefill_attn_rotated_batched
     fused = not args.separate_launches
     in_place = args.modules_in_place
     if in_place:
@@ -317,6 +339,9 @@ def main() -> int:
                       P(tail_pos), hp(q_off_c), hp(zeros_c), stream)
             a_shr = (ctx, layer, P(Q[layer]), P(q_pos), hp(q_off_c), B, hp(ids_flat), hp(mod_offs), P(tail_K[layer]),
                      P(tail_V[layer]), P(out[layer]), stream)
+            if rot_once:   # the tail's append launch also rotates Q; attention takes it rotated
+                a_tail = a_tail[:4] + (P(Q[layer]),) + a_tail[4:-1] + (P(Q_rot[layer]), stream)
+                a_shr = a_shr[:2] + (P(Q_rot[layer]),) + a_shr[3:]
             calls_ip.append((a_tail, a_shr))
 
     if args.overlap:
@@ -327,8 +352,9 @@ def main() -> int:
 
     def step():
         if in_place:
+            f_tail, f_sh = (lib.pc_append_rotate_batched, lib.pc_prefill_attn_shared_rotated_batched) if rot_once else (f_app, f_shr)
             for a_tail, a_shr in calls_ip:
-                rc = f_app(*a_tail) or f_shr(*a_shr)
+                rc = f_tail(*a_tail) or f_sh(*a_shr)
                 if rc:
                     raise pcb.PcError(rc, "bench step (modules in place)")
             return
@@ -345,6 +371,12 @@ def main() -> int:
                 ev_att[l].record(main_t)
                 if rc:
                     raise pcb.PcError(rc, "bench step (overlapped)")
+            return
+        if rot_once:
+            for a_fusr, a_attr in calls_rot:
+                rc = f_fusr(*a_fusr) or f_attr(*a_attr)
+                if rc:
+                    raise pcb.PcError(rc, "bench step (Q rotated once)")
             return
         for a_asm, a_app, a_att, a_fus in calls:
             rc = (f_fus(*a_fus) if fused else (f_asm(*a_asm) or f_app(*a_app))) or f_att(*a_att)
@@ -399,6 +431,8 @@ def main() -> int:
         gather_bytes_layer = sum(n_new) * (2 * 2 * w.row_bytes + 8)
     elif fused:   # the same launch also reads and writes the uncached tokens' rows (and reads/writes their position IDs)
         gather_bytes_layer += sum(n_new) * (2 * 2 * w.row_bytes + 8)
+    if rot_once:   # the same launch reads Q_new and writes Q_rot
+        gather_bytes_layer += sum(n_new) * 2 * w.n_q_heads * w.head_dim * w.elem_bytes
     attn_tflops_step = flops_layer * L / (ms_per_step * 1e-3) / 1e12
 
     result = {
@@ -412,7 +446,7 @@ def main() -> int:
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "kv_path": "modules read in place" if in_place else "packed copy",
                    "module_tier": ("host memory, " + ("loaded by the assembly kernel" if args.host_tier == "kernel" else "copy engine")) if args.host_tier else "HBM pool",
-                   "overlap": bool(args.overlap), "hip_graph": bool(args.graph), "position_encoding": "alibi" if args.alibi else "rope", "layers": L, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
+                   "q_rotation": "once per token, in the assembly launch" if rot_once else "in every attention workgroup", "overlap": bool(args.overlap), "hip_graph": bool(args.graph), "position_encoding": "alibi" if args.alibi else "rope", "layers": L, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
                    "head_dim": w.head_dim, "prompts": B, "module_tokens": n_mod if B <= 4 else [n_mod[0], "..."],
                    "uncached_tokens": n_new[0], "attn_launch": {"kv_splits": launch[0], "workgroups": launch[1],
                                                               "waves_per_wg": launch[2]}},
@@ -428,13 +462,15 @@ def main() -> int:
         result["kernels_us_median_min"] = {k: [round(v["median_us"], 2), round(v["min_us"], 2)] for k, v in kern.items() if v["avg_us"]}
         result["assemble_GBps"] = round(gat_gbs, 1)
         result["attn_kernel_TFLOPs"] = round(attn_tf, 1)
-        result["roofline"] = {"kernel": ("attn_bf16_dma_kernel<1, 8, %s, %s>" % ("true" if in_place else "false", "true" if args.alibi else "false")) if (w.head_dim == 128 and (in_place or w.n_q_heads // w.n_kv_heads * ((max(n_new) + 31) // 32) >= 4)) else "attn_bf16_kernel", "bound": "mfma", "achieved": round(attn_tf, 1),
+        plain = fused and not (in_place or args.overlap or args.alibi or args.host_tier)
+        traffic_known = MEASURED_TRAFFIC.get((w.name, "once" if rot_once else "attention"), {}) if plain else {}
+        result["roofline"] = {"kernel": ("attn_bf16_dma_kernel<1, 8, %s, %s>" % ("true" if in_place else "false", "true" if args.alibi else "false")) if w.head_dim == 128 else "attn_bf16_kernel", "bound": "mfma", "achieved": round(attn_tf, 1),
                               "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                               "frac": round(attn_tf / MFMA_BF16_PEAK_TFLOPS, 4),
-                              "traffic": None if in_place else MEASURED_TRAFFIC.get((w.name, 32), {}).get("attn")}
+                              "traffic": traffic_known.get("attn")}
         result["roofline_assemble"] = {"kernel": "append_kernel" if in_place else ("gather_append_kernel" if fused else "gather_kv_kernel"), "bound": "hbm", "achieved": round(gat_gbs, 1),
                                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gat_gbs / HBM_PEAK_GBS, 4),
-                                       "traffic": None if in_place else MEASURED_TRAFFIC.get((w.name, 32), {}).get("gather")}
+                                       "traffic": traffic_known.get("gather")}
 
     if args.host_tier:
         # PCIe-inclusive view: the modules' K and V cross the host link once per layer and step

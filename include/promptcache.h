@@ -268,6 +268,43 @@ int pc_prefill_attn_batched(pc_ctx *ctx, int layer, const void *Q_new, const int
                             void *out, void *stream);
 
 /*
+ * Sec. 4.2 (rotation looked up by position ID), applied once per token instead of once per
+ * attention workgroup: the calls below do what pc_append_kv_batched /
+ * pc_assemble_append_kv_batched do and, in the same launch, also write
+ *     Q_rot[row] = rotation of Q_new[row] at q_pos[row], times the attention kernels' score scale
+ * (Q_new, Q_rot: device [total_q, n_q_heads, head_dim], 16-byte aligned, distinct buffers; under
+ * pc_set_alibi the rows are only scaled).  Q_rot is an operand for the *_rotated attention calls
+ * and nothing else: the scale folded in is 1/sqrt(head_dim) for fp32 contexts and
+ * log2(e)/sqrt(head_dim) for bf16 ones.
+ *   pc_append_rotate_batched            arguments of pc_append_kv_batched + Q_new, Q_rot
+ *   pc_assemble_append_rotate_batched   arguments of pc_assemble_append_kv_batched + Q_new, Q_rot
+ *   pc_prefill_attn_rotated_batched,
+ *   pc_prefill_attn_shared_rotated_batched   as their namesakes, with Q_rot in place of Q_new; the
+ *                                        results are those of the namesakes on Q_new
+ * Every attention workgroup otherwise rotates its queries itself, once per KV split; with the
+ * rotation done here that part of the kernels' prologue goes away.
+ */
+int pc_append_rotate_batched(pc_ctx *ctx, int layer, const void *K_new_raw, const void *V_new,
+                             const void *Q_new, const int32_t *q_pos, const int *q_offsets,
+                             int n_prompts, void *asm_K, void *asm_V, int32_t *asm_pos,
+                             const int *kv_offsets, const int *kv_lens, void *Q_rot, void *stream);
+int pc_assemble_append_rotate_batched(pc_ctx *ctx, int layer, const int *module_ids_flat,
+                                      const int *mod_offsets, int n_prompts, const void *K_new_raw,
+                                      const void *V_new, const void *Q_new, const int32_t *q_pos,
+                                      const int *q_offsets, void *out_K, void *out_V, int32_t *out_pos,
+                                      const int *kv_offsets, int *out_n_tokens, void *Q_rot,
+                                      void *stream);
+int pc_prefill_attn_rotated_batched(pc_ctx *ctx, int layer, const void *Q_rot, const int32_t *q_pos,
+                                    const int *q_offsets, int n_prompts, const void *asm_K,
+                                    const void *asm_V, const int32_t *asm_pos, const int *kv_offsets,
+                                    const int *kv_lens, void *out, void *stream);
+int pc_prefill_attn_shared_rotated_batched(pc_ctx *ctx, int layer, const void *Q_rot,
+                                           const int32_t *q_pos, const int *q_offsets, int n_prompts,
+                                           const int *module_ids_flat, const int *mod_offsets,
+                                           const void *K_tail, const void *V_tail, void *out,
+                                           void *stream);
+
+/*
  * Sec. 3.3 ("attention masking effect"), scaffolding: a scaffold is a set of prompt modules
  * that was ALSO encoded jointly, so that its members share one attention span.  When a prompt
  * imports every member of a scaffold, the jointly encoded states override the members' own.

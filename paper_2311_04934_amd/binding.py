@@ -27,6 +27,8 @@ EXPORTS = [
     "pc_profile_read_each", "pc_set_module_params", "pc_fill_params",
     "pc_host_pool_reserve", "pc_store_module_host", "pc_set_host_copy_mode", "pc_set_alibi", "pc_alibi_slopes",
     "pc_define_scaffold", "pc_resolve_scaffolds", "pc_calib_copy", "pc_calib_mfma",
+    "pc_append_rotate_batched", "pc_assemble_append_rotate_batched", "pc_prefill_attn_rotated_batched",
+    "pc_prefill_attn_shared_rotated_batched",
 ]
 PROF_GATHER, PROF_APPEND, PROF_ATTN, PROF_COMBINE, PROF_ROPE = range(5)
 PC_POS_NONE = 0x7FFFFFFF
@@ -83,6 +85,10 @@ def lib() -> ctypes.CDLL:
     L.pc_resolve_scaffolds.argtypes = [i, vp, i, vp, vp, vp, vp]
     L.pc_calib_copy.argtypes = [vp, ctypes.c_size_t, i, ctypes.POINTER(ctypes.c_double)]
     L.pc_calib_mfma.argtypes = [vp, i, ctypes.POINTER(ctypes.c_double)]
+    L.pc_append_rotate_batched.argtypes = [vp, i, vp, vp, vp, vp, vp, i, vp, vp, vp, vp, vp, vp, vp]
+    L.pc_assemble_append_rotate_batched.argtypes = [vp, i, vp, vp, i, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    L.pc_prefill_attn_rotated_batched.argtypes = [vp, i, vp, vp, vp, i, vp, vp, vp, vp, vp, vp, vp]
+    L.pc_prefill_attn_shared_rotated_batched.argtypes = [vp, i, vp, vp, vp, i, vp, vp, vp, vp, vp, vp]
     L.pc_set_module_params.argtypes = [vp, i, i, vp, vp]
     L.pc_fill_params.argtypes = [vp, i, vp, i, i, vp, vp, vp, vp, vp, vp, vp, vp, i, vp]
     L.pc_schema_layout.argtypes = [i, vp, vp, vp]
@@ -318,6 +324,51 @@ class PromptCache:
 
     def pc_set_host_copy_mode(self, mode: int) -> None:
         _check(lib().pc_set_host_copy_mode(self._ctx, int(mode)), "pc_set_host_copy_mode")
+
+    # -- Q rotated once per token (in the append launch) instead of in every attention workgroup
+    def pc_append_rotate_batched(self, layer: int, K_new_raw, V_new, Q_new, q_pos, q_offsets: Sequence[int], asm_K, asm_V,
+                                 asm_pos, kv_offsets: Sequence[int], kv_lens: Sequence[int], Q_rot, stream=None) -> None:
+        qo, kvo, kvl = _ints(q_offsets), _ints(kv_offsets), _ints(kv_lens)
+        B = len(kvl)
+        assert len(qo) == B + 1 and len(kvo) == B + 1
+        _check(lib().pc_append_rotate_batched(self._ctx, layer, _dev(K_new_raw), _dev(V_new), _dev(Q_new), _dev(q_pos),
+                                              _np_ptr(qo), B, _dev(asm_K), _dev(asm_V), _dev(asm_pos), _np_ptr(kvo),
+                                              _np_ptr(kvl), _dev(Q_rot), _stream(stream)), "pc_append_rotate_batched")
+
+    def pc_assemble_append_rotate_batched(self, layer: int, module_ids: Sequence[Sequence[int]], K_new_raw, V_new, Q_new,
+                                          q_pos, q_offsets: Sequence[int], out_K, out_V, out_pos,
+                                          kv_offsets: Sequence[int], Q_rot, stream=None) -> List[int]:
+        flat = _ints([m for ids in module_ids for m in ids])
+        offs = _ints(np.concatenate([[0], np.cumsum([len(ids) for ids in module_ids])]))
+        qo, kvo = _ints(q_offsets), _ints(kv_offsets)
+        B = len(module_ids)
+        assert len(qo) == B + 1 and len(kvo) == B + 1
+        n_out = np.zeros(max(B, 1), dtype=np.intc)
+        _check(lib().pc_assemble_append_rotate_batched(self._ctx, layer, _np_ptr(flat), _np_ptr(offs), B, _dev(K_new_raw),
+                                                       _dev(V_new), _dev(Q_new), _dev(q_pos), _np_ptr(qo), _dev(out_K),
+                                                       _dev(out_V), _dev(out_pos), _np_ptr(kvo), _np_ptr(n_out), _dev(Q_rot),
+                                                       _stream(stream)), "pc_assemble_append_rotate_batched")
+        return [int(x) for x in n_out[:B]]
+
+    def pc_prefill_attn_rotated_batched(self, layer: int, Q_rot, q_pos, q_offsets: Sequence[int], asm_K, asm_V, asm_pos,
+                                        kv_offsets: Sequence[int], kv_lens: Sequence[int], out, stream=None) -> None:
+        qo, kvo, kvl = _ints(q_offsets), _ints(kv_offsets), _ints(kv_lens)
+        B = len(kvl)
+        assert len(qo) == B + 1 and len(kvo) == B + 1
+        _check(lib().pc_prefill_attn_rotated_batched(self._ctx, layer, _dev(Q_rot), _dev(q_pos), _np_ptr(qo), B, _dev(asm_K),
+                                                     _dev(asm_V), _dev(asm_pos), _np_ptr(kvo), _np_ptr(kvl), _dev(out),
+                                                     _stream(stream)), "pc_prefill_attn_rotated_batched")
+
+    def pc_prefill_attn_shared_rotated_batched(self, layer: int, Q_rot, q_pos, q_offsets: Sequence[int],
+                                               module_ids: Sequence[Sequence[int]], K_tail, V_tail, out, stream=None) -> None:
+        qo = _ints(q_offsets)
+        flat = _ints([m for ids in module_ids for m in ids])
+        offs = _ints(np.concatenate([[0], np.cumsum([len(ids) for ids in module_ids])]))
+        B = len(module_ids)
+        assert len(qo) == B + 1
+        _check(lib().pc_prefill_attn_shared_rotated_batched(self._ctx, layer, _dev(Q_rot), _dev(q_pos), _np_ptr(qo), B,
+                                                            _np_ptr(flat), _np_ptr(offs), _dev(K_tail), _dev(V_tail),
+                                                            _dev(out), _stream(stream)), "pc_prefill_attn_shared_rotated_batched")
 
     def pc_calib_copy(self, n_bytes: int, repeats: int = 10) -> float:
         v = ctypes.c_double(0.0)

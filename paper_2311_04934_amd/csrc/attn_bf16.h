@@ -35,6 +35,7 @@ struct AttnParams {
     const float2 *rope;      // [max_pos][D/2]
     const float2 *rope_t;    // [D/2][max_pos]
     const float *alibi;      // [Hq] slopes of the linear bias, or nullptr: rotation
+    int q_rotated;           // Q comes rotated and scaled (log2(e)/sqrt(D)) already: its bf16 values are the operand
     int max_pos;
     int Hq, Hkv, G;
     int n_splits;

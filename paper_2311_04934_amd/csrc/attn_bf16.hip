@@ -153,9 +153,10 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p,
                 uint32_t wl = lo[e >> 1], wh = hi[e >> 1];
                 float xl = bf16_bits_to_f32((e & 1) ? (wl >> 16) : (wl & 0xffffu));
                 float xh = bf16_bits_to_f32((e & 1) ? (wh >> 16) : (wh & 0xffffu));
-                float2 cs = p.alibi ? make_float2(1.f, 0.f) : trow[d0 + e];   // linear bias: Q is used as it is
-                olo[e] = (__bf16)((xl * cs.x - xh * cs.y) * p.q_scale);
-                ohi[e] = (__bf16)((xh * cs.x + xl * cs.y) * p.q_scale);
+                float2 cs = (p.alibi || p.q_rotated) ? make_float2(1.f, 0.f) : trow[d0 + e];   // linear bias or rotated by the caller: Q as it is
+                const float qs = p.q_rotated ? 1.f : p.q_scale;
+                olo[e] = (__bf16)((xl * cs.x - xh * cs.y) * qs);
+                ohi[e] = (__bf16)((xh * cs.x + xl * cs.y) * qs);
             }
             qf[kb] = olo;
             qf[kb + KB / 2] = ohi;
@@ -501,7 +502,7 @@ int launch_variant(pc_ctx *ctx, AttnParams &p, int n_blocks, hipStream_t stream,
 }  // namespace
 
 int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const int32_t *q_pos, const void *k,
-                     const void *v, const int32_t *kv_pos, void *out, hipStream_t stream, const KvSegTable *tab)
+                     const void *v, const int32_t *kv_pos, void *out, hipStream_t stream, const KvSegTable *tab, bool q_rotated)
 {
     const int D = ctx->cfg.head_dim, Hq = ctx->cfg.n_q_heads, Hkv = ctx->cfg.n_kv_heads, G = Hq / Hkv;
     if (D != 64 && D != 128) return PC_E_UNSUPPORTED;
@@ -555,6 +556,7 @@ int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const i
     p.rope = ctx->rope_table;
     p.rope_t = ctx->rope_table_t;
     p.alibi = ctx->use_alibi ? ctx->alibi : nullptr;
+    p.q_rotated = q_rotated ? 1 : 0;
     p.max_pos = ctx->cfg.max_pos;
     p.Hq = Hq;
     p.Hkv = Hkv;

@@ -307,8 +307,9 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
         // table values (position-minor table: the 32 lanes of a half-wave hold 32 queries, usually at
         // consecutive positions, so one pair index is a contiguous 256-byte read for them)
         float2 cs[NQT][KB / 2][8];
+        const bool q_rot = p.q_rotated != 0;   // uniform: Q was rotated and scaled by the caller (append/assemble call)
 #pragma unroll
-        for (int x = 0; x < NQT && !ALIBI; ++x) {
+        for (int x = 0; x < NQT && !ALIBI && !q_rot; ++x) {
             int tpos = qt[x].qpos;
             tpos = tpos < 0 ? 0 : (tpos >= p.max_pos ? p.max_pos - 1 : tpos);
             const float2 *tcol = p.rope_t + tpos;
@@ -326,6 +327,11 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
             for (int kb = 0; kb < KB / 2; ++kb) {
                 const u32x4 lo = *reinterpret_cast<const __attribute__((address_space(3))) u32x4 *>(qrow + (((2 * kb + hh) ^ (col & 15)) << 4));
                 const u32x4 hi = *reinterpret_cast<const __attribute__((address_space(3))) u32x4 *>(qrow + (((2 * kb + hh + 8) ^ (col & 15)) << 4));
+                if (q_rot) {   // the staged values are the operand
+                    qf[x][kb] = __builtin_bit_cast(bf16x8, lo);
+                    qf[x][kb + KB / 2] = __builtin_bit_cast(bf16x8, hi);
+                    continue;
+                }
                 bf16x8 olo, ohi;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {

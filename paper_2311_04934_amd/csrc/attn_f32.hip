@@ -39,6 +39,7 @@ struct F32Params {
     float *out;
     const float2 *rope;
     const float *alibi;  // per-head slopes, or nullptr: rotation
+    int q_rotated;       // Q comes rotated and scaled already
     int max_pos, Hq, Hkv, d;
     int q_lo, q_hi;  // query rows covered by this launch
     float scale;
@@ -75,9 +76,10 @@ __global__ __launch_bounds__(kWaves * 64) void attn_f32_kernel(const F32Params p
     // rotate the query at its position ID, fold in 1/sqrt(d)
     const int qpos = active ? p.q_pos[q_row] : 0;
     const float slope = (active && p.alibi) ? p.alibi[h] : 0.f;
-    if (active && p.alibi) {   // linear bias (Sec. 4.2): the query is used as it is
+    if (active && (p.alibi || p.q_rotated)) {   // linear bias (Sec. 4.2), or Q rotated by the caller: used as it is
         const float *qr = p.q + ((size_t)q_row * p.Hq + h) * d;
-        for (int i = lane; i < d; i += 64) s_q[wave][i] = qr[i] * p.scale;
+        const float sc = p.q_rotated ? 1.f : p.scale;
+        for (int i = lane; i < d; i += 64) s_q[wave][i] = qr[i] * sc;
     } else if (active) {
         int tp = qpos < 0 ? 0 : (qpos >= p.max_pos ? p.max_pos - 1 : qpos);
         const float2 *trow = p.rope + (size_t)tp * half;
@@ -165,7 +167,8 @@ __global__ __launch_bounds__(kWaves * 64) void attn_f32_kernel(const F32Params p
 }  // namespace
 
 int launch_attn_f32(pc_ctx *ctx, const AttnBatch &batch, const float *q, const int32_t *q_pos, const float *k,
-                    const float *v, const int32_t *kv_pos, float *out, hipStream_t stream, const KvSegTable *tab)
+                    const float *v, const int32_t *kv_pos, float *out, hipStream_t stream, const KvSegTable *tab,
+                    bool q_rotated)
 {
     const int d = ctx->cfg.head_dim;
     if (d > kMaxD || (d & 1)) return PC_E_UNSUPPORTED;
@@ -180,6 +183,7 @@ int launch_attn_f32(pc_ctx *ctx, const AttnBatch &batch, const float *q, const i
     p.q = q; p.q_pos = q_pos; p.k = k; p.v = v; p.kv_pos = kv_pos; p.out = out;
     p.rope = ctx->rope_table;
     p.alibi = ctx->use_alibi ? ctx->alibi : nullptr;
+    p.q_rotated = q_rotated ? 1 : 0;
     p.max_pos = ctx->cfg.max_pos;
     p.Hq = ctx->cfg.n_q_heads; p.Hkv = ctx->cfg.n_kv_heads; p.d = d;
     p.q_lo = q_lo; p.q_hi = q_hi;

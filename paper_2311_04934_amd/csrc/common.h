@@ -139,11 +139,14 @@ struct FusedKvArgs {
     int app_rows;
     AppendSeg app[kMaxFusedAppendSegs];
 };
+// q_new != nullptr: the launch also writes q_rot[row] = rotation of q_new[row] at the row's position, times q_scale
 int launch_gather_append(pc_ctx *ctx, const FusedKvArgs &args, uint8_t *out_k, uint8_t *out_v, int32_t *out_pos,
-                         const void *k_new, const void *v_new, const int32_t *q_pos, hipStream_t stream);
+                         const void *k_new, const void *v_new, const int32_t *q_pos, hipStream_t stream,
+                         const void *q_new = nullptr, void *q_rot = nullptr, float q_scale = 1.f);
 
 int launch_append(pc_ctx *ctx, const AppendArgs &args, const void *k_new, const void *v_new, const int32_t *q_pos,
-                  void *asm_k, void *asm_v, int32_t *asm_pos, hipStream_t stream);
+                  void *asm_k, void *asm_v, int32_t *asm_pos, hipStream_t stream, const void *q_new = nullptr,
+                  void *q_rot = nullptr, float q_scale = 1.f);
 
 // ---- attention -----------------------------------------------------------------
 // One prompt of a (possibly batched) attention call.
@@ -161,10 +164,12 @@ struct AttnBatch {
 
 struct KvSegTable;
 int launch_attn_f32(pc_ctx *ctx, const AttnBatch &batch, const float *q, const int32_t *q_pos, const float *k,
-                    const float *v, const int32_t *kv_pos, float *out, hipStream_t stream, const KvSegTable *tab = nullptr);
+                    const float *v, const int32_t *kv_pos, float *out, hipStream_t stream, const KvSegTable *tab = nullptr,
+                    bool q_rotated = false);
 
 int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const int32_t *q_pos, const void *k,
-                     const void *v, const int32_t *kv_pos, void *out, hipStream_t stream, const KvSegTable *tab = nullptr);
+                     const void *v, const int32_t *kv_pos, void *out, hipStream_t stream, const KvSegTable *tab = nullptr,
+                     bool q_rotated = false);
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? PC_OK : PC_E_HIP; }
 

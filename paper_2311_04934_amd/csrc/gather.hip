@@ -32,14 +32,14 @@ __global__ __launch_bounds__(kv::kThreads) void gather_append_kernel(const Fused
                                                                       int32_t *__restrict__ out_pos, const T *k_new,
                                                                       const T *v_new, const int32_t *q_pos,
                                                                       int n_kv_heads, int d, const float2 *table,
-                                                                      int max_pos)
+                                                                      int max_pos, const kv::QRotate<T> qr)
 {
     const int b = blockIdx.x;
     if (b < a.g.total_tiles)
         kv::gather_tile(a.g, b, out_k, out_v, out_pos);
     else
         kv::append_row<T>(a.app, a.n_app, b - a.g.total_tiles, k_new, v_new, q_pos, reinterpret_cast<T *>(out_k),
-                             reinterpret_cast<T *>(out_v), out_pos, n_kv_heads, d, table, max_pos);
+                             reinterpret_cast<T *>(out_v), out_pos, n_kv_heads, d, table, max_pos, qr);
 }
 
 }  // namespace
@@ -53,18 +53,31 @@ int launch_gather(pc_ctx *ctx, const GatherArgs &args, uint8_t *out_k, uint8_t *
 }
 
 int launch_gather_append(pc_ctx *ctx, const FusedKvArgs &args, uint8_t *out_k, uint8_t *out_v, int32_t *out_pos,
-                         const void *k_new, const void *v_new, const int32_t *q_pos, hipStream_t stream)
+                         const void *k_new, const void *v_new, const int32_t *q_pos, hipStream_t stream, const void *q_new,
+                         void *q_rot, float q_scale)
 {
     const int blocks = args.g.total_tiles + args.app_rows;
     if (blocks <= 0) return PC_OK;
     const int n_kv_heads = ctx->cfg.n_kv_heads, head_dim = ctx->cfg.head_dim, max_pos = ctx->cfg.max_pos;
-    if (ctx->cfg.dtype == PC_F32)
+    const float2 *table = ctx->use_alibi ? nullptr : ctx->rope_table;
+    if (ctx->cfg.dtype == PC_F32) {
+        kv::QRotate<float> qr;
+        qr.q_new = static_cast<const float *>(q_new);
+        qr.q_rot = static_cast<float *>(q_rot);
+        qr.n_q_heads = ctx->cfg.n_q_heads;
+        qr.scale = q_scale;
         return launch_kernel(ctx, kProfGather, gather_append_kernel<float>, dim3(blocks), dim3(kv::kThreads), 0, stream,
                              args, out_k, out_v, out_pos, static_cast<const float *>(k_new),
-                             static_cast<const float *>(v_new), q_pos, n_kv_heads, head_dim, ctx->use_alibi ? nullptr : ctx->rope_table, max_pos);
+                             static_cast<const float *>(v_new), q_pos, n_kv_heads, head_dim, table, max_pos, qr);
+    }
+    kv::QRotate<uint16_t> qr;
+    qr.q_new = static_cast<const uint16_t *>(q_new);
+    qr.q_rot = static_cast<uint16_t *>(q_rot);
+    qr.n_q_heads = ctx->cfg.n_q_heads;
+    qr.scale = q_scale;
     return launch_kernel(ctx, kProfGather, gather_append_kernel<uint16_t>, dim3(blocks), dim3(kv::kThreads), 0, stream,
                          args, out_k, out_v, out_pos, static_cast<const uint16_t *>(k_new),
-                         static_cast<const uint16_t *>(v_new), q_pos, n_kv_heads, head_dim, ctx->use_alibi ? nullptr : ctx->rope_table, max_pos);
+                         static_cast<const uint16_t *>(v_new), q_pos, n_kv_heads, head_dim, table, max_pos, qr);
 }
 
 }  // namespace pc

@@ -120,13 +120,60 @@ struct Vec8<float> {
     }
 };
 
-// Row `row` of the append's flat work list, handled by one workgroup: K_new rotated at the row's
-// position ID into the tail of the assembled K, V_new copied, the position ID written.  A thread
-// rotates 8 pairs (element i with element i + d/2) per pass when d is a multiple of 16.
+// dst = rotation of src at one position (table row trow; nullptr: no rotation), times scale: n_heads heads of d
+// elements, half-split pairs (element i with element i + d/2).  Run by a whole workgroup; a thread handles
+// 8 pairs per pass when d is a multiple of 16.
 template <typename T>
-__device__ __forceinline__ void append_row(const AppendSeg *seg, int n_segs, int row, const T *k_new, const T *v_new,
-                                           const int32_t *q_pos, T *asm_k, T *asm_v, int32_t *asm_pos, int n_kv_heads,
-                                           int d, const float2 *table, int max_pos)
+__device__ __forceinline__ void rotate_row(const T *__restrict__ src, T *__restrict__ dst, int n_heads, int d,
+                                           const float2 *__restrict__ trow, float scale)
+{
+    const int half = d >> 1;
+    if (d & 15) {   // odd head sizes (fp32 only): element by element
+        for (int e = threadIdx.x; e < n_heads * half; e += kThreads) {
+            const int h = e / half, i = e % half;
+            const float2 cs = trow ? trow[i] : make_float2(1.f, 0.f);
+            const float lo = Elem<T>::load(src + h * d + i), hi = Elem<T>::load(src + h * d + i + half);
+            Elem<T>::store(dst + h * d + i, (lo * cs.x - hi * cs.y) * scale);
+            Elem<T>::store(dst + h * d + i + half, (hi * cs.x + lo * cs.y) * scale);
+        }
+        return;
+    }
+    const int blocks_per_head = half >> 3;
+    for (int blk = threadIdx.x; blk < n_heads * blocks_per_head; blk += kThreads) {
+        const int h = blk / blocks_per_head, i0 = (blk % blocks_per_head) << 3;
+        float lo[8], hi[8], olo[8], ohi[8];
+        Vec8<T>::load(src + h * d + i0, lo);
+        Vec8<T>::load(src + h * d + i0 + half, hi);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float2 cs = trow ? trow[i0 + e] : make_float2(1.f, 0.f);
+            olo[e] = (lo[e] * cs.x - hi[e] * cs.y) * scale;
+            ohi[e] = (hi[e] * cs.x + lo[e] * cs.y) * scale;
+        }
+        Vec8<T>::store(dst + h * d + i0, olo);
+        Vec8<T>::store(dst + h * d + i0 + half, ohi);
+    }
+}
+
+// Optional second job of an append row: the same token's query row, rotated at the same position and
+// scaled, for attention calls that take Q already rotated.
+template <typename T>
+struct QRotate {
+    const T *__restrict__ q_new = nullptr;   // [rows][n_q_heads][d], nullptr: nothing to do
+    T *__restrict__ q_rot = nullptr;
+    int n_q_heads = 0;
+    float scale = 1.f;
+};
+
+// Row `row` of the append's flat work list, handled by one workgroup: K_new rotated at the row's
+// position ID into the tail of the assembled K (copied as it is when table == nullptr: models with a
+// linear attention bias, Sec. 4.2), V_new copied, the position ID written.
+template <typename T>
+__device__ __forceinline__ void append_row(const AppendSeg *seg, int n_segs, int row, const T *__restrict__ k_new,
+                                           const T *__restrict__ v_new, const int32_t *__restrict__ q_pos,
+                                           T *__restrict__ asm_k, T *__restrict__ asm_v, int32_t *__restrict__ asm_pos,
+                                           int n_kv_heads, int d, const float2 *__restrict__ table, int max_pos,
+                                           const QRotate<T> qr = QRotate<T>())
 {
     int r = row, s = 0;
     while (s < n_segs && r >= seg[s].n) {
@@ -144,55 +191,29 @@ __device__ __forceinline__ void append_row(const AppendSeg *seg, int n_segs, int
     const int half = d >> 1;
     const int row_elems = n_kv_heads * d;
     const int p = mode >= 0 ? mode + r : q_pos[src];
+    const float2 *trow = table ? table + (size_t)clamp_pos(p, max_pos) * half : nullptr;
     const T *ks = k_new + (size_t)src * row_elems;
     const T *vs = v_new + (size_t)src * row_elems;
     T *kd = asm_k + (size_t)dst * row_elems;
     T *vd = asm_v + (size_t)dst * row_elems;
-    if (table == nullptr) {   // linear-bias models (Sec. 4.2, ALiBi): keys carry no position, both rows are copies
-        if ((row_elems * sizeof(T)) & 15) {
-            for (int e = threadIdx.x; e < row_elems; e += kThreads) { kd[e] = ks[e]; vd[e] = vs[e]; }
-        } else {
-            const int n_vec = (int)((size_t)row_elems * sizeof(T) >> 4);
-            for (int i = threadIdx.x; i < n_vec; i += kThreads) {
-                reinterpret_cast<u32x4 *>(kd)[i] = reinterpret_cast<const u32x4 *>(ks)[i];
-                reinterpret_cast<u32x4 *>(vd)[i] = reinterpret_cast<const u32x4 *>(vs)[i];
-            }
+    // V (and K when it is not rotated) first: these copies do not depend on the position ID
+    if ((row_elems * sizeof(T)) & 15) {
+        for (int e = threadIdx.x; e < row_elems; e += kThreads) {
+            vd[e] = vs[e];
+            if (!trow) kd[e] = ks[e];
         }
-        if (threadIdx.x == 0) asm_pos[dst] = p;
-        return;
-    }
-    const float2 *trow = table + (size_t)clamp_pos(p, max_pos) * half;
-    if (d & 15) {   // odd head sizes (fp32 only): element by element
-        for (int e = threadIdx.x; e < n_kv_heads * half; e += kThreads) {
-            const int h = e / half, i = e % half;
-            const float2 cs = trow[i];
-            const float lo = Elem<T>::load(ks + h * d + i), hi = Elem<T>::load(ks + h * d + i + half);
-            Elem<T>::store(kd + h * d + i, lo * cs.x - hi * cs.y);
-            Elem<T>::store(kd + h * d + i + half, hi * cs.x + lo * cs.y);
-        }
-        for (int e = threadIdx.x; e < row_elems; e += kThreads) vd[e] = vs[e];
     } else {
-        // V first: its copy does not depend on the position ID
         const int n_vec = (int)((size_t)row_elems * sizeof(T) >> 4);
-        const u32x4 *vs4 = reinterpret_cast<const u32x4 *>(vs);
-        u32x4 *vd4 = reinterpret_cast<u32x4 *>(vd);
-        for (int i = threadIdx.x; i < n_vec; i += kThreads) vd4[i] = vs4[i];
-        const int blocks_per_head = half >> 3;
-        for (int blk = threadIdx.x; blk < n_kv_heads * blocks_per_head; blk += kThreads) {
-            const int h = blk / blocks_per_head, i0 = (blk % blocks_per_head) << 3;
-            float lo[8], hi[8], olo[8], ohi[8];
-            Vec8<T>::load(ks + h * d + i0, lo);
-            Vec8<T>::load(ks + h * d + i0 + half, hi);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float2 cs = trow[i0 + e];
-                olo[e] = lo[e] * cs.x - hi[e] * cs.y;
-                ohi[e] = hi[e] * cs.x + lo[e] * cs.y;
-            }
-            Vec8<T>::store(kd + h * d + i0, olo);
-            Vec8<T>::store(kd + h * d + i0 + half, ohi);
+        for (int i = threadIdx.x; i < n_vec; i += kThreads) {
+            reinterpret_cast<u32x4 *>(vd)[i] = reinterpret_cast<const u32x4 *>(vs)[i];
+            if (!trow) reinterpret_cast<u32x4 *>(kd)[i] = reinterpret_cast<const u32x4 *>(ks)[i];
         }
     }
+    if (qr.q_new) {
+        const size_t q_elems = (size_t)qr.n_q_heads * d;
+        rotate_row<T>(qr.q_new + (size_t)src * q_elems, qr.q_rot + (size_t)src * q_elems, qr.n_q_heads, d, trow, qr.scale);
+    }
+    if (trow) rotate_row<T>(ks, kd, n_kv_heads, d, trow, 1.f);
     if (threadIdx.x == 0) asm_pos[dst] = p;
 }
 

@@ -39,10 +39,10 @@ template <typename T>
 __global__ __launch_bounds__(kv::kThreads) void append_kernel(const AppendArgs a, const T *k_new, const T *v_new,
                                                               const int32_t *q_pos, T *asm_k, T *asm_v,
                                                               int32_t *asm_pos, int n_kv_heads, int d,
-                                                              const float2 *table, int max_pos)
+                                                              const float2 *table, int max_pos, const kv::QRotate<T> qr)
 {
     kv::append_row<T>(a.seg, a.n_segs, blockIdx.x, k_new, v_new, q_pos, asm_k, asm_v, asm_pos, n_kv_heads, d, table,
-                      max_pos);
+                      max_pos, qr);
 }
 
 }  // namespace
@@ -62,20 +62,32 @@ int launch_rope(pc_ctx *ctx, void *x, int n_tokens, int n_heads, const int32_t *
 }
 
 int launch_append(pc_ctx *ctx, const AppendArgs &args, const void *k_new, const void *v_new, const int32_t *q_pos,
-                  void *asm_k, void *asm_v, int32_t *asm_pos, hipStream_t stream)
+                  void *asm_k, void *asm_v, int32_t *asm_pos, hipStream_t stream, const void *q_new, void *q_rot,
+                  float q_scale)
 {
     if (args.total_rows <= 0) return PC_OK;
     const int n_kv_heads = ctx->cfg.n_kv_heads, head_dim = ctx->cfg.head_dim, max_pos = ctx->cfg.max_pos;
     const float2 *table = ctx->use_alibi ? nullptr : ctx->rope_table;   // linear-bias models store keys unrotated
-    if (ctx->cfg.dtype == PC_F32)
+    if (ctx->cfg.dtype == PC_F32) {
+        kv::QRotate<float> qr;
+        qr.q_new = static_cast<const float *>(q_new);
+        qr.q_rot = static_cast<float *>(q_rot);
+        qr.n_q_heads = ctx->cfg.n_q_heads;
+        qr.scale = q_scale;
         return launch_kernel(ctx, kProfAppend, append_kernel<float>, dim3(args.total_rows), dim3(kv::kThreads), 0, stream, args,
                              static_cast<const float *>(k_new), static_cast<const float *>(v_new), q_pos,
                              static_cast<float *>(asm_k), static_cast<float *>(asm_v), asm_pos, n_kv_heads, head_dim,
-                             table, max_pos);
+                             table, max_pos, qr);
+    }
+    kv::QRotate<uint16_t> qr;
+    qr.q_new = static_cast<const uint16_t *>(q_new);
+    qr.q_rot = static_cast<uint16_t *>(q_rot);
+    qr.n_q_heads = ctx->cfg.n_q_heads;
+    qr.scale = q_scale;
     return launch_kernel(ctx, kProfAppend, append_kernel<uint16_t>, dim3(args.total_rows), dim3(kv::kThreads), 0, stream, args,
                          static_cast<const uint16_t *>(k_new), static_cast<const uint16_t *>(v_new), q_pos,
                          static_cast<uint16_t *>(asm_k), static_cast<uint16_t *>(asm_v), asm_pos, n_kv_heads, head_dim,
-                         table, max_pos);
+                         table, max_pos, qr);
 }
 
 }  // namespace pc

@@ -208,13 +208,20 @@ int run_gather(pc_ctx *ctx, std::vector<GatherSeg> &segs, void *out_K, void *out
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// Factor folded into a pre-rotated Q: 1/sqrt(d), in the log2 domain for the bf16 kernels (their softmax is base 2).
+float q_prescale(const pc_ctx *ctx)
+{
+    const float inv = 1.0f / sqrtf((float)ctx->cfg.head_dim);
+    return ctx->cfg.dtype == PC_F32 ? inv : 1.4426950408889634f * inv;
+}
+
 int run_attn(pc_ctx *ctx, const AttnBatch &b, const void *Q, const int32_t *q_pos, const void *K, const void *V,
-             const int32_t *pos, void *out, hipStream_t stream)
+             const int32_t *pos, void *out, hipStream_t stream, bool q_rotated = false)
 {
     if (ctx->cfg.dtype == PC_F32)
         return launch_attn_f32(ctx, b, static_cast<const float *>(Q), q_pos, static_cast<const float *>(K),
-                               static_cast<const float *>(V), pos, static_cast<float *>(out), stream);
-    return launch_attn_bf16(ctx, b, Q, q_pos, K, V, pos, out, stream);
+                               static_cast<const float *>(V), pos, static_cast<float *>(out), stream, nullptr, q_rotated);
+    return launch_attn_bf16(ctx, b, Q, q_pos, K, V, pos, out, stream, nullptr, q_rotated);
 }
 
 }  // namespace
@@ -586,9 +593,9 @@ int pc_rope(pc_ctx *ctx, void *x, int n_tokens, int n_heads, const int32_t *pos,
     return launch_rope(ctx, x, n_tokens, n_heads, pos, as_stream(stream));
 }
 
-int pc_append_kv_batched(pc_ctx *ctx, int layer, const void *K_new_raw, const void *V_new, const int32_t *q_pos,
-                         const int *q_offsets, int n_prompts, void *asm_K, void *asm_V, int32_t *asm_pos,
-                         const int *kv_offsets, const int *kv_lens, void *stream)
+static int append_impl(pc_ctx *ctx, int layer, const void *K_new_raw, const void *V_new, const int32_t *q_pos,
+                       const int *q_offsets, int n_prompts, void *asm_K, void *asm_V, int32_t *asm_pos,
+                       const int *kv_offsets, const int *kv_lens, void *stream, const void *Q_new, void *Q_rot)
 {
     if (!ctx || n_prompts < 0 || !q_offsets || !kv_offsets || !kv_lens) return PC_E_BADARG;
     if (layer < 0 || layer >= ctx->cfg.n_layers) return PC_E_LAYER;
@@ -611,16 +618,36 @@ int pc_append_kv_batched(pc_ctx *ctx, int layer, const void *K_new_raw, const vo
             a.seg[i].pos0 = kPosFromArray;
             a.total_rows += a.seg[i].n;
         }
-        int rc = launch_append(ctx, a, K_new_raw, V_new, q_pos, asm_K, asm_V, asm_pos, as_stream(stream));
+        int rc = launch_append(ctx, a, K_new_raw, V_new, q_pos, asm_K, asm_V, asm_pos, as_stream(stream), Q_new, Q_rot,
+                               q_prescale(ctx));
         if (rc != PC_OK) return rc;
     }
     return PC_OK;
 }
 
-int pc_assemble_append_kv_batched(pc_ctx *ctx, int layer, const int *module_ids_flat, const int *mod_offsets,
-                                  int n_prompts, const void *K_new_raw, const void *V_new, const int32_t *q_pos,
-                                  const int *q_offsets, void *out_K, void *out_V, int32_t *out_pos,
-                                  const int *kv_offsets, int *out_n_tokens, void *stream)
+int pc_append_kv_batched(pc_ctx *ctx, int layer, const void *K_new_raw, const void *V_new, const int32_t *q_pos,
+                         const int *q_offsets, int n_prompts, void *asm_K, void *asm_V, int32_t *asm_pos,
+                         const int *kv_offsets, const int *kv_lens, void *stream)
+{
+    return append_impl(ctx, layer, K_new_raw, V_new, q_pos, q_offsets, n_prompts, asm_K, asm_V, asm_pos, kv_offsets, kv_lens,
+                       stream, nullptr, nullptr);
+}
+
+int pc_append_rotate_batched(pc_ctx *ctx, int layer, const void *K_new_raw, const void *V_new, const void *Q_new,
+                             const int32_t *q_pos, const int *q_offsets, int n_prompts, void *asm_K, void *asm_V,
+                             int32_t *asm_pos, const int *kv_offsets, const int *kv_lens, void *Q_rot, void *stream)
+{
+    if (!ctx || n_prompts < 0 || !q_offsets) return PC_E_BADARG;
+    if (n_prompts > 0 && q_offsets[n_prompts] > q_offsets[0] && (!Q_new || !Q_rot || !aligned16(Q_new) || !aligned16(Q_rot)))
+        return PC_E_BADARG;
+    return append_impl(ctx, layer, K_new_raw, V_new, q_pos, q_offsets, n_prompts, asm_K, asm_V, asm_pos, kv_offsets, kv_lens,
+                       stream, Q_new, Q_rot);
+}
+
+static int assemble_append_impl(pc_ctx *ctx, int layer, const int *module_ids_flat, const int *mod_offsets,
+                                int n_prompts, const void *K_new_raw, const void *V_new, const int32_t *q_pos,
+                                const int *q_offsets, void *out_K, void *out_V, int32_t *out_pos,
+                                const int *kv_offsets, int *out_n_tokens, void *stream, const void *Q_new, void *Q_rot)
 {
     if (!ctx || n_prompts < 0 || !mod_offsets || !kv_offsets || !q_offsets) return PC_E_BADARG;
     if (layer < 0 || layer >= ctx->cfg.n_layers) return PC_E_LAYER;
@@ -666,17 +693,38 @@ int pc_assemble_append_kv_batched(pc_ctx *ctx, int layer, const int *module_ids_
             a.app[b].pos0 = kPosFromArray;
         }
         rc = launch_gather_append(ctx, a, static_cast<uint8_t *>(out_K), static_cast<uint8_t *>(out_V), out_pos,
-                                  K_new_raw, V_new, q_pos, as_stream(stream));
+                                  K_new_raw, V_new, q_pos, as_stream(stream), Q_new, Q_rot, q_prescale(ctx));
     } else {
         // too many segments for one argument block: the two steps one after the other
         rc = run_gather(ctx, segs, out_K, out_V, out_pos, as_stream(stream));
         if (rc == PC_OK)
-            rc = pc_append_kv_batched(ctx, layer, K_new_raw, V_new, q_pos, q_offsets, n_prompts, out_K, out_V, out_pos,
-                                      kv_offsets, rows.data(), stream);
+            rc = append_impl(ctx, layer, K_new_raw, V_new, q_pos, q_offsets, n_prompts, out_K, out_V, out_pos, kv_offsets,
+                             rows.data(), stream, Q_new, Q_rot);
     }
     if (rc == PC_OK && out_n_tokens)
         for (int b = 0; b < n_prompts; ++b) out_n_tokens[b] = rows[b] + (q_offsets[b + 1] - q_offsets[b]);
     return rc;
+}
+
+int pc_assemble_append_kv_batched(pc_ctx *ctx, int layer, const int *module_ids_flat, const int *mod_offsets,
+                                  int n_prompts, const void *K_new_raw, const void *V_new, const int32_t *q_pos,
+                                  const int *q_offsets, void *out_K, void *out_V, int32_t *out_pos,
+                                  const int *kv_offsets, int *out_n_tokens, void *stream)
+{
+    return assemble_append_impl(ctx, layer, module_ids_flat, mod_offsets, n_prompts, K_new_raw, V_new, q_pos, q_offsets, out_K,
+                                out_V, out_pos, kv_offsets, out_n_tokens, stream, nullptr, nullptr);
+}
+
+int pc_assemble_append_rotate_batched(pc_ctx *ctx, int layer, const int *module_ids_flat, const int *mod_offsets,
+                                      int n_prompts, const void *K_new_raw, const void *V_new, const void *Q_new,
+                                      const int32_t *q_pos, const int *q_offsets, void *out_K, void *out_V,
+                                      int32_t *out_pos, const int *kv_offsets, int *out_n_tokens, void *Q_rot, void *stream)
+{
+    if (!ctx || n_prompts < 0 || !q_offsets) return PC_E_BADARG;
+    if (n_prompts > 0 && q_offsets[n_prompts] > q_offsets[0] && (!Q_new || !Q_rot || !aligned16(Q_new) || !aligned16(Q_rot)))
+        return PC_E_BADARG;
+    return assemble_append_impl(ctx, layer, module_ids_flat, mod_offsets, n_prompts, K_new_raw, V_new, q_pos, q_offsets, out_K,
+                                out_V, out_pos, kv_offsets, out_n_tokens, stream, Q_new, Q_rot);
 }
 
 int pc_set_module_params(pc_ctx *ctx, int module_id, int n_params, const int *offsets, const int *lens)
@@ -757,9 +805,9 @@ int pc_append_kv(pc_ctx *ctx, int layer, const void *K_new_raw, const void *V_ne
                                 kv_lens, stream);
 }
 
-int pc_prefill_attn_batched(pc_ctx *ctx, int layer, const void *Q_new, const int32_t *q_pos, const int *q_offsets,
-                            int n_prompts, const void *asm_K, const void *asm_V, const int32_t *asm_pos,
-                            const int *kv_offsets, const int *kv_lens, void *out, void *stream)
+static int prefill_attn_batched_impl(pc_ctx *ctx, int layer, const void *Q_new, const int32_t *q_pos, const int *q_offsets,
+                                     int n_prompts, const void *asm_K, const void *asm_V, const int32_t *asm_pos,
+                                     const int *kv_offsets, const int *kv_lens, void *out, void *stream, bool q_rotated)
 {
     if (!ctx || n_prompts < 0 || !q_offsets || !kv_offsets || !kv_lens) return PC_E_BADARG;
     if (layer < 0 || layer >= ctx->cfg.n_layers) return PC_E_LAYER;
@@ -785,15 +833,52 @@ int pc_prefill_attn_batched(pc_ctx *ctx, int layer, const void *Q_new, const int
             ab.seq[i].kv_begin = kv_offsets[b];
             ab.seq[i].n_kv = kv_lens[b];
         }
-        int rc = run_attn(ctx, ab, Q_new, q_pos, asm_K, asm_V, asm_pos, out, as_stream(stream));
+        int rc = run_attn(ctx, ab, Q_new, q_pos, asm_K, asm_V, asm_pos, out, as_stream(stream), q_rotated);
         if (rc != PC_OK) return rc;
     }
     return PC_OK;
 }
 
+int pc_prefill_attn_batched(pc_ctx *ctx, int layer, const void *Q_new, const int32_t *q_pos, const int *q_offsets,
+                            int n_prompts, const void *asm_K, const void *asm_V, const int32_t *asm_pos,
+                            const int *kv_offsets, const int *kv_lens, void *out, void *stream)
+{
+    return prefill_attn_batched_impl(ctx, layer, Q_new, q_pos, q_offsets, n_prompts, asm_K, asm_V, asm_pos, kv_offsets, kv_lens,
+                                     out, stream, false);
+}
+
+int pc_prefill_attn_rotated_batched(pc_ctx *ctx, int layer, const void *Q_rot, const int32_t *q_pos, const int *q_offsets,
+                                    int n_prompts, const void *asm_K, const void *asm_V, const int32_t *asm_pos,
+                                    const int *kv_offsets, const int *kv_lens, void *out, void *stream)
+{
+    return prefill_attn_batched_impl(ctx, layer, Q_rot, q_pos, q_offsets, n_prompts, asm_K, asm_V, asm_pos, kv_offsets, kv_lens,
+                                     out, stream, true);
+}
+
+static int prefill_attn_shared_impl(pc_ctx *ctx, int layer, const void *Q_new, const int32_t *q_pos, const int *q_offsets,
+                                    int n_prompts, const int *module_ids_flat, const int *mod_offsets, const void *K_tail,
+                                    const void *V_tail, void *out, void *stream, bool q_rotated);
+
 int pc_prefill_attn_shared_batched(pc_ctx *ctx, int layer, const void *Q_new, const int32_t *q_pos, const int *q_offsets,
                                    int n_prompts, const int *module_ids_flat, const int *mod_offsets, const void *K_tail,
                                    const void *V_tail, void *out, void *stream)
+{
+    return prefill_attn_shared_impl(ctx, layer, Q_new, q_pos, q_offsets, n_prompts, module_ids_flat, mod_offsets, K_tail, V_tail,
+                                    out, stream, false);
+}
+
+int pc_prefill_attn_shared_rotated_batched(pc_ctx *ctx, int layer, const void *Q_rot, const int32_t *q_pos,
+                                           const int *q_offsets, int n_prompts, const int *module_ids_flat,
+                                           const int *mod_offsets, const void *K_tail, const void *V_tail, void *out,
+                                           void *stream)
+{
+    return prefill_attn_shared_impl(ctx, layer, Q_rot, q_pos, q_offsets, n_prompts, module_ids_flat, mod_offsets, K_tail, V_tail,
+                                    out, stream, true);
+}
+
+static int prefill_attn_shared_impl(pc_ctx *ctx, int layer, const void *Q_new, const int32_t *q_pos, const int *q_offsets,
+                                    int n_prompts, const int *module_ids_flat, const int *mod_offsets, const void *K_tail,
+                                    const void *V_tail, void *out, void *stream, bool q_rotated)
 {
     if (!ctx || n_prompts < 0 || !q_offsets || !mod_offsets) return PC_E_BADARG;
     if (layer < 0 || layer >= ctx->cfg.n_layers) return PC_E_LAYER;
@@ -861,8 +946,9 @@ int pc_prefill_attn_shared_batched(pc_ctx *ctx, int layer, const void *Q_new, co
         tab.seg_begin[ab.n_seqs] = n_seg;
         int rc = ctx->cfg.dtype == PC_F32
                      ? launch_attn_f32(ctx, ab, static_cast<const float *>(Q_new), q_pos, nullptr, nullptr, nullptr,
-                                       static_cast<float *>(out), as_stream(stream), &tab)
-                     : launch_attn_bf16(ctx, ab, Q_new, q_pos, nullptr, nullptr, nullptr, out, as_stream(stream), &tab);
+                                       static_cast<float *>(out), as_stream(stream), &tab, q_rotated)
+                     : launch_attn_bf16(ctx, ab, Q_new, q_pos, nullptr, nullptr, nullptr, out, as_stream(stream), &tab,
+                                        q_rotated);
         if (rc != PC_OK) return rc;
     }
     return PC_OK;

@@ -869,6 +869,130 @@ def test_random_workloads_modules_in_place(seed):
     _shared_run(_random_workload(seed), 0, None)
 
 
+# ------------------------------------------------------------------ Q rotated once per token, in the append launch
+def _rotated_run(w, in_place, alibi=False):
+    """The *_rotate calls write Q_rot = rope(Q_new, q_pos) x score scale next to the appended rows; attention on Q_rot
+    must give what attention on Q_new gives, and both must match the oracle."""
+    c = build_case(w, 0, encode_keys=not alibi)
+    r = GpuRunner(c)
+    dev = r.dev
+    slopes = None
+    if alibi:
+        slopes = pcb.pc_alibi_slopes(w.n_q_heads)
+        r.pc.pc_set_alibi(slopes)
+    B = len(c.prompts)
+    n_mod = [sum(w.sizes[m] for m in p.module_ids) for p in c.prompts]
+    n_new = [len(p.q_pos) for p in c.prompts]
+    lens = [a + b for a, b in zip(n_mod, n_new)]
+    kv_off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    q_off = np.concatenate([[0], np.cumsum(n_new)]).astype(np.int64)
+    Q = torch.cat([p.Q for p in c.prompts]).to(dev)
+    Kn = torch.cat([p.K_new for p in c.prompts]).to(dev)
+    Vn = torch.cat([p.V_new for p in c.prompts]).to(dev)
+    qp_host = np.concatenate([p.q_pos for p in c.prompts])
+    qp = torch.from_numpy(qp_host).to(dev)
+    ids = [p.module_ids for p in c.prompts]
+    Q_rot = torch.full_like(Q, float("nan"))
+    out_rot = torch.full_like(Q, float("nan"))
+    out_ref = torch.full_like(Q, float("nan"))
+    rows = int(q_off[-1]) if in_place else int(kv_off[-1])
+    bK = torch.full((rows, w.n_kv_heads, w.head_dim), float("nan"), dtype=w.torch_dtype, device=dev)
+    bV = torch.full_like(bK, float("nan"))
+    bP = torch.full((rows,), -7, dtype=torch.int32, device=dev)
+    try:
+        if in_place:
+            r.pc.pc_append_rotate_batched(0, Kn, Vn, Q, qp, q_off, bK, bV, bP, q_off, [0] * B, Q_rot)
+            r.pc.pc_prefill_attn_shared_rotated_batched(0, Q_rot, qp, q_off, ids, bK, bV, out_rot)
+            r.pc.pc_prefill_attn_shared_batched(0, Q, qp, q_off, ids, bK, bV, out_ref)
+        else:
+            totals = r.pc.pc_assemble_append_rotate_batched(0, ids, Kn, Vn, Q, qp, q_off, bK, bV, bP, kv_off, Q_rot)
+            assert totals == lens
+            r.pc.pc_prefill_attn_rotated_batched(0, Q_rot, qp, q_off, bK, bV, bP, kv_off, lens, out_rot)
+            r.pc.pc_prefill_attn_batched(0, Q, qp, q_off, bK, bV, bP, kv_off, lens, out_ref)
+        torch.cuda.synchronize()
+        launch = r.pc.pc_last_attn_launch()
+        hK, hV, hP, hQ, o, o_ref = bK.cpu(), bV.cpu(), bP.cpu().numpy(), Q_rot.cpu(), out_rot.cpu(), out_ref.cpu()
+    finally:
+        r.close()
+    # same formula in both places; the compiler may contract the multiply-adds differently, so a few Q values can
+    # differ by one unit in the last place, hence the outputs only agree to well inside the tolerance
+    dmax = float((o.double() - o_ref.double()).abs().max())
+    print(f"[{w.name}/rotated] max |out(Q_rot) - out(Q_new)| = {dmax:.3e}", flush=True)
+    assert dmax <= 0.1 * TOL_ABS[w.dtype] * max(1.0, float(o_ref.double().abs().max()))
+    # Q_rot against the oracle's rotation times the score scale, to one unit in the last place of the dtype
+    scale = (1.0 if w.dtype == "f32" else 1.4426950408889634) / np.sqrt(w.head_dim)
+    q64 = to_f64(torch.cat([p.Q for p in c.prompts]))
+    want = (q64 if alibi else oracle.rope(q64, qp_host, w.rope_base)) * scale
+    ulp = 2.0 ** -8 if w.dtype == "bf16" else 2.0 ** -22
+    assert np.all(np.abs(to_f64(hQ) - want) <= ulp * np.maximum(np.abs(want), 2.0 ** -6) + 1e-7)
+    for b in range(B):
+        if n_new[b] == 0:
+            continue
+        if not in_place and not alibi:
+            res = dict(asm_K=hK[kv_off[b]:kv_off[b + 1]], asm_V=hV[kv_off[b]:kv_off[b + 1]], asm_pos=hP[kv_off[b]:kv_off[b + 1]],
+                       n_mod=n_mod[b], n_kv=lens[b], out=o[q_off[b]:q_off[b + 1]], launch=launch)
+            check_assembly(c, b, res)
+            check_append(c, b, res)
+            check_attention(c, b, res, None, "/rotated")
+        else:
+            pcx = c.prompts[b]
+            Ks = [to_f64(c.mod_K[m]) for m in pcx.module_ids]
+            Vs = [to_f64(c.mod_V[m]) for m in pcx.module_ids] + [to_f64(pcx.V_new)]
+            P = np.concatenate([np.arange(c.starts[m], c.starts[m] + w.sizes[m]) for m in pcx.module_ids] + [pcx.q_pos]).astype(np.int32)
+            if alibi:
+                ref = oracle.attn_alibi(to_f64(pcx.Q), pcx.q_pos, np.concatenate(Ks + [to_f64(pcx.K_new)]), np.concatenate(Vs), P,
+                                        np.asarray(slopes, dtype=np.float64))
+            else:
+                ref = oracle.attn(to_f64(pcx.Q), pcx.q_pos, np.concatenate(Ks + [oracle.rope(to_f64(pcx.K_new), pcx.q_pos, w.rope_base)]),
+                                  np.concatenate(Vs), P, w.rope_base)
+            err, rel = attn_errors(o[q_off[b]:q_off[b + 1]], ref)
+            print(f"[{w.name}/rotated{'/in-place' if in_place else ''}{'/alibi' if alibi else ''}] prompt {b}: max abs err {err:.3e}, rel L2 {rel:.3e}", flush=True)
+            assert err <= TOL_ABS[w.dtype] * max(1.0, float(np.abs(ref).max())) and rel <= TOL_REL[w.dtype], (err, rel)
+
+
+@pytest.mark.parametrize("dtype,hq,hkv,d", [("f32", 6, 2, 64), ("f32", 4, 4, 40), ("bf16", 8, 8, 64), ("bf16", 8, 2, 128), ("bf16", 4, 4, 128)])
+@pytest.mark.parametrize("in_place", [False, True])
+def test_query_rotated_in_the_append_launch(dtype, hq, hkv, d, in_place):
+    w = W.custom(f"qrot_{dtype}_{d}", dtype, hq, hkv, d, [300, 64, 90, 70, 120, 33], [-1, 0, 0, 0, 1, 1],
+                 [W.Prompt([0, 1, 4], 40), W.Prompt([4, 2, 0], 17), W.Prompt([], 9), W.Prompt([3, 0, 5], 64),
+                  W.Prompt([0], 1), W.Prompt([5], 70)], max_pos=1024)
+    _rotated_run(w, in_place)
+
+
+@pytest.mark.parametrize("dtype,hq,hkv,d", [("f32", 6, 2, 64), ("bf16", 8, 2, 128), ("bf16", 8, 8, 64)])
+def test_query_scaled_in_the_append_launch_under_the_linear_bias(dtype, hq, hkv, d):
+    w = W.custom(f"qrot_alibi_{dtype}_{d}", dtype, hq, hkv, d, [300, 64, 90], None,
+                 [W.Prompt([0, 1, 2], 40), W.Prompt([2, 0], 17), W.Prompt([1], 70)], max_pos=1024)
+    _rotated_run(w, False, alibi=True)
+
+
+def test_query_rotation_many_prompts_and_argument_checks():
+    """More prompts than one fused launch holds (the call falls back to gather, then append + rotation), and
+    the pointer checks of the new arguments."""
+    sizes = [40, 24, 56]
+    prompts = [W.Prompt([i % 3], 1 + (i % 5)) for i in range(70)]
+    w = W.custom("qrot_many", "bf16", 4, 2, 128, sizes, None, prompts, max_pos=512)
+    _rotated_run(w, False)
+    c = build_case(W.custom("qrot_err", "bf16", 8, 2, 128, [32], None, [W.Prompt([0], 8)], max_pos=256), 0)
+    r = GpuRunner(c)
+    dev = r.dev
+    p0 = c.prompts[0]
+    aK = torch.zeros((40, 2, 128), dtype=torch.bfloat16, device=dev)
+    aP = torch.zeros((40,), dtype=torch.int32, device=dev)
+    qp = torch.from_numpy(p0.q_pos).to(dev)
+    try:
+        with pytest.raises(pcb.PcError) as e:
+            r.pc.pc_assemble_append_rotate_batched(0, [[0]], p0.K_new.to(dev), p0.V_new.to(dev), p0.Q.to(dev), qp, [0, 8],
+                                                   aK, aK.clone(), aP, [0, 40], None)
+        assert e.value.status == -1
+        with pytest.raises(pcb.PcError) as e:
+            r.pc.pc_append_rotate_batched(0, p0.K_new.to(dev), p0.V_new.to(dev), None, qp, [0, 8], aK, aK.clone(), aP,
+                                          [0, 40], [32], torch.zeros_like(p0.Q, device=dev))
+        assert e.value.status == -1
+    finally:
+        r.close()
+
+
 # ------------------------------------------------------------------ HIP graph capture
 def test_step_replays_from_a_hip_graph():
     """The request-path calls allocate nothing, clear nothing and never synchronise, so a caller may capture
@@ -1022,3 +1146,7 @@ def test_config3_long_doc_8k_host_tier_full_size_sampled(mode):
 @pytest.mark.parametrize("in_place", [False, True])
 def test_config3_long_doc_8k_alibi_full_size_sampled(in_place):
     _alibi_run(W.long_doc_8k(), 31, 12, in_place=in_place)
+
+
+def test_config3_long_doc_8k_rotated_query_full_size():
+    _rotated_run(W.long_doc_8k(), False)
