@@ -164,16 +164,32 @@ int copy_host_segments(pc_ctx *ctx, std::vector<GatherSeg> &segs, void *out_K, v
     return PC_OK;
 }
 
-// Rows per gather tile.  A workgroup moves 32 KiB of K and 32 KiB of V per pass (512 lanes x 4 x 16 bytes, all
-// loads issued before the first store).  One pass per tile gives the most workgroups, which is what short
-// launches need; launches of hundreds of megabytes run ~6 % faster with two passes per workgroup (measured).
-int gather_rows_per_tile(const pc_ctx *ctx, const std::vector<GatherSeg> &segs)
+// Rows per gather tile.  A workgroup moves up to 32 KiB of K and 32 KiB of V in one pass (512 lanes x 4 x 16
+// bytes, all loads issued before the first store).  Measured: a launch takes about as long as its busiest CU,
+// i.e. (workgroups on that CU) x (tile bytes): 528 tiles of 32 KiB (two per CU on 240 CUs, three on 16) take
+// 25 % longer than 512, while the same rows cut into 704 tiles of 24 KiB take 7 % longer.  So 24 KiB tiles are
+// used where they make ceil(workgroups / CUs) x tile bytes smaller than 32 KiB tiles do, and 16 KiB tiles only
+// for launches that would otherwise leave CUs without a workgroup (smaller tiles cost more per byte).
+// `extra_wgs` are the workgroups the same launch runs for appended rows.  Launches of hundreds of megabytes
+// run ~6 % faster with two passes per workgroup.
+int gather_rows_per_tile(const pc_ctx *ctx, const std::vector<GatherSeg> &segs, long extra_wgs = 0)
 {
     size_t rows = 0;
     for (const GatherSeg &sg : segs) rows += (size_t)sg.n_rows;
-    const size_t tile_bytes = rows * ctx->row_bytes > ((size_t)128 << 20) ? 65536 : 32768;
-    const int r = (int)(tile_bytes / ctx->row_bytes);
-    return r < 1 ? 1 : r;
+    const size_t rb = ctx->row_bytes;
+    if (rows * rb > ((size_t)128 << 20)) return std::max(1, (int)(65536 / rb));
+    const long n_cu = ctx->n_cu > 0 ? ctx->n_cu : 256;
+    auto tiles_with = [&](int rpt) {
+        long tiles = 0;
+        for (const GatherSeg &sg : segs)
+            if (sg.src_k) tiles += (sg.n_rows + rpt - 1) / rpt;
+        return tiles;
+    };
+    const int r32 = std::max(1, (int)(32768 / rb)), r24 = std::max(1, (int)(24576 / rb)), r16 = std::max(1, (int)(16384 / rb));
+    if (tiles_with(r24) + extra_wgs < n_cu) return r16;
+    const long c32 = ((tiles_with(r32) + extra_wgs + n_cu - 1) / n_cu) * r32;
+    const long c24 = ((tiles_with(r24) + extra_wgs + n_cu - 1) / n_cu) * r24;
+    return c24 < c32 ? r24 : r32;
 }
 
 int tiles_of(const GatherSeg &sg, int rows_per_tile)
@@ -673,7 +689,7 @@ static int assemble_append_impl(pc_ctx *ctx, int layer, const int *module_ids_fl
         rc = copy_host_segments(ctx, segs, out_K, out_V, as_stream(stream));
         if (rc != PC_OK) return rc;
         FusedKvArgs a;
-        const int rows_per_tile = gather_rows_per_tile(ctx, segs);
+        const int rows_per_tile = gather_rows_per_tile(ctx, segs, new_rows);
         a.g.n_segs = (int)segs.size();
         a.g.rows_per_tile = rows_per_tile;
         a.g.row_bytes = (int)ctx->row_bytes;
