@@ -446,6 +446,18 @@ int pc_calib_mfma(pc_ctx *ctx, int iters, double *tflop_per_s);
 /* Bytes of pool in use / total. */
 int pc_pool_usage(const pc_ctx *ctx, size_t *used, size_t *total);
 
+/*
+ * Which bf16 attention kernel serves head_dim 128.  PC_ATTN_AUTO (default): the kernel that stages
+ * K/V with asynchronous global->LDS copies, which addresses a prompt's packed K (or V) with 32-bit
+ * offsets, and the register-staged kernel (64-bit offsets) for prompts whose packed K exceeds 4 GiB.
+ * PC_ATTN_REGISTER_STAGED: the register-staged kernel for every packed-buffer call (tests and
+ * comparisons; calls that read modules in place keep the automatic choice).  No effect on
+ * head_dim 64 and fp32, which have one kernel each.
+ */
+#define PC_ATTN_AUTO 0
+#define PC_ATTN_REGISTER_STAGED 1
+int pc_set_attn_kernel(pc_ctx *ctx, int which);
+
 /* How the last pc_prefill_attn[_batched] call was launched: number of KV splits,
  * workgroups of the main kernel and waves per workgroup (for benchmarks). */
 int pc_last_attn_launch(const pc_ctx *ctx, int *n_splits, int *n_workgroups, int *waves_per_wg);

@@ -25,7 +25,7 @@ EXPORTS = [
     "pc_schema_layout", "pc_uncached_positions", "pc_check_selection", "pc_bytes_per_token",
     "pc_module_info", "pc_pool_usage", "pc_last_attn_launch", "pc_profile_enable", "pc_profile_read",
     "pc_profile_read_each", "pc_set_module_params", "pc_fill_params",
-    "pc_host_pool_reserve", "pc_store_module_host", "pc_set_host_copy_mode", "pc_set_alibi", "pc_alibi_slopes",
+    "pc_host_pool_reserve", "pc_store_module_host", "pc_set_host_copy_mode", "pc_set_attn_kernel", "pc_set_alibi", "pc_alibi_slopes",
     "pc_define_scaffold", "pc_resolve_scaffolds", "pc_calib_copy", "pc_calib_mfma",
     "pc_append_rotate_batched", "pc_assemble_append_rotate_batched", "pc_prefill_attn_rotated_batched",
     "pc_prefill_attn_shared_rotated_batched",
@@ -33,6 +33,7 @@ EXPORTS = [
 PROF_GATHER, PROF_APPEND, PROF_ATTN, PROF_COMBINE, PROF_ROPE = range(5)
 PC_POS_NONE = 0x7FFFFFFF
 PC_HOST_READ_KERNEL, PC_HOST_COPY_ENGINE = 0, 1
+PC_ATTN_AUTO, PC_ATTN_REGISTER_STAGED = 0, 1
 
 
 class PcConfig(ctypes.Structure):
@@ -79,6 +80,7 @@ def lib() -> ctypes.CDLL:
     L.pc_host_pool_reserve.argtypes = [vp, ctypes.c_size_t]
     L.pc_store_module_host.argtypes = [vp, i, i, vp, vp, i, i]
     L.pc_set_host_copy_mode.argtypes = [vp, i]
+    L.pc_set_attn_kernel.argtypes = [vp, i]
     L.pc_set_alibi.argtypes = [vp, vp]
     L.pc_alibi_slopes.argtypes = [i, vp]
     L.pc_define_scaffold.argtypes = [vp, i, vp, vp]
@@ -324,6 +326,9 @@ class PromptCache:
 
     def pc_set_host_copy_mode(self, mode: int) -> None:
         _check(lib().pc_set_host_copy_mode(self._ctx, int(mode)), "pc_set_host_copy_mode")
+
+    def pc_set_attn_kernel(self, which: int) -> None:
+        _check(lib().pc_set_attn_kernel(self._ctx, int(which)), "pc_set_attn_kernel")
 
     # -- Q rotated once per token (in the append launch) instead of in every attention workgroup
     def pc_append_rotate_batched(self, layer: int, K_new_raw, V_new, Q_new, q_pos, q_offsets: Sequence[int], asm_K, asm_V,

@@ -523,7 +523,7 @@ int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const i
     for (int s = 0; s < batch.n_seqs; ++s) max_kv = batch.seq[s].n_kv > max_kv ? batch.seq[s].n_kv : max_kv;
     const bool fits_u32 = max_kv * (long)Hkv * D * 2 < (1L << 32);   // the wide kernel uses 32-bit row offsets
     // a range table is read by the DMA-staged kernel only (32-bit offsets there are per range, checked by the caller)
-    bool wide = D == 128 && (tab || (max_row_tiles >= kWideMinRowTiles && fits_u32));
+    const bool wide = D == 128 && (tab || (max_row_tiles >= kWideMinRowTiles && fits_u32 && ctx->attn_kernel == PC_ATTN_AUTO));
     const int NW = wide ? 4 : (max_row_tiles <= 4 ? 4 : 8);
     const int tiles_per_wg = wide ? kWideRowTilesPerWg : NW;
     const int rb_max = (max_row_tiles + tiles_per_wg - 1) / tiles_per_wg;

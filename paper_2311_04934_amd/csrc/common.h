@@ -65,6 +65,7 @@ struct pc_ctx {
     uint8_t *host_pool = nullptr;  // module pool in pinned host memory, mapped into the device's address space
     size_t host_pool_bytes = 0, host_pool_used = 0;
     int host_copy_mode = PC_HOST_READ_KERNEL;
+    int attn_kernel = PC_ATTN_AUTO;
     std::vector<std::unordered_map<int, pc::ModuleEntry>> modules;  // per layer
     std::unordered_map<int, std::vector<pc::ParamSlot>> params;     // per module id (schema level, all layers)
     std::vector<pc::Scaffold> scaffolds;                            // in definition order (schema level)

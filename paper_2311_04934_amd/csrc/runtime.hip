@@ -527,6 +527,13 @@ int pc_set_host_copy_mode(pc_ctx *ctx, int mode)
     return PC_OK;
 }
 
+int pc_set_attn_kernel(pc_ctx *ctx, int which)
+{
+    if (!ctx || (which != PC_ATTN_AUTO && which != PC_ATTN_REGISTER_STAGED)) return PC_E_BADARG;
+    ctx->attn_kernel = which;
+    return PC_OK;
+}
+
 int pc_store_module_host(pc_ctx *ctx, int layer, int module_id, const void *K_host, const void *V_host, int n_tokens,
                          int start_pos)
 {

@@ -123,8 +123,10 @@ def oracle_attn(c: Case, pi: int, q_rows: Optional[Sequence[int]] = None) -> np.
 class GpuRunner:
     """Stores a case's modules in a pool and serves its prompts through the C ABI."""
 
-    def __init__(self, c: Case, scratch_bytes: int = 0, host_modules: Sequence[int] = (), host_mode: Optional[int] = None):
-        """host_modules: ids stored in the pinned host pool instead of the HBM pool (Sec. 4.1)."""
+    def __init__(self, c: Case, scratch_bytes: int = 0, host_modules: Sequence[int] = (), host_mode: Optional[int] = None,
+                 attn_kernel: Optional[int] = None):
+        """host_modules: ids stored in the pinned host pool instead of the HBM pool (Sec. 4.1);
+        attn_kernel: PC_ATTN_* choice of the bf16 head_dim-128 kernel (None = the library's own)."""
         self.c = c
         w = c.w
         self.pc = pcb.PromptCache.for_workload(w, n_layers=max(c.layer + 1, 1), scratch_bytes=scratch_bytes)
@@ -137,6 +139,8 @@ class GpuRunner:
             self.pc.pc_host_pool_reserve(sum(2 * (w.sizes[m] * w.row_bytes + 512) for m in host))
         if host_mode is not None:
             self.pc.pc_set_host_copy_mode(host_mode)
+        if attn_kernel is not None:
+            self.pc.pc_set_attn_kernel(attn_kernel)
         for m in sorted(c.mod_K):
             if m in host:
                 self.pc.pc_store_module_host(c.layer, m, c.mod_K[m].contiguous(), c.mod_V[m].contiguous(), c.starts[m])

@@ -630,11 +630,11 @@ def test_host_tier_error_paths():
 
 
 # ------------------------------------------------------------------ linear bias on position IDs (Sec. 4.2, ALiBi)
-def _alibi_run(w, layer, q_sample, in_place=False, slopes=None):
+def _alibi_run(w, layer, q_sample, in_place=False, slopes=None, attn_kernel=None):
     """Modules and new tokens hold unrotated keys; the context adds -slope*(pos_q - pos_k) to the scores.
     Expected: the oracle's attn_alibi over its own concatenation."""
     c = build_case(w, layer, encode_keys=False)
-    r = GpuRunner(c)
+    r = GpuRunner(c, attn_kernel=attn_kernel)
     dev = r.dev
     if slopes is None:
         slopes = pcb.pc_alibi_slopes(w.n_q_heads)
@@ -870,11 +870,11 @@ def test_random_workloads_modules_in_place(seed):
 
 
 # ------------------------------------------------------------------ Q rotated once per token, in the append launch
-def _rotated_run(w, in_place, alibi=False):
+def _rotated_run(w, in_place, alibi=False, attn_kernel=None):
     """The *_rotate calls write Q_rot = rope(Q_new, q_pos) x score scale next to the appended rows; attention on Q_rot
     must give what attention on Q_new gives, and both must match the oracle."""
     c = build_case(w, 0, encode_keys=not alibi)
-    r = GpuRunner(c)
+    r = GpuRunner(c, attn_kernel=attn_kernel)
     dev = r.dev
     slopes = None
     if alibi:
@@ -994,6 +994,82 @@ def test_query_rotation_many_prompts_and_argument_checks():
 
 
 # ------------------------------------------------------------------ HIP graph capture
+# ------------------------------------------------------------------ head_dim 128 on the register-staged kernel
+# (the kernel with 64-bit offsets that takes over when a prompt's packed K exceeds 4 GiB)
+@pytest.mark.parametrize("hq,hkv", [(8, 2), (4, 4)])
+def test_register_staged_kernel_head_dim_128(hq, hkv):
+    w = W.custom(f"bf16_regstaged_{hq}_{hkv}", "bf16", hq, hkv, 128, [200, 333, 64, 77], None,
+                 [W.Prompt([3, 0, 1], 70), W.Prompt([1], 33), W.Prompt([2, 0], 1)], max_pos=2048)
+    run_and_check(w, extra_capacity=3, label="/register-staged", attn_kernel=pcb.PC_ATTN_REGISTER_STAGED)
+    w = W.custom(f"bf16_regstaged_split_{hq}_{hkv}", "bf16", hq, hkv, 128, [900, 700], None, [W.Prompt([0, 1], 40)], max_pos=4096)
+    run_and_check(w, label="/register-staged", attn_kernel=pcb.PC_ATTN_REGISTER_STAGED)
+
+
+def test_register_staged_kernel_head_dim_128_linear_bias_and_rotated_query():
+    w = W.custom("bf16_regstaged_alibi", "bf16", 8, 2, 128, [128, 200, 96], None,
+                 [W.Prompt([0, 2], 24, gap_after=0, n_gap=40), W.Prompt([2, 1, 0], 33)], max_pos=1024)
+    _alibi_run(w, 0, None, attn_kernel=pcb.PC_ATTN_REGISTER_STAGED)
+    w = W.custom("bf16_regstaged_rot", "bf16", 8, 2, 128, [150, 260], None,
+                 [W.Prompt([1, 0], 45), W.Prompt([0], 9)], max_pos=1024)
+    _rotated_run(w, False, attn_kernel=pcb.PC_ATTN_REGISTER_STAGED)
+
+
+def test_set_attn_kernel_argument_check():
+    pc = pcb.PromptCache(1, 8, 2, 128, pcb.PC_BF16, max_pos=64, pool_bytes=1 << 16)
+    try:
+        with pytest.raises(pcb.PcError) as e:
+            pc.pc_set_attn_kernel(7)
+        assert e.value.status == -1   # PC_E_BADARG
+        pc.pc_set_attn_kernel(pcb.PC_ATTN_REGISTER_STAGED)
+        pc.pc_set_attn_kernel(pcb.PC_ATTN_AUTO)
+    finally:
+        pc.close()
+
+
+def test_prompt_with_more_than_4_gib_of_packed_keys():
+    """Maximum size: 2^21 + 4133 rows of 2 KiB, so K and V are 4.3 GB each and byte offsets need 64 bits.
+    Position IDs repeat with period 1000 (i * 7 mod 1000), so about half the keys are hidden from each query.
+    Checked: sampled queries of the first and the last kv head against the oracle run on that head alone."""
+    hq = hkv = 8
+    d, n_kv, n_q = 128, (1 << 21) + 4133, 40
+    dev = torch.device("cuda:0")
+    g = torch.Generator(device=dev)
+    g.manual_seed(4242)
+    K = torch.empty((n_kv, hkv, d), dtype=torch.bfloat16, device=dev)
+    V = torch.empty_like(K)
+    step = 1 << 18
+    for a in range(0, n_kv, step):
+        b = min(n_kv, a + step)
+        K[a:b] = torch.randn((b - a, hkv, d), device=dev, generator=g).to(torch.bfloat16)
+        V[a:b] = torch.randn((b - a, hkv, d), device=dev, generator=g).to(torch.bfloat16)
+    assert K.numel() * 2 > (1 << 32)
+    kv_pos = ((torch.arange(n_kv, dtype=torch.int64, device=dev) * 7) % 1000).to(torch.int32)
+    rng = np.random.default_rng(77)
+    q_pos_h = np.sort(rng.integers(100, 1000, size=n_q)).astype(np.int32)
+    Q = torch.randn((n_q, hq, d), generator=torch.Generator().manual_seed(5)).to(torch.bfloat16)
+    out = torch.full((n_q, hq, d), float("nan"), dtype=torch.bfloat16, device=dev)
+    pc = pcb.PromptCache(1, hq, hkv, d, pcb.PC_BF16, max_pos=1024, pool_bytes=1 << 16)
+    try:
+        pc.pc_prefill_attn(0, Q.to(dev), torch.from_numpy(q_pos_h).to(dev), K, V, kv_pos, n_kv, out)
+        torch.cuda.synchronize()
+        launch = pc.pc_last_attn_launch()
+    finally:
+        pc.close()
+    o = out.cpu()
+    assert not torch.isnan(o).any()
+    rows = np.array([0, 7, 19, 31, 32, n_q - 1])
+    kp = kv_pos.cpu().numpy()
+    for h in (0, hkv - 1):
+        Kh = K[:, h, :].contiguous().cpu().double().numpy()[:, None, :]
+        Vh = V[:, h, :].contiguous().cpu().double().numpy()[:, None, :]
+        ref = oracle.attn(to_f64(Q[rows][:, h:h + 1, :]), q_pos_h[rows], Kh, Vh, kp)
+        err, rel = attn_errors(o[rows][:, h:h + 1, :], ref)
+        print(f"[4 GiB+] head {h}: max abs err {err:.3e}, rel L2 {rel:.3e}, |ref|max {np.abs(ref).max():.3e}, "
+              f"launch(splits, wgs, waves)={launch}", flush=True)
+        assert err <= TOL_ABS["bf16"] and rel <= TOL_REL["bf16"], (err, rel)
+        del Kh, Vh
+
+
 def test_step_replays_from_a_hip_graph():
     """The request-path calls allocate nothing, clear nothing and never synchronise, so a caller may capture
     them.  One captured step (assemble+append, attention with a KV split and its combine) is replayed several
