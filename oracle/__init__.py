@@ -33,12 +33,9 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
-def _load():
-    global _lib
-    if _lib is not None:
-        return _lib
-    build()
-    lib = ctypes.CDLL(_LIB)
+def _bind(path: str):
+    """Open a build of pc_oracle.c and declare its functions' signatures."""
+    lib = ctypes.CDLL(path)
     c_int, c_long, c_dbl, c_sz = ctypes.c_int, ctypes.c_long, ctypes.c_double, ctypes.c_size_t
     P = ctypes.c_void_p
     lib.orc_set_threads.argtypes = [c_int]
@@ -63,8 +60,15 @@ def _load():
     lib.orc_fill_param.restype = c_int
     lib.orc_bytes_per_token.argtypes = [c_int, c_int, c_int, c_int]
     lib.orc_bytes_per_token.restype = c_long
-    _lib = lib
     return lib
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = _bind(_LIB)
+    return _lib
 
 
 def _ptr(a: np.ndarray):
