@@ -227,6 +227,8 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
+    from paper_2311_04934_amd import build as pc_build
+    pc_build.ensure_built()   # the library that is built is the one measured; built here only when none is there
     if args.length_sweep:
         return length_sweep(args)
     dev = torch.device("cuda:0")

@@ -33,6 +33,11 @@ def library_path() -> str:
     return LIB
 
 
+def ensure_built() -> str:
+    """Build only when no library is there (tests, the smoke check and the benchmark load what is built)."""
+    return LIB if os.path.exists(LIB) else build()
+
+
 def build(verbose: bool = False, extra_flags=()) -> str:
     os.makedirs(OBJDIR, exist_ok=True)
     procs = []

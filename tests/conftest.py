@@ -10,6 +10,9 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # the tests load the library that is built; only when none is there do they build it (hipcc cross-compiles)
+    from paper_2311_04934_amd import build as pc_build
+    pc_build.ensure_built()
 
 
 def _gpu_present() -> bool:
