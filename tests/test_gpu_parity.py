@@ -328,6 +328,16 @@ def test_fused_assemble_append_matches_oracle(dtype):
     _batched_run(w, 0, None, fused=True)
 
 
+@pytest.mark.parametrize("hq,hkv", [(8, 8), (16, 16), (32, 4)])
+def test_fused_assemble_append_hundreds_of_tiles_few_rows(hq, hkv):
+    """Several hundred gather tiles with ragged last tiles and a few dozen appended rows behind them in one launch,
+    rows of 2 KiB to 4 KiB, three prompts, with and without the rotated Q rows."""
+    w = W.custom(f"fused_embedded_{hq}_{hkv}", "bf16", hq, hkv, 128, [600, 700, 330], None,
+                 [W.Prompt([0, 1, 2], 40), W.Prompt([1], 25), W.Prompt([2, 0], 3)], max_pos=4096)
+    _batched_run(w, 0, None, fused=True)
+    _rotated_run(w, False)
+
+
 def test_fused_assemble_append_many_prompts_takes_two_launches():
     """More prompts than one argument block holds: the call falls back to gather then append."""
     sizes = [40, 24, 56]
