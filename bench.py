@@ -176,7 +176,7 @@ def length_sweep(args) -> int:
     return 0
 
 
-def main() -> int:
+def main(argv=None) -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
@@ -211,7 +211,7 @@ def main() -> int:
                     help="capture one step (all layers' launches) into a HIP graph and time K replays of it")
     ap.add_argument("--overlap", action="store_true",
                     help="assemble layer l+1 on a second stream while layer l's attention runs")
-    args = ap.parse_args()
+    args = ap.parse_args(argv)
     if args.host_tier and args.modules_in_place:
         print("bench.py: --host-tier modules have to be assembled; it excludes --modules-in-place", file=sys.stderr)
         return 2
