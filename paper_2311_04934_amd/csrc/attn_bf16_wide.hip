@@ -664,13 +664,17 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
 
     // does tile t (already visible in LDS) need the per-element mask for this wave?  Yes when it holds
     // a position ID above the wave's smallest query position, or fewer than 64 real keys.
-    auto tile_needs_mask = [&](int t) -> bool {
-        const int buf = t & (NBUF - 1);
+    // The decision comes in two parts, so that the LDS read's latency can pass behind other work: the
+    // position ID of this lane's key of tile t, and the vote on it.
+    auto tile_pos = [&](int t) -> int {
+        return *reinterpret_cast<const __attribute__((address_space(3))) int *>(lds + LDS_POS + (t & (NBUF - 1)) * KT * 4 + lane * 4);
+    };
+    auto tile_vote = [&](int t, int kpos) -> bool {
         const int n_valid = k_end - (k_begin + t * KT);
-        const int kpos = *reinterpret_cast<const __attribute__((address_space(3))) int *>(lds + LDS_POS + buf * KT * 4 + lane * 4);
         store_bias(t, kpos);
         return __any(kpos > wave_min_qpos) || n_valid < KT;
     };
+    auto tile_needs_mask = [&](int t) -> bool { return tile_vote(t, tile_pos(t)); };
 
     // ---- main loop
     if (n_tiles > 0) {
@@ -731,13 +735,16 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
             // tile t+1 and the V^T fragments of tile t become visible; the copies of tile t+2 may stay in flight
             PC_WAIT_VMCNT(DMA_PER_TILE);
             __syncthreads();
-            const bool mask_next = has_next ? tile_needs_mask(t + 1) : false;
+            // tile t+1's position IDs are read now and voted on after the first step (the read returns behind it)
+            int kpos_next = tile_pos(has_next ? t + 1 : t);
 
             if (mask_cur) apply_mask(sc[0], buf, 0, n_valid);
             rescale();
             // P.V of tile t-1's second half | K.Q of this tile's second half | softmax of its first half;
             // the copies of tile t+3 are issued here
             step(pf[1], k_cur + 32 * ROW_BYTES, sc[1], sc[0], pf[0], v_cur, true, t + 3, false, 0, bias_strip(t, 1));
+            asm volatile("" : "+v"(kpos_next));
+            const bool mask_next = has_next ? tile_vote(t + 1, kpos_next) : false;
 
             if (mask_cur) apply_mask(sc[1], buf, 1, n_valid);
             rescale();
