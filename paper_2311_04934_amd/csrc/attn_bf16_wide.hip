@@ -50,7 +50,7 @@ constexpr int LDS_VT = LDS_V + NVRAW * TILE_BYTES;           // 112 KiB: V^T fra
 constexpr int LDS_POS = LDS_VT + NVT * TILE_BYTES;           // 144 KiB
 constexpr int LDS_BIAS = LDS_POS + NBUF * KT * 4;          // linear-bias variant: per wave, 2 tiles x 64 floats
 constexpr int LDS_MAIN = LDS_BIAS + kWideRowTilesPerWg * 2 * KT * 4;
-constexpr int EPI_STRIDE = D * 4 + 16;           // fp32 row of O plus a 16-byte pad
+constexpr int EPI_STRIDE = D * 2 + 16;           // bf16 row of O plus a 16-byte pad
 constexpr int LDS_EPI = 256 * EPI_STRIDE;        // 256 query rows per workgroup
 constexpr int LDS_TOTAL = LDS_MAIN > LDS_EPI ? LDS_MAIN : LDS_EPI;
 
@@ -777,11 +777,11 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
 #pragma unroll
         for (int b = 0; b < DB; ++b)
 #pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
-                f32x4 w;
+            for (int i4 = 0; i4 < 4; ++i4) {   // 4 consecutive d of this lane's query, rounded to bf16 here
+                bf16x4 w;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) w[e] = o_acc[x][b][i4 * 4 + e] * inv[x];
-                *reinterpret_cast<__attribute__((address_space(3))) f32x4 *>(epi + (x * 32 + col) * EPI_STRIDE + (b * 32 + i4 * 8 + hh * 4) * 4) = w;
+                for (int e = 0; e < 4; ++e) w[e] = (__bf16)(o_acc[x][b][i4 * 4 + e] * inv[x]);
+                *reinterpret_cast<__attribute__((address_space(3))) bf16x4 *>(epi + (x * 32 + col) * EPI_STRIDE + (b * 32 + i4 * 8 + hh * 4) * 2) = w;
             }
     // (m, l) of the partial, one lane per query
     if (p.n_splits > 1 && hh == 0) {
@@ -801,7 +801,6 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
     }
     __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): this wave's LDS writes have landed
     __builtin_amdgcn_wave_barrier();
-    // a wave instruction moves 2 rows of 512 bytes (fp32) or 4 rows of 256 bytes (bf16)
 #pragma unroll
     for (int x = 0; x < NQT; ++x) {
         // row of the row tile handled by each lane's query index: broadcast through the tile descriptor
@@ -815,13 +814,8 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
         for (int it = 0; it < 8; ++it) {
             const int q = it * 4 + (lane >> 4);
             const int qi = tq * RW + q;
-            const lds_u8 *src = epi + (x * 32 + q) * EPI_STRIDE + (lane & 15) * 32;
-            const f32x4 w0 = *reinterpret_cast<const __attribute__((address_space(3))) f32x4 *>(src);
-            const f32x4 w1 = *reinterpret_cast<const __attribute__((address_space(3))) f32x4 *>(src + 16);
+            const bf16x8 o = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8 *>(epi + (x * 32 + q) * EPI_STRIDE + (lane & 15) * 16);
             if (qi < seq.n_q) {
-                bf16x8 o;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) { o[e] = (__bf16)w0[e]; o[4 + e] = (__bf16)w1[e]; }
                 const size_t out_row = (size_t)(seq.q_begin + qi) * p.Hq + head;
                 *reinterpret_cast<bf16x8 *>(dst_base + out_row * D + (lane & 15) * 8) = o;
             }
