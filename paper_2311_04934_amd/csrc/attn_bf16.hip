@@ -118,8 +118,8 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p,
     const int row_tiles = p.G * tiles_q;
     if (rb * NW >= row_tiles) return;   // whole workgroup has nothing to do
 
-    // this split's key range: equal shares rounded up to a multiple of 32 keys
-    const int share = (((seq.n_kv + p.n_splits - 1) / p.n_splits) + 31) & ~31;
+    // this split's key range: equal shares rounded up to whole 64-key tiles (only a prompt's last split ends ragged)
+    const int share = (((seq.n_kv + p.n_splits - 1) / p.n_splits) + KT - 1) & ~(KT - 1);
     const int k_begin = split * share < seq.n_kv ? split * share : seq.n_kv;
     const int k_end = k_begin + share < seq.n_kv ? k_begin + share : seq.n_kv;
     const int n_tiles = (k_end - k_begin + KT - 1) / KT;

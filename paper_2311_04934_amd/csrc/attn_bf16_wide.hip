@@ -123,7 +123,9 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
     const int row_tiles = p.G * tiles_q;
     if (rb * kWideRowTilesPerWg >= row_tiles) return;
 
-    const int share = (((seq.n_kv + p.n_splits - 1) / p.n_splits) + 31) & ~31;
+    // a split's share of the keys is a whole number of 64-key tiles: only the last split of a prompt then ends in a
+    // ragged tile (which costs a masked iteration), and with 16.5 tiles per split every split would have one
+    const int share = (((seq.n_kv + p.n_splits - 1) / p.n_splits) + KT - 1) & ~(KT - 1);
     const int k_begin = split * share < seq.n_kv ? split * share : seq.n_kv;
     const int k_end = k_begin + share < seq.n_kv ? k_begin + share : seq.n_kv;
     const int n_tiles = (k_end - k_begin + KT - 1) / KT;
