@@ -273,10 +273,10 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
     };
 
     // ---- prologue.  Order matters for latency.  The position IDs come first (the rotation-table
-    // addresses depend on them).  Then three kinds of requests go out together: the raw Q rows, as
-    // asynchronous copies into LDS (whole 256-byte rows per 16 lanes, where a direct load into the
-    // MFMA operand layout would touch 32 cache lines per instruction); the first two K/V tiles; and
-    // the table values.  The compiler does not see the copies: when it waits for the table values,
+    // addresses depend on them).  Then three kinds of requests go out together: the first two K/V tiles
+    // (from HBM, the longest wait, so they go first); the raw Q rows, as asynchronous copies into LDS
+    // (whole 256-byte rows per 16 lanes, where a direct load into the MFMA operand layout would touch
+    // 32 cache lines per instruction); and the table values.  The compiler does not see the copies: when it waits for the table values,
     // the older copies still in flight make that wait longer (all of them are needed now anyway),
     // while younger copies could let the count drop early, so the third tile is issued later.
     //
@@ -292,6 +292,9 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
         int qq = qt[0].qpos;
         asm volatile("" : "+v"(qq));   // the position IDs have arrived
         qt[0].qpos = qq;
+        // K/V come from HBM and are requested first; the Q rows (shared by all KV splits) mostly hit in cache
+        issue_tile(0);
+        issue_tile(1);
 #pragma unroll
         for (int x = 0; x < NQT; ++x) {
             const uint8_t *qhead = reinterpret_cast<const uint8_t *>(p.q) + ((size_t)seq.q_begin * p.Hq + qt[x].head) * (D * 2);
@@ -304,8 +307,6 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
                 dma_b128(qhead + (size_t)qi * p.Hq * (D * 2) + ((c ^ (r & 15)) << 4), dst0 + j * 1024);
             }
         }
-        issue_tile(0);
-        issue_tile(1);
         // table values (position-minor table: the 32 lanes of a half-wave hold 32 queries, usually at
         // consecutive positions, so one pair index is a contiguous 256-byte read for them)
         float2 cs[NQT][KB / 2][8];
