@@ -105,6 +105,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);   // the same number in a scalar register (for the epilogue)
     const int col = lane & 31;
     const int hh = lane >> 5;
 
@@ -768,13 +769,17 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
 
     // ---- epilogue: O^T -> LDS -> whole rows to global
     __syncthreads();   // every wave is done with the K/V buffers
+    // Lane and wave indices for the epilogue: from the hardware's lane counter and from a scalar register, so that
+    // the prologue's per-lane indices need not live (or be spilled) across the main loop, which has no register to spare.
+    const int lane_e = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+    const int wave_e = wave_s, col_e = lane_e & 31, hh_e = lane_e >> 5;
     float l_tot[NQT], inv[NQT];
 #pragma unroll
     for (int x = 0; x < NQT; ++x) {
         l_tot[x] = sum_across_halves(l_run[x]);
         inv[x] = p.n_splits == 1 ? (l_tot[x] > 0.f ? 1.f / l_tot[x] : 0.f) : 1.f;
     }
-    lds_u8 *epi = lds + wave * NQT * 32 * EPI_STRIDE;
+    lds_u8 *epi = lds + wave_e * NQT * 32 * EPI_STRIDE;
 #pragma unroll
     for (int x = 0; x < NQT; ++x)
 #pragma unroll
@@ -784,17 +789,14 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
                 bf16x4 w;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) w[e] = (__bf16)(o_acc[x][b][i4 * 4 + e] * inv[x]);
-                *reinterpret_cast<__attribute__((address_space(3))) bf16x4 *>(epi + (x * 32 + col) * EPI_STRIDE + (b * 32 + i4 * 8 + hh * 4) * 2) = w;
+                *reinterpret_cast<__attribute__((address_space(3))) bf16x4 *>(epi + (x * 32 + col_e) * EPI_STRIDE + (b * 32 + i4 * 8 + hh_e * 4) * 2) = w;
             }
     // (m, l) of the partial, one lane per query
-    if (p.n_splits > 1 && hh == 0) {
-        // the row index is recomputed from an opaque copy of the lane's column: kept from the prologue it
-        // would occupy two registers across the whole main loop, which has none to spare
-        int col2 = lane & 31;
-        asm volatile("" : "+v"(col2));
+    if (p.n_splits > 1 && hh_e == 0) {
+        const int col2 = col_e;
 #pragma unroll
         for (int x = 0; x < NQT; ++x) {
-            const int rt = __builtin_amdgcn_readfirstlane(rb * kWideRowTilesPerWg + wave * NQT + x);
+            const int rt = __builtin_amdgcn_readfirstlane(rb * kWideRowTilesPerWg + wave_e * NQT + x);
             const int qi2 = (rt % tiles_q) * RW + col2;
             if (rt < row_tiles && qi2 < seq.n_q) {
                 const size_t out_row = (size_t)(seq.q_begin + qi2) * p.Hq + (kvh * p.G + rt / tiles_q);
@@ -807,7 +809,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
 #pragma unroll
     for (int x = 0; x < NQT; ++x) {
         // row of the row tile handled by each lane's query index: broadcast through the tile descriptor
-        const int rt = rb * kWideRowTilesPerWg + wave * NQT + x;
+        const int rt = rb * kWideRowTilesPerWg + wave_e * NQT + x;
         if (rt >= row_tiles) continue;
         const int g_head = rt / tiles_q, tq = rt % tiles_q;
         const int head = kvh * p.G + g_head;
@@ -815,12 +817,12 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
         uint16_t *dst_base = p.n_splits > 1 ? p.part_o + (size_t)split * p.total_q * p.Hq * D : p.out;
 #pragma unroll 4
         for (int it = 0; it < 8; ++it) {
-            const int q = it * 4 + (lane >> 4);
+            const int q = it * 4 + (lane_e >> 4);
             const int qi = tq * RW + q;
-            const bf16x8 o = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8 *>(epi + (x * 32 + q) * EPI_STRIDE + (lane & 15) * 16);
+            const bf16x8 o = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8 *>(epi + (x * 32 + q) * EPI_STRIDE + (lane_e & 15) * 16);
             if (qi < seq.n_q) {
                 const size_t out_row = (size_t)(seq.q_begin + qi) * p.Hq + head;
-                *reinterpret_cast<bf16x8 *>(dst_base + out_row * D + (lane & 15) * 8) = o;
+                *reinterpret_cast<bf16x8 *>(dst_base + out_row * D + (lane_e & 15) * 8) = o;
             }
         }
     }
