@@ -109,9 +109,10 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p,
     const int g = (slot / p.rb_max) * 8 + xcd;
     const int rb = slot % p.rb_max;
     if (g >= p.n_groups) return;
-    const int split = g % p.n_splits;
-    const int seq_i = (g / p.n_splits) % p.batch.n_seqs;
-    const int kvh = g / (p.n_splits * p.batch.n_seqs);
+    // kv head fastest: the KV splits of a (prompt, kv head) share an XCD, hence its L2 copy of their query rows
+    const int kvh = g % p.Hkv;
+    const int split = (g / p.Hkv) % p.n_splits;
+    const int seq_i = g / (p.Hkv * p.n_splits);
     const AttnSeq seq = p.batch.seq[seq_i];
 
     const int tiles_q = (seq.n_q + RW - 1) / RW;

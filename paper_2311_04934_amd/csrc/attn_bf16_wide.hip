@@ -115,9 +115,12 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
     const int g = (slot / p.rb_max) * 8 + xcd;
     const int rb = slot % p.rb_max;
     if (g >= p.n_groups) return;
-    const int split = g % p.n_splits;
-    const int seq_i = (g / p.n_splits) % p.batch.n_seqs;
-    const int kvh = g / (p.n_splits * p.batch.n_seqs);
+    // the kv head varies fastest, so g % 8 (the XCD) follows the kv head: all KV splits of a (prompt, kv head) run on
+    // one XCD and fetch the query rows of that head group once into its L2 (with the split fastest, every XCD
+    // fetched the whole Q: 8 x 2.1 MB at config 3), while each K/V range is still read by one XCD only
+    const int kvh = g % p.Hkv;
+    const int split = (g / p.Hkv) % p.n_splits;
+    const int seq_i = g / (p.Hkv * p.n_splits);
     const AttnSeq seq = p.batch.seq[seq_i];
 
     const int tiles_q = (seq.n_q + RW - 1) / RW;
