@@ -538,6 +538,14 @@ int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const i
     if (n_splits > max_by_keys) n_splits = max_by_keys;
     if (n_splits > 32) n_splits = 32;
     if (n_splits < 1) n_splits = 1;
+    // A split's share is a whole number of 64-key tiles (the kernels round it up), so with T tiles in the longest
+    // prompt only ceil(T / ceil(T / n_splits)) splits get any keys: launch exactly those.  The others would run a
+    // prologue and write partials that the merge then reads for nothing.
+    if (n_splits > 1) {
+        const int longest = (int)((max_kv + KT - 1) / KT);
+        const int tiles_per_split = (longest + n_splits - 1) / n_splits;
+        n_splits = (longest + tiles_per_split - 1) / tiles_per_split;
+    }
     const size_t per_split = (size_t)total_q * Hq * (D * sizeof(uint16_t) + sizeof(float2));
     if (n_splits > 1) {
         const size_t fit = ctx->scratch_bytes / per_split;
