@@ -338,11 +338,12 @@ def test_fused_assemble_append_hundreds_of_tiles_few_rows(hq, hkv):
     _rotated_run(w, False)
 
 
+@pytest.mark.parametrize("d", [128, 64])
 @pytest.mark.parametrize("in_place", [False, True])
-def test_split_kv_with_prompts_of_unequal_length_leaves_some_splits_empty(in_place):
+def test_split_kv_with_prompts_of_unequal_length_leaves_some_splits_empty(in_place, d):
     """One launch, two prompts of 940 and 1940 keys: the number of KV splits follows the longer one (7 splits of 5
     tiles), the shorter one's share is 3 tiles, so its last two splits get no keys at all and contribute nothing."""
-    w = W.custom("split_unequal", "bf16", 8, 2, 128, [900, 1900], None, [W.Prompt([0], 40), W.Prompt([1], 40)], max_pos=4096)
+    w = W.custom(f"split_unequal_{d}", "bf16", 8, 2, d, [900, 1900], None, [W.Prompt([0], 40), W.Prompt([1], 40)], max_pos=4096)
     if in_place:
         _shared_run(w, 0, None)
     else:
