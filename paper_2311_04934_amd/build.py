@@ -7,6 +7,7 @@ hipcc cross-compiles for gfx950 without a GPU present.  Objects go to
 """
 from __future__ import annotations
 
+import hashlib
 import os
 import subprocess
 import sys
@@ -25,6 +26,7 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 VALU forms
     "-Wall", "-Wno-unused-function",
+    "-Wno-inline-asm",   # the asynchronous-copy statements name m0 as clobbered; the compiler notes that m0 is reserved
     "-I", INCLUDE, "-I", CSRC,
 ]
 
@@ -33,9 +35,33 @@ def library_path() -> str:
     return LIB
 
 
+HASH_FILE = LIB + ".sha256"
+
+
+def source_hash() -> str:
+    """Hash of everything the library is built from: the sources, the headers and the compiler flags."""
+    h = hashlib.sha256(" ".join(FLAGS[:-4]).encode())
+    for d in (CSRC, INCLUDE):
+        for name in sorted(os.listdir(d)):
+            if name.endswith((".hip", ".h")):
+                h.update(name.encode())
+                with open(os.path.join(d, name), "rb") as f:
+                    h.update(f.read())
+    return h.hexdigest()
+
+
+def built_hash() -> str | None:
+    """The source hash recorded beside the library when it was built (None: no library, or no record)."""
+    if not (os.path.exists(LIB) and os.path.exists(HASH_FILE)):
+        return None
+    with open(HASH_FILE) as f:
+        return f.read().strip()
+
+
 def ensure_built() -> str:
-    """Build only when no library is there (tests, the smoke check and the benchmark load what is built)."""
-    return LIB if os.path.exists(LIB) else build()
+    """Tests, the smoke check and the benchmark load what is built.  The library is rebuilt when it is missing or
+    was built from other sources than the tree now holds (contents are compared, not time stamps)."""
+    return LIB if built_hash() == source_hash() else build()
 
 
 def build(verbose: bool = False, extra_flags=()) -> str:
@@ -61,7 +87,12 @@ def build(verbose: bool = False, extra_flags=()) -> str:
     if failed:
         raise RuntimeError("hipcc failed")
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    if os.path.exists(HASH_FILE):
+        os.remove(HASH_FILE)
     subprocess.run(cmd, check=True)
+    if not extra_flags:      # only a plain build stands for the sources as they are
+        with open(HASH_FILE, "w") as f:
+            f.write(source_hash() + "\n")
     return LIB
 
 

@@ -68,11 +68,11 @@ typedef short s16x8 __attribute__((ext_vector_type(8)));
 // workgroup barrier that publishes a tile.
 __device__ __forceinline__ void dma_b128(const void *gsrc, uint32_t lds_addr)
 {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gsrc) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gsrc) : "memory", "m0");
 }
 __device__ __forceinline__ void dma_b32(const void *gsrc, uint32_t lds_addr)
 {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_addr), "v"(gsrc) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_addr), "v"(gsrc) : "memory", "m0");
 }
 
 struct QTile {        // one 32-query row tile of a wave

@@ -26,6 +26,51 @@ def test_more_than_one_gpu_is_refused_with_a_message():
     assert "one GPU" in err
 
 
+def _visible_pairs(w, starts, prompt):
+    """Brute force: (query, key) pairs of one prompt with pos_k <= pos_q, keys = imported module tokens + own tokens."""
+    last = max(prompt.module_ids, key=lambda m: starts[m] + w.sizes[m])
+    q_pos = [starts[last] + w.sizes[last] + i for i in range(prompt.n_new)]
+    k_pos = [starts[m] + i for m in prompt.module_ids for i in range(w.sizes[m])] + q_pos
+    return sum(1 for pq in q_pos for pk in k_pos if pk <= pq)
+
+
+def test_attn_flops_counts_the_visible_pairs_only():
+    """bench.attn_flops (the numerator of every TFLOP/s figure) against a brute-force count of visible
+    (query, key) pairs, 4 x head_dim FLOPs per pair and query head, on small schemas with gaps and unions."""
+    import oracle
+    from paper_2311_04934_amd import workloads as W
+    cases = [W.custom("flops_a", "bf16", 8, 2, 128, [37, 50, 21], None, [W.Prompt([0, 2], 9), W.Prompt([1], 1)], max_pos=256),
+             W.custom("flops_b", "bf16", 4, 4, 64, [30, 64, 90, 17], [-1, 0, 0, -1], [W.Prompt([3, 1], 12), W.Prompt([0, 2, 3], 5)],
+                      max_pos=512),
+             W.tiny_fp32()]
+    for w in cases:
+        starts, _ = oracle.layout(w.sizes, w.union_ids)
+        n_mod = [sum(w.sizes[m] for m in p.module_ids) for p in w.prompts]
+        n_new = [p.n_new for p in w.prompts]
+        pairs = sum(_visible_pairs(w, starts, p) for p in w.prompts)
+        assert bench.attn_flops(w, n_mod, n_new) == 4 * w.head_dim * w.n_q_heads * pairs, w.name
+
+
+def test_full_prefill_flop_count_against_the_papers_cost_model():
+    """Sec. 2.2: a prefill over n tokens costs about 6 n d^2 + 4 n^2 d (d = hidden size); the 4 n^2 d term is the
+    attention over ALL n^2 pairs.  Under the causal rule n(n+1)/2 pairs are visible, so the benchmark's count for
+    'every token is a query' must be that term times (n+1)/(2n).  The formula is read from tests/golden/."""
+    from paper_2311_04934_amd import workloads as W
+    formulas = {}
+    for line in open(os.path.join(ROOT, "tests", "golden", "flops_model.txt")):
+        if line.strip() and not line.startswith("#"):
+            name, expr = line.split()
+            formulas[name] = expr.replace("^", "**")
+    for n, hq, dh in ((1000, 32, 128), (2240, 32, 128), (77, 4, 64)):
+        d = hq * dh
+        attention_term = eval(formulas["prefill"], {"n": n, "d": d}) - 6 * n * d * d
+        assert attention_term == 4 * n * n * d
+        w = W.custom("flops_full", "bf16", hq, hq, dh, [1], None, [W.Prompt([0], n)], max_pos=4096)
+        assert bench.attn_flops(w, [0], [n]) * 2 * n == attention_term * (n + 1)
+        # one decoding step over n cached tokens: the 4 n d term = one query seeing n keys
+        assert eval(formulas["decode"], {"n": n, "d": d}) - 6 * d * d == bench.attn_flops(w, [n], [1]) - 4 * d
+
+
 @pytest.mark.gpu
 def test_default_workload_prints_one_json_line_with_the_agreed_keys():
     rc, out, _ = _run(["--layers", "2", "--steps", "2", "--warmup", "1", "--no-full-prefill"])
