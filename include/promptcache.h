@@ -40,6 +40,8 @@
  * Errors      0 on success, a negative pc_status otherwise.  On error no device
  *             work has been enqueued by that call.  pc_strerror names the code.
  * Threads     a pc_ctx must not be used from two host threads at once.
+ * Streams     attention calls of one context share its split-KV scratch: keep them
+ *             on one stream (see pc_prefill_attn).  Assembly calls may run on another.
  */
 #ifndef PROMPTCACHE_H
 #define PROMPTCACHE_H
@@ -153,12 +155,35 @@ int pc_assemble_kv(pc_ctx *ctx, int layer, const int *module_ids, int n_modules,
  * PC_BF16: QK^T and PV run on bf16 MFMA with fp32 accumulation and fp32 softmax
  * statistics; PC_F32: everything in fp32.  The work is split over the KV axis
  * when that is needed to fill the GPU; partial results go through the context's
- * scratch and a small merge kernel, all on `stream`.
- * Errors   PC_E_LAYER, PC_E_BADARG, PC_E_CAPACITY (scratch too small for n_q).
+ * scratch and a small merge kernel, all on `stream`.  A scratch too small for the
+ * wanted number of splits is no error: the call then runs with as many splits as
+ * fit (down to one, which needs none).
+ * The context has ONE scratch: attention calls of one context (every
+ * pc_prefill_attn* call) must be enqueued on one stream, or be ordered by the
+ * caller; two of them running at once would overwrite each other's partials.
+ * Errors   PC_E_LAYER, PC_E_BADARG.
  */
 int pc_prefill_attn(pc_ctx *ctx, int layer, const void *Q_new, const int32_t *q_pos, int n_q,
                     const void *asm_K, const void *asm_V, const int32_t *asm_pos, int n_kv,
                     void *out, void *stream);
+
+/*
+ * pc_prefill_attn for callers that cannot allocate device memory or hand the library any:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same result (bit for bit: the same launch decomposition).  The split-KV partials go to
+ * a fixed array of PC_STATIC_SCRATCH_BYTES that is part of the library's device code (one copy per
+ * GPU, held until the process ends) instead of the context's scratch; the call allocates nothing
+ * and clears nothing (every byte it reads it has written in the same call).
+ * A launch whose partials exceed the array is refused with PC_E_CAPACITY and nothing is enqueued
+ * (partials take n_splits * n_q * n_q_heads * (2 * head_dim + 8) bytes, about 17 MB when one split
+ * pass fills the GPU and at most twice that).
+ * All calls on one GPU share that GPU's array, whichever context or stream they use: two
+ * pc_prefill_attn_static calls that overlap in time on one GPU race.  Order them on one stream.
+ */
+#define PC_STATIC_SCRATCH_BYTES (32u << 20)
+int pc_prefill_attn_static(pc_ctx *ctx, int layer, const void *Q_new, const int32_t *q_pos, int n_q,
+                           const void *asm_K, const void *asm_V, const int32_t *asm_pos, int n_kv,
+                           void *out, void *stream);
 
 /* --------------------------------------------------------- supporting calls */
 

@@ -28,8 +28,9 @@ EXPORTS = [
     "pc_host_pool_reserve", "pc_store_module_host", "pc_set_host_copy_mode", "pc_set_attn_kernel", "pc_set_alibi", "pc_alibi_slopes",
     "pc_define_scaffold", "pc_resolve_scaffolds", "pc_calib_copy", "pc_calib_mfma",
     "pc_append_rotate_batched", "pc_assemble_append_rotate_batched", "pc_prefill_attn_rotated_batched",
-    "pc_prefill_attn_shared_rotated_batched",
+    "pc_prefill_attn_shared_rotated_batched", "pc_prefill_attn_static",
 ]
+PC_STATIC_SCRATCH_BYTES = 32 << 20
 PROF_GATHER, PROF_APPEND, PROF_ATTN, PROF_COMBINE, PROF_ROPE = range(5)
 PC_POS_NONE = 0x7FFFFFFF
 PC_HOST_READ_KERNEL, PC_HOST_COPY_ENGINE = 0, 1
@@ -70,6 +71,7 @@ def lib() -> ctypes.CDLL:
     L.pc_store_module.argtypes = [vp, i, i, vp, vp, i, i, vp]
     L.pc_assemble_kv.argtypes = [vp, i, vp, i, vp, vp, vp, i, ip, vp]
     L.pc_prefill_attn.argtypes = [vp, i, vp, vp, i, vp, vp, vp, i, vp, vp]
+    L.pc_prefill_attn_static.argtypes = [vp, i, vp, vp, i, vp, vp, vp, i, vp, vp]
     L.pc_rope.argtypes = [vp, vp, i, i, vp, vp]
     L.pc_append_kv.argtypes = [vp, i, vp, vp, vp, i, vp, vp, vp, i, i, vp]
     L.pc_assemble_kv_batched.argtypes = [vp, i, vp, vp, i, vp, vp, vp, vp, vp, vp]
@@ -243,6 +245,11 @@ class PromptCache:
         n_q = int(Q_new.shape[0])
         _check(lib().pc_prefill_attn(self._ctx, layer, _dev(Q_new), _dev(q_pos), n_q, _dev(asm_K), _dev(asm_V),
                                      _dev(asm_pos), n_kv, _dev(out), _stream(stream)), "pc_prefill_attn")
+
+    def pc_prefill_attn_static(self, layer: int, Q_new, q_pos, asm_K, asm_V, asm_pos, n_kv: int, out, stream=None) -> None:
+        n_q = int(Q_new.shape[0])
+        _check(lib().pc_prefill_attn_static(self._ctx, layer, _dev(Q_new), _dev(q_pos), n_q, _dev(asm_K), _dev(asm_V),
+                                            _dev(asm_pos), n_kv, _dev(out), _stream(stream)), "pc_prefill_attn_static")
 
     # -- supporting calls
     def pc_rope(self, x, pos, stream=None) -> None:

@@ -503,8 +503,11 @@ int launch_variant(pc_ctx *ctx, AttnParams &p, int n_blocks, hipStream_t stream,
 }  // namespace
 
 int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const int32_t *q_pos, const void *k,
-                     const void *v, const int32_t *kv_pos, void *out, hipStream_t stream, const KvSegTable *tab, bool q_rotated)
+                     const void *v, const int32_t *kv_pos, void *out, hipStream_t stream, const KvSegTable *tab, bool q_rotated,
+                     const ScratchRef *scratch)
 {
+    const ScratchRef own{reinterpret_cast<uint8_t *>(ctx->scratch), ctx->scratch_bytes, false};
+    const ScratchRef &sc = scratch ? *scratch : own;
     const int D = ctx->cfg.head_dim, Hq = ctx->cfg.n_q_heads, Hkv = ctx->cfg.n_kv_heads, G = Hq / Hkv;
     if (D != 64 && D != 128) return PC_E_UNSUPPORTED;
 
@@ -546,11 +549,12 @@ int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const i
         const int tiles_per_split = (longest + n_splits - 1) / n_splits;
         n_splits = (longest + tiles_per_split - 1) / tiles_per_split;
     }
-    const size_t per_split = (size_t)total_q * Hq * (D * sizeof(uint16_t) + sizeof(float2));
-    if (n_splits > 1) {
-        const size_t fit = ctx->scratch_bytes / per_split;
-        if (fit < 2) n_splits = 1;
-        else if ((size_t)n_splits > fit) n_splits = (int)fit;
+    // partial O of every split, padded to 256 bytes, then every split's (m, l)
+    auto ml_offset = [&](int ns) { return ((size_t)ns * total_q * Hq * D * sizeof(uint16_t) + 255) & ~(size_t)255; };
+    auto scratch_need = [&](int ns) { return ml_offset(ns) + (size_t)ns * total_q * Hq * sizeof(float2); };
+    if (n_splits > 1 && scratch_need(n_splits) > sc.bytes) {
+        if (sc.strict) return PC_E_CAPACITY;
+        while (n_splits > 1 && scratch_need(n_splits) > sc.bytes) --n_splits;
     }
 
     AttnParams p;
@@ -560,8 +564,8 @@ int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const i
     p.v = static_cast<const uint16_t *>(v);
     p.kv_pos = kv_pos;
     p.out = static_cast<uint16_t *>(out);
-    p.part_o = reinterpret_cast<uint16_t *>(ctx->scratch);
-    p.part_ml = reinterpret_cast<float2 *>(reinterpret_cast<uint8_t *>(ctx->scratch) + (((size_t)n_splits * total_q * Hq * D * sizeof(uint16_t) + 255) & ~(size_t)255));
+    p.part_o = reinterpret_cast<uint16_t *>(sc.ptr);
+    p.part_ml = reinterpret_cast<float2 *>(sc.ptr + ml_offset(n_splits));
     p.rope = ctx->rope_table;
     p.rope_t = ctx->rope_table_t;
     p.alibi = ctx->use_alibi ? ctx->alibi : nullptr;

@@ -79,6 +79,7 @@ struct pc_ctx {
 
     float *scratch = nullptr;  // device, split-KV partials
     size_t scratch_bytes = 0;
+    uint8_t *static_scratch = nullptr;  // this device's copy of the library's fixed scratch array (pc_prefill_attn_static)
 
     int n_cu = 256;
     pc::AttnLaunchInfo last_attn;
@@ -163,6 +164,14 @@ struct AttnBatch {
     AttnSeq seq[kMaxAttnSeqs];
 };
 
+// Where an attention launch keeps its split-KV partials.  strict: a launch whose partials do not fit is refused
+// (PC_E_CAPACITY) instead of being run with fewer splits.
+struct ScratchRef {
+    uint8_t *ptr;
+    size_t bytes;
+    bool strict;
+};
+
 struct KvSegTable;
 int launch_attn_f32(pc_ctx *ctx, const AttnBatch &batch, const float *q, const int32_t *q_pos, const float *k,
                     const float *v, const int32_t *kv_pos, float *out, hipStream_t stream, const KvSegTable *tab = nullptr,
@@ -170,7 +179,7 @@ int launch_attn_f32(pc_ctx *ctx, const AttnBatch &batch, const float *q, const i
 
 int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const int32_t *q_pos, const void *k,
                      const void *v, const int32_t *kv_pos, void *out, hipStream_t stream, const KvSegTable *tab = nullptr,
-                     bool q_rotated = false);
+                     bool q_rotated = false, const ScratchRef *scratch = nullptr /* nullptr: the context's own */);
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? PC_OK : PC_E_HIP; }
 

@@ -14,10 +14,20 @@
 
 using namespace pc;
 
+static __device__ __align__(256) uint8_t scratch[PC_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 constexpr size_t kPoolAlign = 256;
 constexpr size_t kDefaultScratch = (size_t)256 << 20;
+
+// Fixed scratch of pc_prefill_attn_static: split-KV partials of callers that must not allocate.  Every GPU the
+// library runs on holds its own copy of the array (until the process ends) at its own address; in host code the
+// array's name is only a handle for hipGetSymbolAddress, never a device address.  pc_create looks the address up
+// once per device and every later use goes through that pointer.
+constexpr size_t kStaticScratchBytes = (size_t)PC_STATIC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+uint8_t *g_static_scratch[kMaxDevices] = {nullptr};   // per device, filled by pc_create with that device current
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -232,12 +242,12 @@ float q_prescale(const pc_ctx *ctx)
 }
 
 int run_attn(pc_ctx *ctx, const AttnBatch &b, const void *Q, const int32_t *q_pos, const void *K, const void *V,
-             const int32_t *pos, void *out, hipStream_t stream, bool q_rotated = false)
+             const int32_t *pos, void *out, hipStream_t stream, bool q_rotated = false, const ScratchRef *scratch = nullptr)
 {
-    if (ctx->cfg.dtype == PC_F32)
+    if (ctx->cfg.dtype == PC_F32)   // one wave per (query, head), no KV split: no scratch
         return launch_attn_f32(ctx, b, static_cast<const float *>(Q), q_pos, static_cast<const float *>(K),
                                static_cast<const float *>(V), pos, static_cast<float *>(out), stream, nullptr, q_rotated);
-    return launch_attn_bf16(ctx, b, Q, q_pos, K, V, pos, out, stream, nullptr, q_rotated);
+    return launch_attn_bf16(ctx, b, Q, q_pos, K, V, pos, out, stream, nullptr, q_rotated, scratch);
 }
 
 }  // namespace
@@ -279,7 +289,13 @@ int pc_create(const pc_config *cfg, pc_ctx **out_ctx)
     ctx->modules.resize(cfg->n_layers);
     ctx->scratch_bytes = cfg->scratch_bytes ? cfg->scratch_bytes : kDefaultScratch;
 
-    bool ok = hipGetDevice(&ctx->device) == hipSuccess;
+    bool ok = hipGetDevice(&ctx->device) == hipSuccess && ctx->device >= 0 && ctx->device < kMaxDevices;
+    if (ok && !g_static_scratch[ctx->device]) {   // this device's copy of the fixed scratch array
+        void *ptr = nullptr;
+        ok = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) == hipSuccess && ptr != nullptr;
+        if (ok) g_static_scratch[ctx->device] = static_cast<uint8_t *>(ptr);
+    }
+    if (ok) ctx->static_scratch = g_static_scratch[ctx->device];
     hipDeviceProp_t prop;
     if (ok && hipGetDeviceProperties(&prop, ctx->device) == hipSuccess) ctx->n_cu = prop.multiProcessorCount;
     if (ok && cfg->pool_bytes) ok = hipMalloc(reinterpret_cast<void **>(&ctx->pool), cfg->pool_bytes) == hipSuccess;
@@ -830,7 +846,8 @@ int pc_append_kv(pc_ctx *ctx, int layer, const void *K_new_raw, const void *V_ne
 
 static int prefill_attn_batched_impl(pc_ctx *ctx, int layer, const void *Q_new, const int32_t *q_pos, const int *q_offsets,
                                      int n_prompts, const void *asm_K, const void *asm_V, const int32_t *asm_pos,
-                                     const int *kv_offsets, const int *kv_lens, void *out, void *stream, bool q_rotated)
+                                     const int *kv_offsets, const int *kv_lens, void *out, void *stream, bool q_rotated,
+                                     const ScratchRef *scratch = nullptr)
 {
     if (!ctx || n_prompts < 0 || !q_offsets || !kv_offsets || !kv_lens) return PC_E_BADARG;
     if (layer < 0 || layer >= ctx->cfg.n_layers) return PC_E_LAYER;
@@ -856,7 +873,7 @@ static int prefill_attn_batched_impl(pc_ctx *ctx, int layer, const void *Q_new, 
             ab.seq[i].kv_begin = kv_offsets[b];
             ab.seq[i].n_kv = kv_lens[b];
         }
-        int rc = run_attn(ctx, ab, Q_new, q_pos, asm_K, asm_V, asm_pos, out, as_stream(stream), q_rotated);
+        int rc = run_attn(ctx, ab, Q_new, q_pos, asm_K, asm_V, asm_pos, out, as_stream(stream), q_rotated, scratch);
         if (rc != PC_OK) return rc;
     }
     return PC_OK;
@@ -986,6 +1003,19 @@ int pc_prefill_attn(pc_ctx *ctx, int layer, const void *Q_new, const int32_t *q_
     const int kv_lens[1] = {n_kv};
     return pc_prefill_attn_batched(ctx, layer, Q_new, q_pos, q_offsets, 1, asm_K, asm_V, asm_pos, kv_offsets, kv_lens,
                                    out, stream);
+}
+
+int pc_prefill_attn_static(pc_ctx *ctx, int layer, const void *Q_new, const int32_t *q_pos, int n_q, const void *asm_K,
+                           const void *asm_V, const int32_t *asm_pos, int n_kv, void *out, void *stream)
+{
+    if (!ctx || n_q < 0 || n_kv < 0) return PC_E_BADARG;
+    if (!ctx->static_scratch) return PC_E_HIP;
+    const int q_offsets[2] = {0, n_q};
+    const int kv_offsets[2] = {0, n_kv};
+    const int kv_lens[1] = {n_kv};
+    const ScratchRef fixed{ctx->static_scratch, kStaticScratchBytes, true};
+    return prefill_attn_batched_impl(ctx, layer, Q_new, q_pos, q_offsets, 1, asm_K, asm_V, asm_pos, kv_offsets, kv_lens, out,
+                                     stream, false, &fixed);
 }
 
 /* ------------------------------------------------------------ host integers */
