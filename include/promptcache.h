@@ -261,6 +261,27 @@ int pc_assemble_kv_batched(pc_ctx *ctx, int layer, const int *module_ids_flat, c
                            int n_prompts, void *out_K, void *out_V, int32_t *out_pos,
                            const int *kv_offsets, int *out_n_tokens, void *stream);
 
+/*
+ * Sec. 3.4: retrieving the cached modules "solely requires memory copy" and does not depend on the
+ * forward pass, so the modules of ALL layers can be concatenated when the request arrives, before
+ * the first layer runs.  This call does pc_assemble_kv_batched for layers first_layer ..
+ * first_layer+n_layers-1 with as few kernel launches as the kernels' segment tables allow (64
+ * module segments and 32 layers per launch), which spreads a launch's fixed cost over gigabytes
+ * instead of tens of megabytes.  The uncached tokens' rows are appended per layer afterwards
+ * (pc_append_kv_batched / pc_append_rotate_batched), when the forward pass has produced them.
+ *
+ * out_K, out_V, out_pos   HOST arrays of n_layers device pointers: layer first_layer+l is assembled
+ *                         into out_K[l], out_V[l], out_pos[l], each laid out like the buffers of
+ *                         pc_assemble_kv_batched (same kv_offsets for every layer), 16-byte aligned.
+ * The other arguments, the result per layer and the errors are those of pc_assemble_kv_batched;
+ * PC_E_LAYER if the layer range leaves [0, n_layers).  Every layer is validated before the first
+ * launch: on error nothing has been enqueued.
+ */
+int pc_assemble_kv_layers(pc_ctx *ctx, int first_layer, int n_layers, const int *module_ids_flat,
+                          const int *mod_offsets, int n_prompts, void *const *out_K, void *const *out_V,
+                          int32_t *const *out_pos, const int *kv_offsets, int *out_n_tokens,
+                          void *stream);
+
 /* Batched pc_append_kv.  Prompt b's new tokens are rows q_offsets[b] .. q_offsets[b+1]-1
  * of K_new_raw/V_new/q_pos and go to rows kv_offsets[b]+kv_lens[b] ... of the packed
  * buffer; they must fit below kv_offsets[b+1].  All offset arrays are host. */
@@ -467,6 +488,16 @@ int pc_module_info(const pc_ctx *ctx, int layer, int module_id, int *n_tokens, i
  */
 int pc_calib_copy(pc_ctx *ctx, size_t bytes, int repeats, double *gb_per_s);
 int pc_calib_mfma(pc_ctx *ctx, int iters, double *tflop_per_s);
+
+/*
+ * Sec. 3.4 (a prompt's imports are validated and its modules retrieved once): every call that takes
+ * import lists keeps the validated plan of its last few distinct lists, so the same lists at the next
+ * layer or the next step cost an integer comparison: no look-up, no sort, no host allocation.
+ * Storing a new module or defining a scaffold discards the kept plans.
+ * pc_plan_stats (for tests and benchmarks): calls served from a kept plan, calls that had to plan, and
+ * the number of host heap allocations the planning code has made so far on the calling thread.
+ */
+int pc_plan_stats(const pc_ctx *ctx, long *hits, long *misses, long *heap_allocs);
 
 /* Bytes of pool in use / total. */
 int pc_pool_usage(const pc_ctx *ctx, size_t *used, size_t *total);

@@ -28,7 +28,7 @@ EXPORTS = [
     "pc_host_pool_reserve", "pc_store_module_host", "pc_set_host_copy_mode", "pc_set_attn_kernel", "pc_set_alibi", "pc_alibi_slopes",
     "pc_define_scaffold", "pc_resolve_scaffolds", "pc_calib_copy", "pc_calib_mfma",
     "pc_append_rotate_batched", "pc_assemble_append_rotate_batched", "pc_prefill_attn_rotated_batched",
-    "pc_prefill_attn_shared_rotated_batched", "pc_prefill_attn_static",
+    "pc_prefill_attn_shared_rotated_batched", "pc_prefill_attn_static", "pc_assemble_kv_layers", "pc_plan_stats",
 ]
 PC_STATIC_SCRATCH_BYTES = 32 << 20
 PROF_GATHER, PROF_APPEND, PROF_ATTN, PROF_COMBINE, PROF_ROPE = range(5)
@@ -75,6 +75,8 @@ def lib() -> ctypes.CDLL:
     L.pc_rope.argtypes = [vp, vp, i, i, vp, vp]
     L.pc_append_kv.argtypes = [vp, i, vp, vp, vp, i, vp, vp, vp, i, i, vp]
     L.pc_assemble_kv_batched.argtypes = [vp, i, vp, vp, i, vp, vp, vp, vp, vp, vp]
+    L.pc_assemble_kv_layers.argtypes = [vp, i, i, vp, vp, i, vp, vp, vp, vp, vp, vp]
+    L.pc_plan_stats.argtypes = [vp, ctypes.POINTER(ctypes.c_long), ctypes.POINTER(ctypes.c_long), ctypes.POINTER(ctypes.c_long)]
     L.pc_append_kv_batched.argtypes = [vp, i, vp, vp, vp, vp, i, vp, vp, vp, vp, vp, vp]
     L.pc_assemble_append_kv_batched.argtypes = [vp, i, vp, vp, i, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     L.pc_prefill_attn_batched.argtypes = [vp, i, vp, vp, vp, i, vp, vp, vp, vp, vp, vp, vp]
@@ -276,6 +278,21 @@ class PromptCache:
                "pc_assemble_kv_batched")
         return [int(x) for x in n_out[:B]]
 
+    def pc_assemble_kv_layers(self, first_layer: int, module_ids: Sequence[Sequence[int]], out_K: Sequence, out_V: Sequence,
+                              out_pos: Sequence, kv_offsets: Sequence[int], stream=None) -> List[int]:
+        """out_K/out_V/out_pos: one device tensor per layer, layers first_layer .. first_layer+len(out_K)-1."""
+        flat = _ints([m for ids in module_ids for m in ids])
+        offs = _ints(np.concatenate([[0], np.cumsum([len(ids) for ids in module_ids])]))
+        kvo = _ints(kv_offsets)
+        B, L = len(module_ids), len(out_K)
+        assert len(kvo) == B + 1 and len(out_V) == L and len(out_pos) == L
+        ptrs = [(ctypes.c_void_p * max(L, 1))(*[_dev(t) for t in ts]) for ts in (out_K, out_V, out_pos)]
+        n_out = np.zeros(max(B, 1), dtype=np.intc)
+        _check(lib().pc_assemble_kv_layers(self._ctx, first_layer, L, _np_ptr(flat), _np_ptr(offs), B, ptrs[0], ptrs[1],
+                                           ptrs[2], _np_ptr(kvo), _np_ptr(n_out), _stream(stream)),
+               "pc_assemble_kv_layers")
+        return [int(x) for x in n_out[:B]]
+
     def pc_append_kv_batched(self, layer: int, K_new_raw, V_new, q_pos, q_offsets: Sequence[int], asm_K, asm_V,
                              asm_pos, kv_offsets: Sequence[int], kv_lens: Sequence[int], stream=None) -> None:
         qo, kvo, kvl = _ints(q_offsets), _ints(kv_offsets), _ints(kv_lens)
@@ -425,6 +442,12 @@ class PromptCache:
         n, s = ctypes.c_int(0), ctypes.c_int(0)
         _check(lib().pc_module_info(self._ctx, layer, module_id, ctypes.byref(n), ctypes.byref(s)), "pc_module_info")
         return n.value, s.value
+
+    def pc_plan_stats(self) -> Tuple[int, int, int]:
+        """(calls served from a kept plan, calls that planned, host heap allocations of the planning code so far)."""
+        h, m, a = ctypes.c_long(0), ctypes.c_long(0), ctypes.c_long(0)
+        _check(lib().pc_plan_stats(self._ctx, ctypes.byref(h), ctypes.byref(m), ctypes.byref(a)), "pc_plan_stats")
+        return h.value, m.value, a.value
 
     def pc_pool_usage(self) -> Tuple[int, int]:
         u, t = ctypes.c_size_t(0), ctypes.c_size_t(0)

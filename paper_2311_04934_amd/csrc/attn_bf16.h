@@ -23,26 +23,33 @@ constexpr int kPosInf = 0x7fffffff;
 // rarely; probabilities then range up to 2^kMaxSlack, which bf16 and fp32 hold without loss.
 constexpr float kMaxSlack = 8.0f;
 
+// Kernel argument of both bf16 kernels.  The fields a workgroup needs first come first, and the first prompt is
+// repeated ahead of the table (seq0), so that a call with one prompt finds its work unit with the first look at
+// the arguments instead of a second, dependent one.
 struct AttnParams {
+    int Hq, Hkv, G;
+    int n_splits;
+    int rb_max;              // row blocks per (prompt, kv head)
+    int n_groups;            // n_seqs * n_splits * Hkv
+    int n_seqs;
+    AttnSeq seq0;            // = batch.seq[0]
+    int q_rotated;           // Q comes rotated and scaled (log2(e)/sqrt(D)) already: its bf16 values are the operand
+    int max_pos;
+    int total_q;
+    float q_scale;           // log2(e) / sqrt(D)
     const uint16_t *q;       // [total_q][Hq][D] bf16 bits
     const int32_t *q_pos;
     const uint16_t *k;       // [total_kv][Hkv][D]
     const uint16_t *v;
     const int32_t *kv_pos;
     uint16_t *out;           // [total_q][Hq][D]
-    uint16_t *part_o;        // bf16 [n_splits][total_q][Hq][D]: un-normalised partial O of every KV split
-    float2 *part_ml;         // [n_splits][total_q][Hq]
+    // Un-normalised partial O (bf16) and (m, l) of every KV split: [n_splits][total_q][Hq] rows in the register-staged
+    // kernel, [n_splits][Hq][total_q] rows in the DMA-staged one.
+    uint16_t *part_o;
+    float2 *part_ml;
     const float2 *rope;      // [max_pos][D/2]
     const float2 *rope_t;    // [D/2][max_pos]
     const float *alibi;      // [Hq] slopes of the linear bias, or nullptr: rotation
-    int q_rotated;           // Q comes rotated and scaled (log2(e)/sqrt(D)) already: its bf16 values are the operand
-    int max_pos;
-    int Hq, Hkv, G;
-    int n_splits;
-    int rb_max;              // row blocks per (prompt, kv head)
-    int n_groups;            // n_seqs * n_splits * Hkv
-    int total_q;
-    float q_scale;           // log2(e) / sqrt(D)
     AttnBatch batch;
 };
 

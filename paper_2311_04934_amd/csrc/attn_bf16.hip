@@ -113,7 +113,8 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p,
     const int kvh = g % p.Hkv;
     const int split = (g / p.Hkv) % p.n_splits;
     const int seq_i = g / (p.Hkv * p.n_splits);
-    const AttnSeq seq = p.batch.seq[seq_i];
+    AttnSeq seq = p.seq0;
+    if (p.n_seqs > 1) seq = p.batch.seq[seq_i];
 
     const int tiles_q = (seq.n_q + RW - 1) / RW;
     const int row_tiles = p.G * tiles_q;
@@ -430,11 +431,12 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_kernel(const AttnParams p,
 
 // Merge the split-KV partials: out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.  The partial O_s are
 // stored in bf16 (they are rounded to bf16 at the output anyway, and the merge is a convex
-// combination); m_s and l_s are fp32.  One thread owns 8 elements of a row.
-template <int D>
+// combination); m_s and l_s are fp32.  One thread owns 8 elements of a row.  HEAD_MAJOR: the partials of a split
+// are [Hq][total_q] rows (the DMA-staged kernel's), else [total_q][Hq] like the output.
+template <int D, bool HEAD_MAJOR>
 __global__ __launch_bounds__(256) void attn_combine_kernel(const uint16_t *part_o, const float2 *part_ml, uint16_t *out,
                                                            int n_splits, long n_rows /* total_q * Hq */,
-                                                           long row_lo, long row_hi /* rows this launch owns */)
+                                                           long row_lo, long row_hi /* rows this launch owns */, int Hq)
 {
     constexpr int CH = D / 8;  // 8-element chunks per row
     constexpr int U = 8;       // splits fetched together: all their loads are in flight at once
@@ -442,6 +444,7 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const uint16_t *part_
     if (idx >= (row_hi - row_lo) * CH) return;
     const long row = row_lo + idx / CH;
     const int ch = (int)(idx % CH);
+    const long prow = HEAD_MAJOR ? (row % Hq) * (n_rows / Hq) + row / Hq : row;   // row of one split's partials
     float M = -INFINITY, Lsum = 0.f;
     float acc[8];
 #pragma unroll
@@ -452,8 +455,8 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const uint16_t *part_
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int s = s0 + u < n_splits ? s0 + u : n_splits - 1;   // clamped: a repeated split gets weight 0 below
-            ml[u] = part_ml[(size_t)s * n_rows + row];
-            o[u] = *reinterpret_cast<const u32x4 *>(part_o + ((size_t)s * n_rows + row) * D + ch * 8);
+            ml[u] = part_ml[(size_t)s * n_rows + prow];
+            o[u] = *reinterpret_cast<const u32x4 *>(part_o + ((size_t)s * n_rows + prow) * D + ch * 8);
         }
         float Mg = M;
 #pragma unroll
@@ -580,6 +583,8 @@ int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const i
     p.total_q = total_q;
     p.q_scale = 1.4426950408889634f / sqrtf((float)D);
     p.batch = batch;
+    p.n_seqs = batch.n_seqs;
+    p.seq0 = p.batch.seq[0];
 
     const int n_blocks = 8 * ((p.n_groups + 7) / 8) * rb_max;
     int rc;
@@ -604,12 +609,15 @@ int launch_attn_bf16(pc_ctx *ctx, const AttnBatch &batch, const void *q, const i
         const int blocks = (int)((n_thr + 255) / 256);
         const uint16_t *po = p.part_o;
         const float2 *pml = p.part_ml;
-        if (D == 128)
-            rc = launch_kernel(ctx, kProfCombine, attn_combine_kernel<128>, dim3(blocks), dim3(256), 0, stream, po, pml,
-                               p.out, n_splits, n_rows, row_lo, n_rows);
+        if (wide)
+            rc = launch_kernel(ctx, kProfCombine, attn_combine_kernel<128, true>, dim3(blocks), dim3(256), 0, stream, po, pml,
+                               p.out, n_splits, n_rows, row_lo, n_rows, Hq);
+        else if (D == 128)
+            rc = launch_kernel(ctx, kProfCombine, attn_combine_kernel<128, false>, dim3(blocks), dim3(256), 0, stream, po, pml,
+                               p.out, n_splits, n_rows, row_lo, n_rows, Hq);
         else
-            rc = launch_kernel(ctx, kProfCombine, attn_combine_kernel<64>, dim3(blocks), dim3(256), 0, stream, po, pml,
-                               p.out, n_splits, n_rows, row_lo, n_rows);
+            rc = launch_kernel(ctx, kProfCombine, attn_combine_kernel<64, false>, dim3(blocks), dim3(256), 0, stream, po, pml,
+                               p.out, n_splits, n_rows, row_lo, n_rows, Hq);
     }
     ctx->last_attn.n_splits = n_splits;
     ctx->last_attn.n_workgroups = n_blocks;

@@ -30,6 +30,54 @@ struct Scaffold {
     std::vector<int> member, override_id;
 };
 
+// Heap allocations made by the request path's planning code are counted (pc_plan_stats), so that a test can show
+// that a call whose plan is cached makes none.
+extern thread_local long g_plan_heap_allocs;
+template <typename T>
+struct CountingAlloc {
+    using value_type = T;
+    CountingAlloc() = default;
+    template <typename U>
+    CountingAlloc(const CountingAlloc<U> &) {}
+    T *allocate(size_t n)
+    {
+        ++g_plan_heap_allocs;
+        return static_cast<T *>(::operator new(n * sizeof(T)));
+    }
+    void deallocate(T *p, size_t) { ::operator delete(p); }
+    template <typename U>
+    bool operator==(const CountingAlloc<U> &) const { return true; }
+    template <typename U>
+    bool operator!=(const CountingAlloc<U> &) const { return false; }
+};
+template <typename T>
+using cvec = std::vector<T, CountingAlloc<T>>;
+
+// The validated import lists of one call (Sec. 3.4: a prompt's imports are checked against the schema and its
+// modules retrieved once per prompt, not once per layer).  Everything in it is independent of the layer:
+// which stored states each prompt concatenates, in which order, how many rows, at which position IDs.
+// Per layer only the modules' addresses differ; they are looked up for every layer when the plan is made.
+struct PlanItem {
+    int prompt;      // index of the prompt in the call
+    int module_id;   // after scaffold overrides
+    int n_rows;      // > 0 (modules without tokens are dropped)
+    int start_pos;
+    int row;         // first row inside the prompt's span
+};
+struct Plan {
+    // key
+    cvec<int> ids, mod_offsets;
+    unsigned long generation = 0;   // of the context's module tables and scaffolds when the plan was made
+    // value
+    cvec<PlanItem> items;
+    cvec<int> prompt_rows;                      // module rows per prompt
+    cvec<const ModuleEntry *> entry;            // [layer][item]
+    cvec<unsigned char> layer_ok;               // the layer holds every item with the plan's length and first position
+    unsigned long last_use = 0;
+    bool valid = false;
+};
+constexpr int kPlanCacheSize = 8;
+
 // A parameter of a module (Sec. 3.2.2): rows [offset, offset+len) of the module hold placeholder states.
 struct ParamSlot {
     int offset;
@@ -69,6 +117,9 @@ struct pc_ctx {
     std::vector<std::unordered_map<int, pc::ModuleEntry>> modules;  // per layer
     std::unordered_map<int, std::vector<pc::ParamSlot>> params;     // per module id (schema level, all layers)
     std::vector<pc::Scaffold> scaffolds;                            // in definition order (schema level)
+    unsigned long generation = 1;   // bumped by every change of the tables above that can change a plan
+    pc::Plan plans[pc::kPlanCacheSize];
+    unsigned long plan_clock = 0, plan_hits = 0, plan_misses = 0;
 
     float2 *rope_table = nullptr;  // device, [max_pos][head_dim/2] (cos, sin)
     int32_t *iota = nullptr;  // device, 0, 1, .. max_pos-1: position IDs of module rows read in place
@@ -112,6 +163,21 @@ struct GatherArgs {
 
 int launch_gather(pc_ctx *ctx, const GatherArgs &args, uint8_t *out_k, uint8_t *out_v, int32_t *out_pos,
                   hipStream_t stream);
+
+// The imported modules of several layers in one launch: every segment names the layer whose packed buffers it
+// is copied into (the modules do not depend on the forward pass, Sec. 3.4, so all layers' copies can be made at
+// the start of a request).
+constexpr int kMaxGatherLayers = 32;
+struct GatherLayerOut {
+    uint8_t *k, *v;
+    int32_t *pos;
+};
+struct GatherLayersArgs {
+    GatherArgs g;
+    unsigned char seg_layer[kMaxGatherSegs];   // index into out[]
+    GatherLayerOut out[kMaxGatherLayers];
+};
+int launch_gather_layers(pc_ctx *ctx, const GatherLayersArgs &args, hipStream_t stream);
 
 // ---- RoPE / append -----------------------------------------------------------
 int launch_rope(pc_ctx *ctx, void *x, int n_tokens, int n_heads, const int32_t *pos, hipStream_t stream);

@@ -22,6 +22,15 @@ __global__ __launch_bounds__(kv::kThreads) void gather_kv_kernel(const GatherArg
     kv::gather_tile(a, blockIdx.x, out_k, out_v, out_pos);
 }
 
+// The same gather over the modules of several layers: a segment's tiles go to the packed buffers of its layer.
+__global__ __launch_bounds__(kv::kThreads) void gather_layers_kernel(const GatherLayersArgs a)
+{
+    const int si = kv::gather_segment(a.g, blockIdx.x);
+    const GatherSeg sg = a.g.seg[si];
+    const GatherLayerOut o = a.out[a.seg_layer[si]];
+    kv::gather_tile_of(a.g, sg, blockIdx.x, o.k, o.v, o.pos);
+}
+
 // Assembly and append in one launch: workgroups [0, total_tiles) gather module rows, the rest append
 // one uncached token's row each.  (Every workgroup of such a launch is resident at once; the append
 // rows, a chain of dependent loads, run fastest at the end of the grid, when the copy stream drains.)  The two write disjoint rows of the same packed buffers, and a kernel
@@ -50,6 +59,12 @@ int launch_gather(pc_ctx *ctx, const GatherArgs &args, uint8_t *out_k, uint8_t *
     if (args.total_tiles <= 0) return PC_OK;
     return launch_kernel(ctx, kProfGather, gather_kv_kernel, dim3(args.total_tiles), dim3(kv::kThreads), 0, stream,
                          args, out_k, out_v, out_pos);
+}
+
+int launch_gather_layers(pc_ctx *ctx, const GatherLayersArgs &args, hipStream_t stream)
+{
+    if (args.g.total_tiles <= 0) return PC_OK;
+    return launch_kernel(ctx, kProfGather, gather_layers_kernel, dim3(args.g.total_tiles), dim3(kv::kThreads), 0, stream, args);
 }
 
 int launch_gather_append(pc_ctx *ctx, const FusedKvArgs &args, uint8_t *out_k, uint8_t *out_v, int32_t *out_pos,

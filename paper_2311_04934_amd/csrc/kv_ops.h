@@ -26,18 +26,33 @@ struct Elem<uint16_t> {  // bf16 bits
 
 __device__ __forceinline__ int clamp_pos(int pos, int max_pos) { return pos < 0 ? 0 : (pos >= max_pos ? max_pos - 1 : pos); }
 
-// Tile `tile` of the gather's flat work list: rows of one module copied verbatim, plus their position IDs.
-__device__ __forceinline__ void gather_tile(const GatherArgs &a, int tile, uint8_t *__restrict__ out_k,
-                                            uint8_t *__restrict__ out_v, int32_t *__restrict__ out_pos)
+// Segment that holds `tile` of the gather's flat work list: the last one whose first_tile <= tile (uniform
+// across the workgroup).
+__device__ __forceinline__ int gather_segment(const GatherArgs &a, int tile)
 {
-    // segment lookup: last segment whose first_tile <= tile (uniform across the workgroup)
     int lo = 0, hi = a.n_segs - 1;
     while (lo < hi) {
         const int mid = (lo + hi + 1) >> 1;
         if (a.seg[mid].first_tile <= tile) lo = mid;
         else hi = mid - 1;
     }
-    const GatherSeg sg = a.seg[lo];
+    return lo;
+}
+
+__device__ __forceinline__ void gather_tile_of(const GatherArgs &a, const GatherSeg &sg, int tile, uint8_t *__restrict__ out_k,
+                                               uint8_t *__restrict__ out_v, int32_t *__restrict__ out_pos);
+
+// Tile `tile` of the gather's flat work list: rows of one module copied verbatim, plus their position IDs.
+__device__ __forceinline__ void gather_tile(const GatherArgs &a, int tile, uint8_t *__restrict__ out_k,
+                                            uint8_t *__restrict__ out_v, int32_t *__restrict__ out_pos)
+{
+    const GatherSeg sg = a.seg[gather_segment(a, tile)];
+    gather_tile_of(a, sg, tile, out_k, out_v, out_pos);
+}
+
+__device__ __forceinline__ void gather_tile_of(const GatherArgs &a, const GatherSeg &sg, int tile, uint8_t *__restrict__ out_k,
+                                               uint8_t *__restrict__ out_v, int32_t *__restrict__ out_pos)
+{
     if (sg.src_k == nullptr) {   // rows copied by the copy engine: position IDs only, in larger tiles
         const int rpt = a.rows_per_tile * kPosOnlyTileFactor;
         const int p0 = (tile - sg.first_tile) * rpt;

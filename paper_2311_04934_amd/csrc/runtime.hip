@@ -14,6 +14,8 @@
 
 using namespace pc;
 
+thread_local long pc::g_plan_heap_allocs = 0;
+
 static __device__ __align__(256) uint8_t scratch[PC_STATIC_SCRATCH_BYTES];
 
 namespace {
@@ -55,7 +57,7 @@ int validate_config(const pc_config *c)
 int check_ranges(int n, const int *starts, const int *lens, int max_pos)
 {
     if (n < 0 || (n > 0 && (!starts || !lens))) return PC_E_BADARG;
-    std::vector<std::pair<long, long>> iv;
+    cvec<std::pair<long, long>> iv;
     iv.reserve(n);
     for (int i = 0; i < n; ++i) {
         if (lens[i] < 0 || starts[i] < 0) return PC_E_BADARG;
@@ -71,12 +73,13 @@ int check_ranges(int n, const int *starts, const int *lens, int max_pos)
 // Scaffolding (Sec. 3.3): replace, in place, the ids of every scaffold whose members are all in the list by
 // the ids of its jointly encoded states.  Scaffolds are taken in definition order; one that would touch a
 // member an earlier scaffold has overridden is skipped.
-void apply_scaffolds(const std::vector<Scaffold> &scaffolds, std::vector<int> &ids, std::vector<int> *replaced_from = nullptr)
+void apply_scaffolds(const std::vector<Scaffold> &scaffolds, cvec<int> &ids, cvec<int> *replaced_from = nullptr)
 {
+    if (replaced_from) *replaced_from = ids;
     if (scaffolds.empty() || ids.empty()) return;
-    const std::vector<int> imported(ids);
-    std::vector<int> taken;
-    auto has = [](const std::vector<int> &v, int x) { return std::find(v.begin(), v.end(), x) != v.end(); };
+    const cvec<int> imported(ids);
+    cvec<int> taken;
+    auto has = [](const cvec<int> &v, int x) { return std::find(v.begin(), v.end(), x) != v.end(); };
     for (const Scaffold &sc : scaffolds) {
         bool complete = true;
         for (int m : sc.member) complete = complete && has(imported, m) && !has(taken, m);
@@ -87,92 +90,155 @@ void apply_scaffolds(const std::vector<Scaffold> &scaffolds, std::vector<int> &i
             taken.push_back(sc.member[i]);
         }
     }
-    if (replaced_from) *replaced_from = imported;
 }
 
-// A prompt's import list with scaffolds applied; the override states must mirror their member
-// (same length, same first position ID), which is checked against the member when it is stored too.
-int resolve_imports(const pc_ctx *ctx, int layer, const int *ids, int n, std::vector<int> &out)
-{
-    out.assign(ids, ids + n);
-    if (ctx->scaffolds.empty()) return PC_OK;
-    std::vector<int> from;
-    apply_scaffolds(ctx->scaffolds, out, &from);
-    const auto &table = ctx->modules[layer];
-    for (int i = 0; i < n; ++i) {
-        if (out[i] == from[i]) continue;
-        auto o = table.find(out[i]);
-        if (o == table.end()) return PC_E_UNKNOWN_MODULE;
-        auto m = table.find(from[i]);
-        if (m != table.end() && (m->second.n_tokens != o->second.n_tokens || m->second.start_pos != o->second.start_pos))
-            return PC_E_SCHEMA;
-    }
-    return PC_OK;
-}
+// ---- request planning (Sec. 3.4: the imports of a prompt are validated and its modules retrieved once) --------
+//
+// make_plan does the whole validation of a call's import lists against the module table of one layer: scaffold
+// overrides, look-up of every id, position ranges of a prompt's modules disjoint, rows fit the prompt's span.
+// Its result does not depend on the layer as long as the layer stores the same modules with the same lengths
+// and first position IDs, which mark_layers establishes for every layer at once.  get_plan keeps the last few
+// plans: a call with the import lists of an earlier one (the next layer of the same prompt, the next step of a
+// serving loop) compares integers and allocates nothing.
 
-// Resolve one prompt's imports into gather segments appended to `segs`.
-// dst_row0: first output row of this prompt; capacity: rows available to it.
-int plan_prompt(const pc_ctx *ctx, int layer, const int *ids, int n, int dst_row0, int capacity,
-                std::vector<GatherSeg> &segs, int *n_rows_out)
+const ModuleEntry *find_module(const pc_ctx *ctx, int layer, int id)
 {
     const auto &table = ctx->modules[layer];
-    std::vector<int> resolved;
-    int rrc = resolve_imports(ctx, layer, ids, n, resolved);
-    if (rrc != PC_OK) return rrc;
-    ids = resolved.data();
-    std::vector<int> starts(n), lens(n);
-    long rows = 0;
-    for (int i = 0; i < n; ++i) {
-        auto it = table.find(ids[i]);
-        if (it == table.end()) return PC_E_UNKNOWN_MODULE;
-        starts[i] = it->second.start_pos;
-        lens[i] = it->second.n_tokens;
-        rows += lens[i];
-    }
-    int rc = check_ranges(n, starts.data(), lens.data(), ctx->cfg.max_pos);
-    if (rc != PC_OK) return rc;
-    if (rows > capacity) return PC_E_CAPACITY;
-    int row = dst_row0;
-    for (int i = 0; i < n; ++i) {
-        const ModuleEntry &m = table.find(ids[i])->second;
-        if (m.n_tokens == 0) continue;
-        GatherSeg s;
-        s.src_k = (m.host ? ctx->host_pool : ctx->pool) + m.k_offset;
-        s.src_v = (m.host ? ctx->host_pool : ctx->pool) + m.v_offset;
-        s.dst_row = row;
-        s.n_rows = m.n_tokens;
-        s.start_pos = m.start_pos;
-        s.first_tile = 0;
-        segs.push_back(s);
-        row += m.n_tokens;
-    }
-    *n_rows_out = (int)rows;
-    return PC_OK;
+    auto it = table.find(id);
+    return it == table.end() ? nullptr : &it->second;
 }
 
-bool in_host_pool(const pc_ctx *ctx, const uint8_t *p)
+// Rows available to prompt b: kv_offsets[b+1] - kv_offsets[b], of which its q_offsets[b+1] - q_offsets[b] uncached
+// tokens need their share (q_offsets == nullptr: none; kv_offsets == nullptr: capacity not checked here).
+long rows_available(const int *kv_offsets, const int *q_offsets, int b)
 {
-    return ctx->host_pool && p >= ctx->host_pool && p < ctx->host_pool + ctx->host_pool_bytes;
+    return (long)kv_offsets[b + 1] - kv_offsets[b] - (q_offsets ? (long)q_offsets[b + 1] - q_offsets[b] : 0L);
 }
 
-// Host-resident modules under PC_HOST_COPY_ENGINE: one transfer per module and tensor on the caller's
-// stream, straight into the packed buffer (a module's rows are contiguous on both sides); the segment
-// is then left to the kernel for its position IDs only.
-int copy_host_segments(pc_ctx *ctx, std::vector<GatherSeg> &segs, void *out_K, void *out_V, hipStream_t stream)
+int make_plan(const pc_ctx *ctx, int layer, const int *ids_flat, const int *mod_offsets, int n_prompts,
+              const int *kv_offsets, const int *q_offsets, Plan &p, cvec<int> &member_of)
 {
-    if (ctx->host_copy_mode != PC_HOST_COPY_ENGINE) return PC_OK;
-    for (GatherSeg &sg : segs) {
-        if (!in_host_pool(ctx, sg.src_k)) continue;
-        const size_t bytes = (size_t)sg.n_rows * ctx->row_bytes, dst = (size_t)sg.dst_row * ctx->row_bytes;
-        if (hipMemcpyAsync(static_cast<uint8_t *>(out_K) + dst, sg.src_k, bytes, hipMemcpyHostToDevice, stream) != hipSuccess ||
-            hipMemcpyAsync(static_cast<uint8_t *>(out_V) + dst, sg.src_v, bytes, hipMemcpyHostToDevice, stream) != hipSuccess) {
-            (void)hipGetLastError();
-            return PC_E_HIP;
+    p.valid = false;
+    p.items.clear();
+    p.prompt_rows.assign(n_prompts, 0);
+    member_of.clear();
+    cvec<int> resolved, from, starts, lens;
+    for (int b = 0; b < n_prompts; ++b) {
+        const int n = mod_offsets[b + 1] - mod_offsets[b];
+        const int *ids = n > 0 ? ids_flat + mod_offsets[b] : nullptr;
+        resolved.assign(ids, ids + n);
+        apply_scaffolds(ctx->scaffolds, resolved, &from);
+        for (int i = 0; i < n; ++i) {   // an override must mirror its member (same length, same first position ID)
+            if (resolved[i] == from[i]) continue;
+            const ModuleEntry *o = find_module(ctx, layer, resolved[i]);
+            if (!o) return PC_E_UNKNOWN_MODULE;
+            const ModuleEntry *m = find_module(ctx, layer, from[i]);
+            if (m && (m->n_tokens != o->n_tokens || m->start_pos != o->start_pos)) return PC_E_SCHEMA;
         }
-        sg.src_k = sg.src_v = nullptr;
+        starts.resize(n);
+        lens.resize(n);
+        long rows = 0;
+        for (int i = 0; i < n; ++i) {
+            const ModuleEntry *m = find_module(ctx, layer, resolved[i]);
+            if (!m) return PC_E_UNKNOWN_MODULE;
+            starts[i] = m->start_pos;
+            lens[i] = m->n_tokens;
+            rows += lens[i];
+        }
+        int rc = check_ranges(n, starts.data(), lens.data(), ctx->cfg.max_pos);
+        if (rc != PC_OK) return rc;
+        if (rows > 0x7fffffffL || (kv_offsets && rows > rows_available(kv_offsets, q_offsets, b))) return PC_E_CAPACITY;
+        int row = 0;
+        for (int i = 0; i < n; ++i) {
+            p.items.push_back(PlanItem{b, resolved[i], lens[i], starts[i], row});
+            member_of.push_back(from[i]);
+            row += lens[i];
+        }
+        p.prompt_rows[b] = (int)rows;
     }
     return PC_OK;
 }
+
+// For every layer: the addresses of the plan's modules there, and whether the layer agrees with the plan
+// (every module stored, same length and first position ID, overrides mirroring their members).
+void mark_layers(const pc_ctx *ctx, Plan &p, const cvec<int> &member_of)
+{
+    const int L = ctx->cfg.n_layers;
+    const size_t n = p.items.size();
+    p.entry.assign((size_t)L * n, nullptr);
+    p.layer_ok.assign(L, 1);
+    for (int layer = 0; layer < L; ++layer)
+        for (size_t i = 0; i < n; ++i) {
+            const PlanItem &it = p.items[i];
+            const ModuleEntry *m = find_module(ctx, layer, it.module_id);
+            bool ok = m && m->n_tokens == it.n_rows && m->start_pos == it.start_pos;
+            if (ok && member_of[i] != it.module_id) {
+                const ModuleEntry *mem = find_module(ctx, layer, member_of[i]);
+                ok = !mem || (mem->n_tokens == it.n_rows && mem->start_pos == it.start_pos);
+            }
+            p.entry[(size_t)layer * n + i] = m;
+            if (!ok) p.layer_ok[layer] = 0;
+        }
+}
+
+struct PlanRef {
+    const Plan *plan = nullptr;
+    const ModuleEntry *const *entry = nullptr;   // this layer's modules, one per plan item
+};
+
+// The plan for these import lists at this layer: from the cache, or made now (and cached).  Errors are those of
+// make_plan.
+int get_plan(pc_ctx *ctx, int layer, const int *ids_flat, const int *mod_offsets, int n_prompts, const int *kv_offsets,
+             const int *q_offsets, PlanRef &out)
+{
+    const int n_ids = mod_offsets[n_prompts] - mod_offsets[0];
+    for (int b = 0; b < n_prompts; ++b)
+        if (mod_offsets[b + 1] < mod_offsets[b]) return PC_E_BADARG;
+    if (n_ids > 0 && !ids_flat) return PC_E_BADARG;
+    Plan *hit = nullptr;
+    for (Plan &p : ctx->plans) {
+        if (!p.valid || p.generation != ctx->generation || (int)p.mod_offsets.size() != n_prompts + 1 ||
+            (int)p.ids.size() != n_ids || !p.layer_ok[layer])
+            continue;
+        bool same = true;
+        for (int b = 0; b <= n_prompts && same; ++b) same = p.mod_offsets[b] == mod_offsets[b] - mod_offsets[0];
+        if (same && (n_ids == 0 || memcmp(p.ids.data(), ids_flat + mod_offsets[0], (size_t)n_ids * sizeof(int)) == 0)) {
+            hit = &p;
+            break;
+        }
+    }
+    if (hit) {
+        if (kv_offsets)
+            for (int b = 0; b < n_prompts; ++b)
+                if (hit->prompt_rows[b] > rows_available(kv_offsets, q_offsets, b)) return PC_E_CAPACITY;
+        ++ctx->plan_hits;
+    } else {
+        ++ctx->plan_misses;
+        Plan *victim = &ctx->plans[0];
+        for (Plan &p : ctx->plans) {
+            if (!p.valid) { victim = &p; break; }
+            if (p.last_use < victim->last_use) victim = &p;
+        }
+        cvec<int> member_of;
+        int rc = make_plan(ctx, layer, ids_flat, mod_offsets, n_prompts, kv_offsets, q_offsets, *victim, member_of);
+        if (rc != PC_OK) return rc;
+        victim->ids.assign(ids_flat + (n_ids ? mod_offsets[0] : 0), ids_flat + (n_ids ? mod_offsets[0] : 0) + n_ids);
+        victim->mod_offsets.resize(n_prompts + 1);
+        for (int b = 0; b <= n_prompts; ++b) victim->mod_offsets[b] = mod_offsets[b] - mod_offsets[0];
+        victim->generation = ctx->generation;
+        mark_layers(ctx, *victim, member_of);
+        victim->valid = true;
+        hit = victim;
+    }
+    hit->last_use = ++ctx->plan_clock;
+    out.plan = hit;
+    out.entry = hit->entry.data() + (size_t)layer * hit->items.size();
+    return PC_OK;
+}
+
+// A host-resident module under PC_HOST_COPY_ENGINE is brought in by copy-engine transfers; the kernel then
+// writes its rows' position IDs only.
+bool by_copy_engine(const pc_ctx *ctx, const ModuleEntry *m) { return m->host && ctx->host_copy_mode == PC_HOST_COPY_ENGINE; }
 
 // Rows per gather tile.  A workgroup moves up to 32 KiB of K and 32 KiB of V in one pass (512 lanes x 4 x 16
 // bytes, all loads issued before the first store).  Measured: a launch takes about as long as its busiest CU,
@@ -181,19 +247,20 @@ int copy_host_segments(pc_ctx *ctx, std::vector<GatherSeg> &segs, void *out_K, v
 // used where they make ceil(workgroups / CUs) x tile bytes smaller than 32 KiB tiles do, and 16 KiB tiles only
 // for launches that would otherwise leave CUs without a workgroup (smaller tiles cost more per byte).
 // `extra_wgs` are the workgroups the same launch runs for appended rows.  Launches of hundreds of megabytes
-// run ~6 % faster with two passes per workgroup.
-int gather_rows_per_tile(const pc_ctx *ctx, const std::vector<GatherSeg> &segs, long extra_wgs = 0)
+// run ~6 % faster with two passes per workgroup.  `n_layers` layers' modules go into the launch.
+int gather_rows_per_tile(const pc_ctx *ctx, const PlanRef &pr, long extra_wgs = 0, int n_layers = 1)
 {
+    const size_t n = pr.plan->items.size();
     size_t rows = 0;
-    for (const GatherSeg &sg : segs) rows += (size_t)sg.n_rows;
+    for (const PlanItem &it : pr.plan->items) rows += (size_t)it.n_rows;
     const size_t rb = ctx->row_bytes;
-    if (rows * rb > ((size_t)128 << 20)) return std::max(1, (int)(65536 / rb));
+    if (rows * n_layers * rb > ((size_t)128 << 20)) return std::max(1, (int)(65536 / rb));
     const long n_cu = ctx->n_cu > 0 ? ctx->n_cu : 256;
     auto tiles_with = [&](int rpt) {
         long tiles = 0;
-        for (const GatherSeg &sg : segs)
-            if (sg.src_k) tiles += (sg.n_rows + rpt - 1) / rpt;
-        return tiles;
+        for (size_t i = 0; i < n; ++i)
+            if (pr.plan->items[i].n_rows > 0 && !by_copy_engine(ctx, pr.entry[i])) tiles += (pr.plan->items[i].n_rows + rpt - 1) / rpt;
+        return tiles * n_layers;
     };
     const int r32 = std::max(1, (int)(32768 / rb)), r24 = std::max(1, (int)(24576 / rb)), r16 = std::max(1, (int)(16384 / rb));
     if (tiles_with(r24) + extra_wgs < n_cu) return r16;
@@ -208,28 +275,69 @@ int tiles_of(const GatherSeg &sg, int rows_per_tile)
     return (sg.n_rows + rpt - 1) / rpt;
 }
 
-int run_gather(pc_ctx *ctx, std::vector<GatherSeg> &segs, void *out_K, void *out_V, int32_t *out_pos,
+// Plan item i as a gather segment of this layer.  A module that the copy engine brings in is transferred here
+// (one transfer per tensor on the caller's stream, straight into the packed rows: a module is contiguous on
+// both sides) and left to the kernel for its position IDs only.
+int segment_of(pc_ctx *ctx, const PlanRef &pr, size_t i, const int *kv_offsets, void *out_K, void *out_V,
+               hipStream_t stream, GatherSeg &sg)
+{
+    const PlanItem &it = pr.plan->items[i];
+    const ModuleEntry *m = pr.entry[i];
+    const uint8_t *pool = m->host ? ctx->host_pool : ctx->pool;
+    sg.src_k = pool + m->k_offset;
+    sg.src_v = pool + m->v_offset;
+    sg.dst_row = kv_offsets[it.prompt] + it.row;
+    sg.n_rows = it.n_rows;
+    sg.start_pos = it.start_pos;
+    sg.first_tile = 0;
+    if (by_copy_engine(ctx, m)) {
+        const size_t bytes = (size_t)sg.n_rows * ctx->row_bytes, dst = (size_t)sg.dst_row * ctx->row_bytes;
+        if (hipMemcpyAsync(static_cast<uint8_t *>(out_K) + dst, sg.src_k, bytes, hipMemcpyHostToDevice, stream) != hipSuccess ||
+            hipMemcpyAsync(static_cast<uint8_t *>(out_V) + dst, sg.src_v, bytes, hipMemcpyHostToDevice, stream) != hipSuccess) {
+            (void)hipGetLastError();
+            return PC_E_HIP;
+        }
+        sg.src_k = sg.src_v = nullptr;
+    }
+    return PC_OK;
+}
+
+// Gather launches for a planned call: as many as the segment table of the kernel arguments needs
+// (kMaxGatherSegs segments each); nothing is allocated.
+int run_gather(pc_ctx *ctx, const PlanRef &pr, const int *kv_offsets, void *out_K, void *out_V, int32_t *out_pos,
                hipStream_t stream)
 {
-    int rc = copy_host_segments(ctx, segs, out_K, out_V, stream);
-    if (rc != PC_OK) return rc;
-    const int rows_per_tile = gather_rows_per_tile(ctx, segs);
-    for (size_t base = 0; base < segs.size(); base += kMaxGatherSegs) {
+    const int rows_per_tile = gather_rows_per_tile(ctx, pr);
+    const size_t n = pr.plan->items.size();
+    size_t i = 0;
+    while (i < n) {
         GatherArgs a;
-        a.n_segs = (int)std::min<size_t>(kMaxGatherSegs, segs.size() - base);
+        a.n_segs = 0;
         a.rows_per_tile = rows_per_tile;
         a.row_bytes = (int)ctx->row_bytes;
         int tiles = 0;
-        for (int i = 0; i < a.n_segs; ++i) {
-            a.seg[i] = segs[base + i];
-            a.seg[i].first_tile = tiles;
-            tiles += tiles_of(a.seg[i], rows_per_tile);
+        for (; i < n && a.n_segs < kMaxGatherSegs; ++i) {
+            if (pr.plan->items[i].n_rows == 0) continue;
+            GatherSeg &sg = a.seg[a.n_segs];
+            int rc = segment_of(ctx, pr, i, kv_offsets, out_K, out_V, stream, sg);
+            if (rc != PC_OK) return rc;
+            sg.first_tile = tiles;
+            tiles += tiles_of(sg, rows_per_tile);
+            ++a.n_segs;
         }
         a.total_tiles = tiles;
-        rc = launch_gather(ctx, a, static_cast<uint8_t *>(out_K), static_cast<uint8_t *>(out_V), out_pos, stream);
+        if (a.n_segs == 0) break;
+        int rc = launch_gather(ctx, a, static_cast<uint8_t *>(out_K), static_cast<uint8_t *>(out_V), out_pos, stream);
         if (rc != PC_OK) return rc;
     }
     return PC_OK;
+}
+
+int count_segments(const PlanRef &pr)
+{
+    int n = 0;
+    for (const PlanItem &it : pr.plan->items) n += it.n_rows > 0;
+    return n;
 }
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -451,6 +559,7 @@ int pc_store_module(pc_ctx *ctx, int layer, int module_id, const void *K, const 
     if (it == table.end()) {
         table.emplace(module_id, e);
         ctx->pool_used = e.v_offset + bytes;
+        ++ctx->generation;   // cached plans were made without this module
     }
     return PC_OK;
 }
@@ -467,7 +576,7 @@ int pc_resolve_scaffolds(int n_ids, const int *ids, int n_scaffolds, const int *
         sc[s].member.assign(member_ids + lo, member_ids + hi);
         sc[s].override_id.assign(override_ids + lo, override_ids + hi);
     }
-    std::vector<int> v(ids, ids + n_ids);
+    cvec<int> v(ids, ids + n_ids);
     apply_scaffolds(sc, v);
     for (int i = 0; i < n_ids; ++i) out_ids[i] = v[i];
     return PC_OK;
@@ -485,6 +594,7 @@ int pc_define_scaffold(pc_ctx *ctx, int n_members, const int *member_ids, const 
         sc.override_id.push_back(override_ids[i]);
     }
     ctx->scaffolds.push_back(sc);
+    ++ctx->generation;   // cached plans were made without this scaffold
     return PC_OK;
 }
 
@@ -583,6 +693,7 @@ int pc_store_module_host(pc_ctx *ctx, int layer, int module_id, const void *K_ho
     if (it == table.end()) {
         table.emplace(module_id, e);
         ctx->host_pool_used = e.v_offset + bytes;
+        ++ctx->generation;
     }
     return PC_OK;
 }
@@ -593,12 +704,12 @@ int pc_assemble_kv(pc_ctx *ctx, int layer, const int *module_ids, int n_modules,
     if (!ctx || n_modules < 0 || capacity_tokens < 0 || (n_modules > 0 && !module_ids)) return PC_E_BADARG;
     if (layer < 0 || layer >= ctx->cfg.n_layers) return PC_E_LAYER;
     if (!out_K || !out_V || !out_pos || !aligned16(out_K) || !aligned16(out_V)) return PC_E_BADARG;
-    std::vector<GatherSeg> segs;
-    int rows = 0;
-    int rc = plan_prompt(ctx, layer, module_ids, n_modules, 0, capacity_tokens, segs, &rows);
+    const int mod_offsets[2] = {0, n_modules}, kv_offsets[2] = {0, capacity_tokens};
+    PlanRef pr;
+    int rc = get_plan(ctx, layer, module_ids, mod_offsets, 1, kv_offsets, nullptr, pr);
     if (rc != PC_OK) return rc;
-    rc = run_gather(ctx, segs, out_K, out_V, out_pos, as_stream(stream));
-    if (rc == PC_OK && out_n_tokens) *out_n_tokens = rows;
+    rc = run_gather(ctx, pr, kv_offsets, out_K, out_V, out_pos, as_stream(stream));
+    if (rc == PC_OK && out_n_tokens) *out_n_tokens = pr.plan->prompt_rows[0];
     return rc;
 }
 
@@ -609,19 +720,80 @@ int pc_assemble_kv_batched(pc_ctx *ctx, int layer, const int *module_ids_flat, c
     if (!ctx || n_prompts < 0 || !mod_offsets || !kv_offsets) return PC_E_BADARG;
     if (layer < 0 || layer >= ctx->cfg.n_layers) return PC_E_LAYER;
     if (!out_K || !out_V || !out_pos || !aligned16(out_K) || !aligned16(out_V)) return PC_E_BADARG;
-    std::vector<GatherSeg> segs;
-    std::vector<int> rows(n_prompts, 0);
-    for (int b = 0; b < n_prompts; ++b) {
-        const int n = mod_offsets[b + 1] - mod_offsets[b];
-        const int cap = kv_offsets[b + 1] - kv_offsets[b];
-        if (n < 0 || cap < 0 || kv_offsets[b] < 0 || (n > 0 && !module_ids_flat)) return PC_E_BADARG;
-        int rc = plan_prompt(ctx, layer, module_ids_flat + mod_offsets[b], n, kv_offsets[b], cap, segs, &rows[b]);
-        if (rc != PC_OK) return rc;
-    }
-    int rc = run_gather(ctx, segs, out_K, out_V, out_pos, as_stream(stream));
+    for (int b = 0; b < n_prompts; ++b)
+        if (kv_offsets[b + 1] - kv_offsets[b] < 0 || kv_offsets[b] < 0) return PC_E_BADARG;
+    PlanRef pr;
+    int rc = get_plan(ctx, layer, module_ids_flat, mod_offsets, n_prompts, kv_offsets, nullptr, pr);
+    if (rc != PC_OK) return rc;
+    rc = run_gather(ctx, pr, kv_offsets, out_K, out_V, out_pos, as_stream(stream));
     if (rc == PC_OK && out_n_tokens)
-        for (int b = 0; b < n_prompts; ++b) out_n_tokens[b] = rows[b];
+        for (int b = 0; b < n_prompts; ++b) out_n_tokens[b] = pr.plan->prompt_rows[b];
     return rc;
+}
+
+int pc_assemble_kv_layers(pc_ctx *ctx, int first_layer, int n_layers, const int *module_ids_flat, const int *mod_offsets,
+                          int n_prompts, void *const *out_K, void *const *out_V, int32_t *const *out_pos,
+                          const int *kv_offsets, int *out_n_tokens, void *stream)
+{
+    if (!ctx || n_prompts < 0 || n_layers < 0 || !mod_offsets || !kv_offsets) return PC_E_BADARG;
+    if (first_layer < 0 || (long)first_layer + n_layers > (long)ctx->cfg.n_layers) return PC_E_LAYER;
+    if (n_layers > 0 && (!out_K || !out_V || !out_pos)) return PC_E_BADARG;
+    for (int l = 0; l < n_layers; ++l)
+        if (!out_K[l] || !out_V[l] || !out_pos[l] || !aligned16(out_K[l]) || !aligned16(out_V[l])) return PC_E_BADARG;
+    for (int b = 0; b < n_prompts; ++b)
+        if (kv_offsets[b + 1] - kv_offsets[b] < 0 || kv_offsets[b] < 0) return PC_E_BADARG;
+    // every layer is planned (validated) before the first launch: an error leaves all outputs untouched
+    PlanRef first;
+    int segs_per_layer = 0;   // of the layer with most
+    for (int l = 0; l < n_layers; ++l) {
+        PlanRef pr;
+        int rc = get_plan(ctx, first_layer + l, module_ids_flat, mod_offsets, n_prompts, kv_offsets, nullptr, pr);
+        if (rc != PC_OK) return rc;
+        if (l == 0) first = pr;
+        segs_per_layer = std::max(segs_per_layer, count_segments(pr));
+    }
+    if (n_layers == 0) return PC_OK;
+    hipStream_t st = as_stream(stream);
+    if (segs_per_layer > kMaxGatherSegs) {   // more segments per layer than one launch holds: layer by layer
+        for (int l = 0; l < n_layers; ++l) {
+            PlanRef pr;
+            int rc = get_plan(ctx, first_layer + l, module_ids_flat, mod_offsets, n_prompts, kv_offsets, nullptr, pr);
+            if (rc == PC_OK) rc = run_gather(ctx, pr, kv_offsets, out_K[l], out_V[l], out_pos[l], st);
+            if (rc != PC_OK) return rc;
+        }
+    } else if (segs_per_layer > 0) {
+        const int layers_per_launch = std::min(kMaxGatherLayers, kMaxGatherSegs / segs_per_layer);
+        for (int l0 = 0; l0 < n_layers; l0 += layers_per_launch) {
+            const int nl = std::min(layers_per_launch, n_layers - l0);
+            GatherLayersArgs a;
+            a.g.n_segs = 0;
+            a.g.row_bytes = (int)ctx->row_bytes;
+            int tiles = 0;
+            for (int l = 0; l < nl; ++l) {
+                PlanRef pr;   // a cache hit (planned above); a layer that differs from the first one has a plan of its own
+                int rc = get_plan(ctx, first_layer + l0 + l, module_ids_flat, mod_offsets, n_prompts, kv_offsets, nullptr, pr);
+                if (rc != PC_OK) return rc;
+                if (l == 0) a.g.rows_per_tile = gather_rows_per_tile(ctx, pr, 0, nl);
+                a.out[l] = GatherLayerOut{static_cast<uint8_t *>(out_K[l0 + l]), static_cast<uint8_t *>(out_V[l0 + l]), out_pos[l0 + l]};
+                for (size_t i = 0; i < pr.plan->items.size(); ++i) {
+                    if (pr.plan->items[i].n_rows == 0) continue;
+                    GatherSeg &sg = a.g.seg[a.g.n_segs];
+                    rc = segment_of(ctx, pr, i, kv_offsets, out_K[l0 + l], out_V[l0 + l], st, sg);
+                    if (rc != PC_OK) return rc;
+                    sg.first_tile = tiles;
+                    tiles += tiles_of(sg, a.g.rows_per_tile);
+                    a.seg_layer[a.g.n_segs] = (unsigned char)l;
+                    ++a.g.n_segs;
+                }
+            }
+            a.g.total_tiles = tiles;
+            int rc = launch_gather_layers(ctx, a, st);
+            if (rc != PC_OK) return rc;
+        }
+    }
+    if (out_n_tokens)
+        for (int b = 0; b < n_prompts; ++b) out_n_tokens[b] = first.plan->prompt_rows[b];
+    return PC_OK;
 }
 
 int pc_rope(pc_ctx *ctx, void *x, int n_tokens, int n_heads, const int32_t *pos, void *stream)
@@ -691,40 +863,39 @@ static int assemble_append_impl(pc_ctx *ctx, int layer, const int *module_ids_fl
     if (!ctx || n_prompts < 0 || !mod_offsets || !kv_offsets || !q_offsets) return PC_E_BADARG;
     if (layer < 0 || layer >= ctx->cfg.n_layers) return PC_E_LAYER;
     if (!out_K || !out_V || !out_pos || !aligned16(out_K) || !aligned16(out_V)) return PC_E_BADARG;
-    std::vector<GatherSeg> segs;
-    std::vector<int> rows(n_prompts, 0);
-    int new_rows = 0;
+    long new_rows = 0;
     for (int b = 0; b < n_prompts; ++b) {
-        const int n = mod_offsets[b + 1] - mod_offsets[b];
         const int cap = kv_offsets[b + 1] - kv_offsets[b];
         const int nq = q_offsets[b + 1] - q_offsets[b];
-        if (n < 0 || cap < 0 || nq < 0 || kv_offsets[b] < 0 || q_offsets[b] < 0 || (n > 0 && !module_ids_flat))
-            return PC_E_BADARG;
-        int rc = plan_prompt(ctx, layer, module_ids_flat + mod_offsets[b], n, kv_offsets[b], cap, segs, &rows[b]);
-        if (rc != PC_OK) return rc;
-        if ((long)rows[b] + nq > (long)cap) return PC_E_CAPACITY;
+        if (cap < 0 || nq < 0 || kv_offsets[b] < 0 || q_offsets[b] < 0) return PC_E_BADARG;
         new_rows += nq;
     }
+    PlanRef pr;
+    int rc = get_plan(ctx, layer, module_ids_flat, mod_offsets, n_prompts, kv_offsets, q_offsets, pr);
+    if (rc != PC_OK) return rc;
     if (new_rows > 0 && (!K_new_raw || !V_new || !q_pos)) return PC_E_BADARG;
+    const int *rows = pr.plan->prompt_rows.data();
 
-    int rc = PC_OK;
-    if (segs.size() <= (size_t)kMaxGatherSegs && n_prompts <= kMaxFusedAppendSegs) {
-        rc = copy_host_segments(ctx, segs, out_K, out_V, as_stream(stream));
-        if (rc != PC_OK) return rc;
+    const int n_segs = count_segments(pr);
+    if (n_segs <= kMaxGatherSegs && n_prompts <= kMaxFusedAppendSegs) {
         FusedKvArgs a;
-        const int rows_per_tile = gather_rows_per_tile(ctx, segs, new_rows);
-        a.g.n_segs = (int)segs.size();
+        const int rows_per_tile = gather_rows_per_tile(ctx, pr, new_rows);
+        a.g.n_segs = 0;
         a.g.rows_per_tile = rows_per_tile;
         a.g.row_bytes = (int)ctx->row_bytes;
         int tiles = 0;
-        for (int i = 0; i < a.g.n_segs; ++i) {
-            a.g.seg[i] = segs[i];
-            a.g.seg[i].first_tile = tiles;
-            tiles += tiles_of(a.g.seg[i], rows_per_tile);
+        for (size_t i = 0; i < pr.plan->items.size(); ++i) {
+            if (pr.plan->items[i].n_rows == 0) continue;
+            GatherSeg &sg = a.g.seg[a.g.n_segs];
+            rc = segment_of(ctx, pr, i, kv_offsets, out_K, out_V, as_stream(stream), sg);
+            if (rc != PC_OK) return rc;
+            sg.first_tile = tiles;
+            tiles += tiles_of(sg, rows_per_tile);
+            ++a.g.n_segs;
         }
         a.g.total_tiles = tiles;
         a.n_app = n_prompts;
-        a.app_rows = new_rows;
+        a.app_rows = (int)new_rows;
         for (int b = 0; b < n_prompts; ++b) {
             a.app[b].q_begin = q_offsets[b];
             a.app[b].n = q_offsets[b + 1] - q_offsets[b];
@@ -735,10 +906,10 @@ static int assemble_append_impl(pc_ctx *ctx, int layer, const int *module_ids_fl
                                   K_new_raw, V_new, q_pos, as_stream(stream), Q_new, Q_rot, q_prescale(ctx));
     } else {
         // too many segments for one argument block: the two steps one after the other
-        rc = run_gather(ctx, segs, out_K, out_V, out_pos, as_stream(stream));
+        rc = run_gather(ctx, pr, kv_offsets, out_K, out_V, out_pos, as_stream(stream));
         if (rc == PC_OK)
             rc = append_impl(ctx, layer, K_new_raw, V_new, q_pos, q_offsets, n_prompts, out_K, out_V, out_pos, kv_offsets,
-                             rows.data(), stream, Q_new, Q_rot);
+                             rows, stream, Q_new, Q_rot);
     }
     if (rc == PC_OK && out_n_tokens)
         for (int b = 0; b < n_prompts; ++b) out_n_tokens[b] = rows[b] + (q_offsets[b + 1] - q_offsets[b]);
@@ -932,31 +1103,22 @@ static int prefill_attn_shared_impl(pc_ctx *ctx, int layer, const void *Q_new, c
     if (!Q_new || !q_pos || !out || !K_tail || !V_tail || !aligned16(Q_new) || !aligned16(out) || !aligned16(K_tail) ||
         !aligned16(V_tail))
         return PC_E_BADARG;
-    const auto &table = ctx->modules[layer];
     const uint8_t *kt = static_cast<const uint8_t *>(K_tail), *vt = static_cast<const uint8_t *>(V_tail);
     // every prompt is checked before the first launch, so that an error leaves `out` untouched
-    std::vector<int> ids_all;   // every prompt's imports with scaffolds applied, same offsets as the caller's list
     for (int b = 0; b < n_prompts; ++b) {
         const int nm = mod_offsets[b + 1] - mod_offsets[b], nq = q_offsets[b + 1] - q_offsets[b];
         if (nm + 1 > kMaxKvSegs || (size_t)nq * ctx->row_bytes >= ((size_t)1 << 32)) return PC_E_UNSUPPORTED;
-        std::vector<int> res;
-        int rrc = resolve_imports(ctx, layer, module_ids_flat + mod_offsets[b], nm, res);
-        if (rrc != PC_OK) return rrc;
-        if ((int)ids_all.size() != mod_offsets[b] - mod_offsets[0]) return PC_E_BADARG;
-        ids_all.insert(ids_all.end(), res.begin(), res.end());
-        std::vector<int> starts(nm), lens(nm);
-        for (int i = 0; i < nm; ++i) {
-            auto it = table.find(res[i]);
-            if (it == table.end()) return PC_E_UNKNOWN_MODULE;
-            starts[i] = it->second.start_pos;
-            lens[i] = it->second.n_tokens;
-            if ((size_t)lens[i] * ctx->row_bytes >= ((size_t)1 << 32)) return PC_E_UNSUPPORTED;   // 32-bit offsets inside a range
-            if (it->second.host) return PC_E_UNSUPPORTED;   // host-resident modules are assembled (copied), not read in place
-        }
-        int rc = check_ranges(nm, starts.data(), lens.data(), ctx->cfg.max_pos);
-        if (rc != PC_OK) return rc;
+    }
+    PlanRef pr;
+    int prc = get_plan(ctx, layer, module_ids_flat, mod_offsets, n_prompts, nullptr, nullptr, pr);
+    if (prc != PC_OK) return prc;
+    const size_t n_items = pr.plan->items.size();
+    for (size_t i = 0; i < n_items; ++i) {
+        if ((size_t)pr.plan->items[i].n_rows * ctx->row_bytes >= ((size_t)1 << 32)) return PC_E_UNSUPPORTED;   // 32-bit offsets inside a range
+        if (pr.entry[i]->host) return PC_E_UNSUPPORTED;   // host-resident modules are assembled (copied), not read in place
     }
     int b = 0;
+    size_t item = 0;   // first plan item of prompt b (items are grouped by prompt, in order)
     while (b < n_prompts) {
         // as many prompts per launch as the range table and the prompt table hold
         AttnBatch ab;
@@ -968,11 +1130,12 @@ static int prefill_attn_shared_impl(pc_ctx *ctx, int layer, const void *Q_new, c
             if (n_seg + nm + 1 > kMaxKvSegs) break;
             const int seg0 = n_seg;
             int rows = 0;
-            for (int i = 0; i < nm; ++i) {
-                const ModuleEntry &m = table.find(ids_all[mod_offsets[b] - mod_offsets[0] + i])->second;
-                if (m.n_tokens == 0) continue;
-                tab.seg[n_seg++] = KvSeg{ctx->pool + m.k_offset, ctx->pool + m.v_offset, ctx->iota + m.start_pos, rows, 0};
-                rows += m.n_tokens;
+            for (; item < n_items && pr.plan->items[item].prompt == b; ++item) {
+                const PlanItem &it = pr.plan->items[item];
+                if (it.n_rows == 0) continue;
+                const ModuleEntry *m = pr.entry[item];
+                tab.seg[n_seg++] = KvSeg{ctx->pool + m->k_offset, ctx->pool + m->v_offset, ctx->iota + it.start_pos, rows, 0};
+                rows += it.n_rows;
             }
             if (nq > 0) {   // the prompt's own tokens: rows q_offsets[b].. of the tail buffers, positions q_pos
                 tab.seg[n_seg++] = KvSeg{kt + (size_t)q_offsets[b] * ctx->row_bytes, vt + (size_t)q_offsets[b] * ctx->row_bytes,
@@ -1016,6 +1179,15 @@ int pc_prefill_attn_static(pc_ctx *ctx, int layer, const void *Q_new, const int3
     const ScratchRef fixed{ctx->static_scratch, kStaticScratchBytes, true};
     return prefill_attn_batched_impl(ctx, layer, Q_new, q_pos, q_offsets, 1, asm_K, asm_V, asm_pos, kv_offsets, kv_lens, out,
                                      stream, false, &fixed);
+}
+
+int pc_plan_stats(const pc_ctx *ctx, long *hits, long *misses, long *heap_allocs)
+{
+    if (!ctx) return PC_E_BADARG;
+    if (hits) *hits = (long)ctx->plan_hits;
+    if (misses) *misses = (long)ctx->plan_misses;
+    if (heap_allocs) *heap_allocs = g_plan_heap_allocs;
+    return PC_OK;
 }
 
 /* ------------------------------------------------------------ host integers */

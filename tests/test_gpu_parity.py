@@ -113,6 +113,51 @@ def test_bf16_text_inside_gap_sees_only_earlier_positions():
     run_and_check(w)
 
 
+@pytest.mark.parametrize("hq,hkv,d", [(8, 2, 128), (4, 4, 128), (8, 8, 64)])
+def test_text_in_a_gap_with_whole_modules_after_it(hq, hkv, d):
+    """Sec. 3.4: uncached text placed between modules.  150 tokens right after module 0, inside the hole the omitted
+    module 1 left; modules 2 and 3 (several 64-key tiles each) lie wholly after them, so their tiles hold nothing the
+    text can see, while the trailing tokens see everything.  Packed (one pass and split over the keys, buffer order
+    that puts the hidden modules first, in the middle and last) and read in place, every row against the oracle."""
+    for order in ([0, 2, 3], [2, 0, 3], [3, 2, 0]):
+        w = W.custom(f"gap_text_{hq}_{hkv}_{d}", "bf16", hq, hkv, d, [260, 500, 330, 200], None,
+                     [W.Prompt(order, 40, gap_after=0, n_gap=150), W.Prompt([0], 3)], max_pos=4096)
+        run_and_check(w, label=f"/order={order}")
+        run_and_check(w, scratch_bytes=4096, label=f"/order={order}/one pass")
+        _shared_run(w, 0, None)
+
+
+def test_hidden_keys_do_not_change_a_bit_of_the_result():
+    """Keys at position IDs above every query's (whole tiles of them: the kernel skips those tiles, or masks them) are
+    appended to a prompt; the output must keep every bit.  One pass over the keys, so that both runs cut the visible
+    keys into the same tiles; the hidden keys carry huge values."""
+    dev = torch.device("cuda:0")
+    hq, hkv, d, n_q, n_vis, n_hid = 8, 2, 128, 96, 640, 448
+    g = torch.Generator().manual_seed(77)
+    K = torch.randn((n_vis + n_hid, hkv, d), generator=g).to(torch.bfloat16)
+    V = torch.randn((n_vis + n_hid, hkv, d), generator=g).to(torch.bfloat16)
+    K[n_vis:] *= 50
+    V[n_vis:] = 1.0e4
+    Q = torch.randn((n_q, hq, d), generator=g).to(torch.bfloat16).to(dev)
+    pos = torch.cat([torch.randperm(n_vis, generator=g), torch.arange(3000, 3000 + n_hid)]).to(torch.int32)
+    q_pos = torch.arange(n_vis - n_q, n_vis, dtype=torch.int32).to(dev)      # the queries sit at the last visible positions
+    pc = pcb.PromptCache(1, hq, hkv, d, pcb.PC_BF16, max_pos=8192, pool_bytes=1 << 20, scratch_bytes=4096)
+    try:
+        outs = []
+        for n_kv in (n_vis, n_vis + n_hid):
+            out = torch.full((n_q, hq, d), float("nan"), dtype=torch.bfloat16, device=dev)
+            pc.pc_prefill_attn(0, Q, q_pos, K[:n_kv].to(dev), V[:n_kv].to(dev), pos[:n_kv].to(dev), n_kv, out)
+            torch.cuda.synchronize()
+            assert pc.pc_last_attn_launch()[0] == 1
+            outs.append(out.cpu())
+        assert torch.equal(outs[0].view(torch.int16), outs[1].view(torch.int16))
+        ref = oracle.attn(to_f64(Q.cpu()), q_pos.cpu().numpy(), to_f64(K), to_f64(V), pos.numpy(), 10000.0)
+        err, rel = attn_errors(outs[1], ref)
+        assert err <= 2e-2 and rel <= 1e-2, (err, rel)
+    finally:
+        pc.close()
+
+
 def test_bf16_masked_keys_cannot_leak():
     """Poison: huge V (and large K) at rows some queries must not see."""
     # module 1 (positions 128..227) is omitted; 24 uncached tokens sit in its hole, module 2 lies after them
