@@ -31,13 +31,25 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
-# HBM bytes per launch from rocprofv3 FETCH_SIZE (x1.988, calibrated on a copy of known size) + WRITE_SIZE;
-# the summaries are kept under profiles/.  Only known for the default workload in the fused-launch, packed-copy mode
-# (keyed by where Q is rotated).
 # --q-rotation auto: the largest number of uncached tokens per step for which Q is rotated in the assembly launch
 ROTATE_ONCE_MAX_TOKENS = 1024
-MEASURED_TRAFFIC = {("long_doc_8k", "once"): {"attn": 37.0e6 + 17.3e6, "gather": 36.7e6 + 36.7e6},
-                    ("long_doc_8k", "attention"): {"attn": 38.0e6 + 17.3e6, "gather": 34.6e6 + 34.6e6}}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic.json")
+
+
+def measured_traffic(config, source_hash):
+    """HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a copy of known size) of the kernels of
+    this run's configuration, as `python -m paper_2311_04934_amd.profile_hot_path` recorded them under profiles/.
+    Only a record made on the sources the loaded library was built from counts; otherwise {} (reported as null)."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            entries = json.load(f)
+    except (OSError, ValueError):
+        return {}
+    for e in entries.values():
+        if (e.get("source_hash") == source_hash and e.get("workload") == config["workload"] and e.get("kv_path") == config["kv_path"]
+                and e.get("assembly") == config["assembly"] and e.get("q_rotation") == config["q_rotation"]):
+            return {k: v["fetched_bytes"] + v["written_bytes"] for k, v in e["kernels"].items()}
+    return {}
 
 
 def attn_flops(w, prompt_lens, n_new):
@@ -207,6 +219,11 @@ def main(argv=None) -> int:
                          "(pc_assemble_append_kv_batched + pc_prefill_attn_batched); auto: once up to "
                          f"{ROTATE_ONCE_MAX_TOKENS} uncached tokens per step (beyond that the extra pass over Q costs "
                          "more HBM time than the attention workgroups save)")
+    ap.add_argument("--assembly", choices=["all-layers", "per-layer"], default="all-layers",
+                    help="all-layers: the imported modules of every layer are concatenated at the start of the step "
+                         "(pc_assemble_kv_layers: modules do not depend on the forward pass), then each layer appends its "
+                         "uncached tokens (pc_append_rotate_batched / pc_append_kv_batched) and runs attention; per-layer: "
+                         "one fused assemble+append launch per layer")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step (all layers' launches) into a HIP graph and time K replays of it")
     ap.add_argument("--overlap", action="store_true",
@@ -327,6 +344,21 @@ def main(argv=None) -> int:
     f_fusr, f_attr = lib.pc_assemble_append_rotate_batched, lib.pc_prefill_attn_rotated_batched
     fused = not args.separate_launches
     in_place = args.modules_in_place
+    all_layers = args.assembly == "all-layers" and not (in_place or args.overlap or args.separate_launches or args.host_tier)
+    if all_layers:
+        fused = False
+        arr = lambda ts: (ctypes.c_void_p * L)(*[t.data_ptr() for t in ts])
+        pK_all, pV_all, pP_all = arr(asm_K), arr(asm_V), arr(asm_pos)
+        a_lay = (ctx, 0, L, hp(ids_flat), hp(mod_offs), B, pK_all, pV_all, pP_all, hp(kv_off_c), hp(n_out), stream)
+        f_lay = lib.pc_assemble_kv_layers
+        calls_al = []
+        for layer in range(L):
+            if rot_once:
+                a_ap = (ctx, layer, P(Kn[layer]), P(Vn[layer]), P(Q[layer]), P(q_pos), hp(q_off_c), B, P(asm_K[layer]),
+                        P(asm_V[layer]), P(asm_pos[layer]), hp(kv_off_c), hp(n_mod_c), P(Q_rot[layer]), stream)
+                calls_al.append((lib.pc_append_rotate_batched, a_ap, f_attr, calls_rot[layer][1]))
+            else:
+                calls_al.append((f_app, calls[layer][1], f_att, calls[layer][2]))
     if in_place:
         # no packed copy: the uncached tokens' rows go to a tail buffer laid out like Q, attention reads
         # the modules from the pool through a row-range table
@@ -353,6 +385,13 @@ def main(argv=None) -> int:
             e.record(torch.cuda.current_stream())
 
     def step():
+        if all_layers:
+            rc = f_lay(*a_lay)
+            for fa, aa, fb, ab in calls_al:
+                rc = rc or fa(*aa) or fb(*ab)
+            if rc:
+                raise pcb.PcError(rc, "bench step (all layers assembled at once)")
+            return
         if in_place:
             f_tail, f_sh = (lib.pc_append_rotate_batched, lib.pc_prefill_attn_shared_rotated_batched) if rot_once else (f_app, f_shr)
             for a_tail, a_shr in calls_ip:
@@ -433,7 +472,7 @@ def main(argv=None) -> int:
         gather_bytes_layer = sum(n_new) * (2 * 2 * w.row_bytes + 8)
     elif fused:   # the same launch also reads and writes the uncached tokens' rows (and reads/writes their position IDs)
         gather_bytes_layer += sum(n_new) * (2 * 2 * w.row_bytes + 8)
-    if rot_once:   # the same launch reads Q_new and writes Q_rot
+    if rot_once and not all_layers:   # the same launch reads Q_new and writes Q_rot
         gather_bytes_layer += sum(n_new) * 2 * w.n_q_heads * w.head_dim * w.elem_bytes
     attn_tflops_step = flops_layer * L / (ms_per_step * 1e-3) / 1e12
 
@@ -447,6 +486,7 @@ def main(argv=None) -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "kv_path": "modules read in place" if in_place else "packed copy",
+                   "assembly": "not used" if in_place else ("all layers' modules at the start of the step (pc_assemble_kv_layers), uncached tokens appended per layer" if all_layers else "per layer, one launch with the append"),
                    "module_tier": ("host memory, " + ("loaded by the assembly kernel" if args.host_tier == "kernel" else "copy engine")) if args.host_tier else "HBM pool",
                    "q_rotation": "once per token, in the assembly launch" if rot_once else "in every attention workgroup", "overlap": bool(args.overlap), "hip_graph": bool(args.graph), "position_encoding": "alibi" if args.alibi else "rope", "layers": L, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
                    "head_dim": w.head_dim, "prompts": B, "module_tokens": n_mod if B <= 4 else [n_mod[0], "..."],
@@ -457,22 +497,34 @@ def main(argv=None) -> int:
     }
     if kern.get("attn", {}).get("avg_us"):
         a_us = kern["attn"]["avg_us"]
-        g_us = kern["append" if in_place else "gather"]["avg_us"]
+        gk = kern["append" if in_place else "gather"]
+        g_us = gk["avg_us"]
         attn_tf = flops_layer / (a_us * 1e-6) / 1e12
-        gat_gbs = gather_bytes_layer / (g_us * 1e-6) / 1e9
+        # bytes of all assembly launches of a step over the time of all of them (one launch per layer, or a few per step)
+        gat_gbs = gather_bytes_layer * L * args.steps / (g_us * gk["launches"] * 1e-6) / 1e9
+        c_us = kern.get("combine", {}).get("avg_us") or 0.0
+        attn_merge_tf = flops_layer / ((a_us + c_us) * 1e-6) / 1e12
         result["kernels_us"] = {k: (round(v["avg_us"], 2) if v["avg_us"] else None) for k, v in kern.items()}
         result["kernels_us_median_min"] = {k: [round(v["median_us"], 2), round(v["min_us"], 2)] for k, v in kern.items() if v["avg_us"]}
         result["assemble_GBps"] = round(gat_gbs, 1)
         result["attn_kernel_TFLOPs"] = round(attn_tf, 1)
-        plain = fused and not (in_place or args.overlap or args.alibi or args.host_tier)
-        traffic_known = MEASURED_TRAFFIC.get((w.name, "once" if rot_once else "attention"), {}) if plain else {}
+        plain = not (args.overlap or args.alibi or args.host_tier or args.graph)
+        traffic_known = measured_traffic(result["config"], pc_build.built_hash()) if plain else {}
+        result["source_hash"] = pc_build.built_hash()
         result["roofline"] = {"kernel": ("attn_bf16_dma_kernel<1, 8, %s, %s>" % ("true" if in_place else "false", "true" if args.alibi else "false")) if w.head_dim == 128 else "attn_bf16_kernel", "bound": "mfma", "achieved": round(attn_tf, 1),
                               "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                               "frac": round(attn_tf / MFMA_BF16_PEAK_TFLOPS, 4),
                               "traffic": traffic_known.get("attn")}
-        result["roofline_assemble"] = {"kernel": "append_kernel" if in_place else ("gather_append_kernel" if fused else "gather_kv_kernel"), "bound": "hbm", "achieved": round(gat_gbs, 1),
+        # the whole attention step of a layer: main kernel plus the merge of the KV splits (when that is a launch of its own)
+        result["roofline"]["with_split_merge"] = {"us": round(a_us + c_us, 2), "achieved": round(attn_merge_tf, 1),
+                                                  "frac": round(attn_merge_tf / MFMA_BF16_PEAK_TFLOPS, 4),
+                                                  "traffic": (traffic_known["attn"] + traffic_known.get("combine", 0)) if "attn" in traffic_known else None}
+        result["roofline_assemble"] = {"kernel": "append_kernel" if in_place else ("gather_layers_kernel" if all_layers else ("gather_append_kernel" if fused else "gather_kv_kernel")),
+                                       "launches_per_step": gk["launches"] / args.steps,
+                                       "mbytes_per_launch": round(gather_bytes_layer * L * args.steps / gk["launches"] / 1e6, 2),
+                                       "bound": "hbm", "achieved": round(gat_gbs, 1),
                                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gat_gbs / HBM_PEAK_GBS, 4),
-                                       "traffic": traffic_known.get("gather")}
+                                       "traffic": traffic_known.get("append" if in_place else "gather")}
 
     if args.host_tier:
         # PCIe-inclusive view: the modules' K and V cross the host link once per layer and step

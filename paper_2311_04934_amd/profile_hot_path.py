@@ -1,0 +1,175 @@
+"""rocprofv3 profile of the benchmark's hot path: kernel durations, HBM bytes per launch, matrix-unit counters.
+
+    python -m paper_2311_04934_amd.profile_hot_path [--workload long_doc_8k] [--out gpurun_out/profile] [bench flags ...]
+
+Runs `bench.py` four times under rocprofv3 (one run per counter group: the profiler does not split counters over
+passes) and writes, under --out:
+
+    <workload>[_<tag>]_hot_path.md   a summary in text: the commands, kernel statistics, FETCH_SIZE / WRITE_SIZE per
+                                     launch scaled by what the same counter reads for a plain copy of known size
+                                     (bench.py --calibrate runs one), and the SQ counters of the attention kernel
+    traffic_<workload>[_<tag>].json  the HBM bytes per launch that `bench.py` reports as roofline.traffic, with the
+                                     hash of the sources they were measured on
+
+Copy both into profiles/ (merge the json into profiles/traffic.json with --merge) to have them reported; bench.py
+prints `null` for a traffic whose source hash is not the one of the library it runs.
+Needs a GPU and rocprofv3.  The program under the profiler is `python3 bench.py ...` itself (no shell in between).
+"""
+from __future__ import annotations
+
+import argparse
+import collections
+import csv
+import glob
+import json
+import os
+import statistics
+import subprocess
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SQ_COUNTERS = ["SQ_VALU_MFMA_BUSY_CYCLES", "SQ_BUSY_CYCLES", "SQ_INSTS_VALU", "SQ_INSTS_MFMA", "SQ_WAVE_CYCLES",
+               "SQ_ACTIVE_INST_VALU", "SQ_WAIT_INST_ANY", "GRBM_GUI_ACTIVE"]
+
+
+def kernel_key(name: str):
+    """Short name of the library's kernels (None for anything else)."""
+    for tag, key in (("attn_bf16_dma_kernel", "attn"), ("attn_bf16_kernel", "attn"), ("attn_combine", "combine"),
+                     ("gather_layers_kernel", "gather"), ("gather_append_kernel", "gather"), ("gather_kv_kernel", "gather"),
+                     ("append_kernel", "append"), ("calib_copy_kernel", "calib_copy")):
+        if tag in name:
+            return key
+    return None
+
+
+def run(cmd, log):
+    print("+ " + " ".join(cmd), flush=True)
+    with open(log, "w") as f:
+        r = subprocess.run(cmd, cwd=ROOT, stdout=f, stderr=subprocess.STDOUT, timeout=900)
+    if r.returncode != 0:
+        raise RuntimeError(f"{cmd[0]} failed ({r.returncode}), see {log}")
+
+
+def counters(path):
+    """{kernel: {counter: [value per dispatch]}} from a rocprofv3 counter_collection csv."""
+    acc = collections.defaultdict(lambda: collections.defaultdict(list))
+    for r in csv.DictReader(open(path)):
+        k = kernel_key(r["Kernel_Name"])
+        if k:
+            acc[k][r["Counter_Name"]].append(float(r["Counter_Value"]))
+    return acc
+
+
+def main(argv=None) -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--workload", default="long_doc_8k")
+    ap.add_argument("--out", default=os.path.join("gpurun_out", "profile"))
+    ap.add_argument("--tag", default="", help="suffix of the output names (e.g. the bench mode)")
+    ap.add_argument("--merge", default=None, help="traffic json to merge the result into (e.g. profiles/traffic.json)")
+    args, bench_flags = ap.parse_known_args(argv)
+    sys.path.insert(0, ROOT)
+    from paper_2311_04934_amd import build as pc_build
+    pc_build.ensure_built()
+    out = os.path.join(ROOT, args.out)
+    os.makedirs(out, exist_ok=True)
+    name = args.workload + ("_" + args.tag if args.tag else "")
+    bench = ["python3", "bench.py", "--workload", args.workload] + bench_flags
+    short = ["--layers", "4", "--steps", "2", "--warmup", "1", "--no-cpu-baseline", "--no-full-prefill", "--calibrate"]
+    cmds = {}
+
+    # 1. durations
+    d_stats = os.path.join(out, name + "_stats")
+    cmds["stats"] = ["rocprofv3", "--kernel-trace", "--stats", "--output-format", "csv", "-d", d_stats, "-o", "bench", "--"] + bench + ["--no-cpu-baseline"]
+    run(cmds["stats"], d_stats + ".log")
+    # 2.-4. counters, one group per run
+    groups = {"fetch": ["FETCH_SIZE"], "write": ["WRITE_SIZE"], "sq": SQ_COUNTERS}
+    dirs = {}
+    for g, names in groups.items():
+        dirs[g] = os.path.join(out, f"{name}_pmc_{g}")
+        cmds[g] = ["rocprofv3", "--pmc"] + names + ["--kernel-trace", "--output-format", "csv", "-d", dirs[g], "-o", g, "--"] + bench + short
+        run(cmds[g], dirs[g] + ".log")
+
+    def find(d, suffix):
+        hits = glob.glob(os.path.join(d, "**", "*" + suffix), recursive=True)
+        if not hits:
+            raise RuntimeError(f"no *{suffix} under {d}")
+        return hits[0]
+
+    # ---- kernel statistics
+    lines = [f"# rocprofv3 summary: hot path on `{args.workload}`" + (f" ({args.tag})" if args.tag else ""), "",
+             f"Sources: hash `{pc_build.source_hash()}` (paper_2311_04934_amd.build.source_hash).  Commands run from the repository root.", "",
+             "## Kernel durations", "", "Command: `" + " ".join(cmds["stats"]) + "`", "",
+             "| kernel | calls | avg us | min us | max us | % of GPU time |", "|---|---|---|---|---|---|"]
+    for r in csv.DictReader(open(find(d_stats, "kernel_stats.csv"))):
+        if kernel_key(r["Name"]):
+            lines.append(f'| {r["Name"]} | {r["Calls"]} | {float(r["AverageNs"]) / 1e3:.2f} | {float(r["MinNs"]) / 1e3:.2f} | '
+                         f'{float(r["MaxNs"]) / 1e3:.2f} | {r["Percentage"]} |')
+    # the attention kernel without the full-prefill comparison's launches (the long ones)
+    durs = collections.defaultdict(list)
+    for r in csv.DictReader(open(find(d_stats, "kernel_trace.csv"))):
+        k = kernel_key(r["Kernel_Name"])
+        if k:
+            durs[k].append((int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3)
+    if durs["attn"]:
+        med = statistics.median(durs["attn"])
+        hot = [x for x in durs["attn"] if x < 5 * med]
+        lines += ["", f"Attention kernel over its {len(hot)} hot-path launches alone (launches shorter than 5x the median; the others "
+                      f"are the full-prefill comparison): average **{sum(hot) / len(hot):.2f} us**, median {statistics.median(hot):.2f} us."]
+    bench_line = None
+    for ln in open(d_stats + ".log"):
+        if ln.startswith("{"):
+            bench_line = json.loads(ln)
+    if bench_line:
+        lines += ["", "`bench.py` in the same run (HIP events carried by the launches): " + json.dumps(bench_line.get("kernels_us")) +
+                  f", {bench_line['per_layer']['cached_us']} us per layer, value {bench_line['value']}."]
+
+    # ---- HBM traffic
+    fetch, write = counters(find(dirs["fetch"], "counter_collection.csv")), counters(find(dirs["write"], "counter_collection.csv"))
+    calib_bytes = float(1 << 30)    # bench.py --calibrate copies 1 GiB: that many bytes fetched and as many written per launch
+    f_raw = statistics.median(fetch["calib_copy"]["FETCH_SIZE"]) * 1024.0
+    w_raw = statistics.median(write["calib_copy"]["WRITE_SIZE"]) * 1024.0
+    f_scale, w_scale = calib_bytes / f_raw, calib_bytes / w_raw
+    lines += ["", "## HBM traffic per launch", "", "Commands (one counter per run):", "`" + " ".join(cmds["fetch"]) + "`", "and the same with `--pmc WRITE_SIZE`.", "",
+              f"Calibration: `calib_copy_kernel` copies 1 GiB; FETCH_SIZE reads {f_raw / 1024:.0f} KiB for it (factor {f_scale:.3f}), "
+              f"WRITE_SIZE {w_raw / 1024:.0f} KiB (factor {w_scale:.3f}).", "",
+              "| kernel | launches | FETCH_SIZE raw KiB (median) | fetched MB | WRITE_SIZE raw KiB (median) | written MB |", "|---|---|---|---|---|---|"]
+    traffic = {}
+    for k in ("gather", "append", "attn", "combine"):
+        if k not in fetch:
+            continue
+        fr, wr = statistics.median(fetch[k]["FETCH_SIZE"]), statistics.median(write[k]["WRITE_SIZE"])
+        fb, wb = fr * 1024 * f_scale, wr * 1024 * w_scale
+        traffic[k] = {"fetched_bytes": round(fb), "written_bytes": round(wb)}
+        lines.append(f"| {k} | {len(fetch[k]['FETCH_SIZE'])} | {fr:.1f} | {fb / 1e6:.2f} | {wr:.1f} | {wb / 1e6:.2f} |")
+
+    # ---- SQ counters of the attention kernel
+    sq = counters(find(dirs["sq"], "counter_collection.csv"))
+    lines += ["", "## Attention kernel, SQ counters (median per launch)", "", "Command: `" + " ".join(cmds["sq"]) + "`", "", "| counter | value |", "|---|---|"]
+    for c in sorted(sq.get("attn", {})):
+        lines.append(f"| {c} | {statistics.median(sq['attn'][c]):.0f} |")
+    a = sq.get("attn", {})
+    if "SQ_VALU_MFMA_BUSY_CYCLES" in a and "SQ_BUSY_CYCLES" in a:
+        lines += ["", f"Matrix pipes busy {statistics.median(a['SQ_VALU_MFMA_BUSY_CYCLES']) / max(statistics.median(a['SQ_BUSY_CYCLES']), 1) / 4:.3f} "
+                      "of the SIMD-cycles the kernel is resident (SQ_VALU_MFMA_BUSY_CYCLES / (4 x SQ_BUSY_CYCLES))."]
+
+    md = os.path.join(out, name + "_hot_path.md")
+    with open(md, "w") as f:
+        f.write("\n".join(lines) + "\n")
+    cfg = (bench_line or {}).get("config", {})
+    entry = {"source_hash": pc_build.source_hash(), "workload": args.workload, "kv_path": cfg.get("kv_path"), "assembly": cfg.get("assembly"),
+             "q_rotation": cfg.get("q_rotation"), "fetch_scale": round(f_scale, 4), "write_scale": round(w_scale, 4), "kernels": traffic}
+    tj = os.path.join(out, f"traffic_{name}.json")
+    with open(tj, "w") as f:
+        json.dump(entry, f, indent=1)
+    if args.merge:
+        path = os.path.join(ROOT, args.merge)
+        allt = json.load(open(path)) if os.path.exists(path) else {}
+        allt[name] = entry
+        with open(path, "w") as f:
+            json.dump(allt, f, indent=1, sort_keys=True)
+    print(open(md).read())
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
