@@ -188,6 +188,10 @@ def length_sweep(args) -> int:
     return 0
 
 
+ASSEMBLY_PER_LAYER = "per layer, one launch with the append"
+ASSEMBLY_ALL_LAYERS = "all layers' modules at the start of the step (pc_assemble_kv_layers), uncached tokens appended per layer"
+
+
 def main(argv=None) -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -219,11 +223,13 @@ def main(argv=None) -> int:
                          "(pc_assemble_append_kv_batched + pc_prefill_attn_batched); auto: once up to "
                          f"{ROTATE_ONCE_MAX_TOKENS} uncached tokens per step (beyond that the extra pass over Q costs "
                          "more HBM time than the attention workgroups save)")
-    ap.add_argument("--assembly", choices=["all-layers", "per-layer"], default="all-layers",
-                    help="all-layers: the imported modules of every layer are concatenated at the start of the step "
-                         "(pc_assemble_kv_layers: modules do not depend on the forward pass), then each layer appends its "
-                         "uncached tokens (pc_append_rotate_batched / pc_append_kv_batched) and runs attention; per-layer: "
-                         "one fused assemble+append launch per layer")
+    ap.add_argument("--assembly", choices=["all-layers", "per-layer"], default="per-layer",
+                    help="per-layer: one fused assemble+append launch per layer; all-layers: the imported modules of every "
+                         "layer are concatenated at the start of the step (pc_assemble_kv_layers: modules do not depend on "
+                         "the forward pass), then each layer appends its uncached tokens (pc_append_rotate_batched / "
+                         "pc_append_kv_batched) and runs attention.  The form that is not chosen is timed too, for the same "
+                         "K steps, and reported under other_assembly_form (--no-other-form leaves it out)")
+    ap.add_argument("--no-other-form", action="store_true")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step (all layers' launches) into a HIP graph and time K replays of it")
     ap.add_argument("--overlap", action="store_true",
@@ -344,9 +350,9 @@ def main(argv=None) -> int:
     f_fusr, f_attr = lib.pc_assemble_append_rotate_batched, lib.pc_prefill_attn_rotated_batched
     fused = not args.separate_launches
     in_place = args.modules_in_place
-    all_layers = args.assembly == "all-layers" and not (in_place or args.overlap or args.separate_launches or args.host_tier)
-    if all_layers:
-        fused = False
+    both_forms = not (in_place or args.overlap or args.separate_launches or args.host_tier)
+    all_layers = args.assembly == "all-layers" and both_forms
+    if both_forms:
         arr = lambda ts: (ctypes.c_void_p * L)(*[t.data_ptr() for t in ts])
         pK_all, pV_all, pP_all = arr(asm_K), arr(asm_V), arr(asm_pos)
         a_lay = (ctx, 0, L, hp(ids_flat), hp(mod_offs), B, pK_all, pV_all, pP_all, hp(kv_off_c), hp(n_out), stream)
@@ -384,14 +390,14 @@ def main(argv=None) -> int:
         for e in ev_att:
             e.record(torch.cuda.current_stream())
 
-    def step():
-        if all_layers:
-            rc = f_lay(*a_lay)
-            for fa, aa, fb, ab in calls_al:
-                rc = rc or fa(*aa) or fb(*ab)
-            if rc:
-                raise pcb.PcError(rc, "bench step (all layers assembled at once)")
-            return
+    def step_all_layers():
+        rc = f_lay(*a_lay)
+        for fa, aa, fb, ab in calls_al:
+            rc = rc or fa(*aa) or fb(*ab)
+        if rc:
+            raise pcb.PcError(rc, "bench step (all layers assembled at once)")
+
+    def step_per_layer():
         if in_place:
             f_tail, f_sh = (lib.pc_append_rotate_batched, lib.pc_prefill_attn_shared_rotated_batched) if rot_once else (f_app, f_shr)
             for a_tail, a_shr in calls_ip:
@@ -424,38 +430,40 @@ def main(argv=None) -> int:
             if rc:
                 raise pcb.PcError(rc, "bench step")
 
-    # ---------------- warmup, then the timed region: exactly K steps, nothing but the library calls
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    run_step = step
-    if args.graph:
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph, stream=torch.cuda.current_stream()):
-            step()
-        run_step = graph.replay
-        run_step()
-        torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        run_step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    step = step_all_layers if all_layers else step_per_layer
+    other_step = (step_per_layer if all_layers else step_all_layers) if both_forms and not (args.no_other_form or args.graph) else None
 
-    # ---------------- the same K steps again, every kernel launch carrying a HIP event pair that holds
-    # the kernel's own begin/end timestamps on its stream.  (Kept out of the region above because launches
-    # that carry events are dispatched one by one and stretch the step by about a fifth.)
-    kern = {}
-    ms_per_step_events = None
-    if not args.no_events:
+    def timed_steps(step_fn):
+        """W untimed steps, then exactly K steps between two device synchronisations: ms per step."""
+        for _ in range(args.warmup):
+            step_fn()
+        torch.cuda.synchronize()
+        run_step = step_fn
+        if args.graph:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=torch.cuda.current_stream()):
+                step_fn()
+            run_step = graph.replay
+            run_step()
+            torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            run_step()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / args.steps
+
+    def steps_with_events(step_fn):
+        """The same K steps again, every kernel launch carrying a HIP event pair that holds the kernel's own
+        begin/end timestamps on its stream.  (Kept out of the timed region because launches that carry events
+        are dispatched one by one and stretch the step by about a fifth.)"""
+        kern = {}
         pc.pc_profile_enable(args.steps * L)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(args.steps):
-            step()
+            step_fn()
         torch.cuda.synchronize()
-        ms_per_step_events = (time.perf_counter() - t0) * 1e3 / args.steps
+        ms = (time.perf_counter() - t0) * 1e3 / args.steps
         for name, kind in (("gather", pcb.PROF_GATHER), ("append", pcb.PROF_APPEND), ("attn", pcb.PROF_ATTN),
                            ("combine", pcb.PROF_COMBINE)):
             each = pc.pc_profile_read_each(kind, args.steps * L) * 1e3      # microseconds per launch
@@ -463,17 +471,35 @@ def main(argv=None) -> int:
             kern[name] = {"launches": n, "avg_us": float(each.mean()) if n else None,
                           "median_us": float(np.median(each)) if n else None, "min_us": float(each.min()) if n else None}
         pc.pc_profile_enable(0)
+        return ms, kern
+
+    # ---------------- the timed region: nothing but the library calls
+    ms_per_step = timed_steps(step)
+    kern, ms_per_step_events = {}, None
+    if not args.no_events:
+        ms_per_step_events, kern = steps_with_events(step)
     launch = pc.pc_last_attn_launch()
+    other = None
+    if other_step is not None:
+        other = {"ms_per_step": timed_steps(other_step)}
+        if not args.no_events:
+            other["kern"] = steps_with_events(other_step)[1]
 
     # ---------------- algorithmic work per layer
     flops_layer = attn_flops(w, n_mod, n_new)
-    gather_bytes_layer = sum(n_mod) * (2 * 2 * w.row_bytes + 4)       # K and V, read + write, + int32 position
-    if in_place:   # only the uncached tokens' rows move: read raw, written rotated, + position IDs
-        gather_bytes_layer = sum(n_new) * (2 * 2 * w.row_bytes + 8)
-    elif fused:   # the same launch also reads and writes the uncached tokens' rows (and reads/writes their position IDs)
-        gather_bytes_layer += sum(n_new) * (2 * 2 * w.row_bytes + 8)
-    if rot_once and not all_layers:   # the same launch reads Q_new and writes Q_rot
-        gather_bytes_layer += sum(n_new) * 2 * w.n_q_heads * w.head_dim * w.elem_bytes
+
+    def assembly_bytes_per_layer(form_all_layers):
+        b = sum(n_mod) * (2 * 2 * w.row_bytes + 4)       # K and V, read + write, + int32 position
+        if in_place:   # only the uncached tokens' rows move: read raw, written rotated, + position IDs
+            return sum(n_new) * (2 * 2 * w.row_bytes + 8)
+        if form_all_layers:   # the gather launch moves the module rows and nothing else
+            return b
+        if fused:   # the same launch also reads and writes the uncached tokens' rows (and reads/writes their position IDs)
+            b += sum(n_new) * (2 * 2 * w.row_bytes + 8)
+        if rot_once:   # the same launch reads Q_new and writes Q_rot
+            b += sum(n_new) * 2 * w.n_q_heads * w.head_dim * w.elem_bytes
+        return b
+    gather_bytes_layer = assembly_bytes_per_layer(all_layers)
     attn_tflops_step = flops_layer * L / (ms_per_step * 1e-3) / 1e12
 
     result = {
@@ -486,7 +512,7 @@ def main(argv=None) -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "kv_path": "modules read in place" if in_place else "packed copy",
-                   "assembly": "not used" if in_place else ("all layers' modules at the start of the step (pc_assemble_kv_layers), uncached tokens appended per layer" if all_layers else "per layer, one launch with the append"),
+                   "assembly": "not used" if in_place else (ASSEMBLY_ALL_LAYERS if all_layers else ASSEMBLY_PER_LAYER),
                    "module_tier": ("host memory, " + ("loaded by the assembly kernel" if args.host_tier == "kernel" else "copy engine")) if args.host_tier else "HBM pool",
                    "q_rotation": "once per token, in the assembly launch" if rot_once else "in every attention workgroup", "overlap": bool(args.overlap), "hip_graph": bool(args.graph), "position_encoding": "alibi" if args.alibi else "rope", "layers": L, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
                    "head_dim": w.head_dim, "prompts": B, "module_tokens": n_mod if B <= 4 else [n_mod[0], "..."],
@@ -525,6 +551,22 @@ def main(argv=None) -> int:
                                        "bound": "hbm", "achieved": round(gat_gbs, 1),
                                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gat_gbs / HBM_PEAK_GBS, 4),
                                        "traffic": traffic_known.get("append" if in_place else "gather")}
+
+    if other is not None:
+        # the other assembly form over the same K steps (same buffers, same attention calls)
+        o_all = not all_layers
+        o_bytes = assembly_bytes_per_layer(o_all)
+        o = {"assembly": ASSEMBLY_ALL_LAYERS if o_all else ASSEMBLY_PER_LAYER, "ms_per_step": round(other["ms_per_step"], 4),
+             "value": round(flops_layer * L / (other["ms_per_step"] * 1e-3) / 1e12, 3), "cached_us_per_layer": round(other["ms_per_step"] * 1e3 / L, 2)}
+        ok = other.get("kern", {})
+        if ok.get("gather", {}).get("avg_us"):
+            gk = ok["gather"]
+            gbs = o_bytes * L * args.steps / (gk["avg_us"] * gk["launches"] * 1e-6) / 1e9
+            o["kernels_us"] = {k: (round(v["avg_us"], 2) if v["avg_us"] else None) for k, v in ok.items()}
+            o["roofline_assemble"] = {"kernel": "gather_layers_kernel" if o_all else "gather_append_kernel", "launches_per_step": gk["launches"] / args.steps,
+                                      "mbytes_per_launch": round(o_bytes * L * args.steps / gk["launches"] / 1e6, 2), "bound": "hbm",
+                                      "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4)}
+        result["other_assembly_form"] = o
 
     if args.host_tier:
         # PCIe-inclusive view: the modules' K and V cross the host link once per layer and step

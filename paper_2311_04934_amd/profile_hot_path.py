@@ -2,8 +2,8 @@
 
     python -m paper_2311_04934_amd.profile_hot_path [--workload long_doc_8k] [--out gpurun_out/profile] [bench flags ...]
 
-Runs `bench.py` four times under rocprofv3 (one run per counter group: the profiler does not split counters over
-passes) and writes, under --out:
+Runs `bench.py` once by itself and four times under rocprofv3 (one run per counter group: the profiler does not
+split counters over passes) and writes, under --out:
 
     <workload>[_<tag>]_hot_path.md   a summary in text: the commands, kernel statistics, FETCH_SIZE / WRITE_SIZE per
                                      launch scaled by what the same counter reads for a plain copy of known size
@@ -23,6 +23,7 @@ import csv
 import glob
 import json
 import os
+import re
 import statistics
 import subprocess
 import sys
@@ -40,6 +41,12 @@ def kernel_key(name: str):
         if tag in name:
             return key
     return None
+
+
+def short_name(name: str) -> str:
+    """Kernel name without its namespaces and parameter list."""
+    m = re.match(r"(?:void )?(?:pc::)?(?:\(anonymous namespace\)::)?([A-Za-z_0-9]+(?:<[^>]*>)?)", name)
+    return m.group(1) if m else name
 
 
 def run(cmd, log):
@@ -70,16 +77,20 @@ def main(argv=None) -> int:
     sys.path.insert(0, ROOT)
     from paper_2311_04934_amd import build as pc_build
     pc_build.ensure_built()
-    out = os.path.join(ROOT, args.out)
-    os.makedirs(out, exist_ok=True)
+    out = args.out    # relative to the repository root, where every command runs
+    os.makedirs(os.path.join(ROOT, out), exist_ok=True)
+    os.chdir(ROOT)
     name = args.workload + ("_" + args.tag if args.tag else "")
-    bench = ["python3", "bench.py", "--workload", args.workload] + bench_flags
-    short = ["--layers", "4", "--steps", "2", "--warmup", "1", "--no-cpu-baseline", "--no-full-prefill", "--calibrate"]
+    bench = ["python3", "bench.py", "--workload", args.workload, "--no-other-form", "--no-cpu-baseline"] + bench_flags
+    short = ["--steps", "2", "--warmup", "1", "--no-full-prefill", "--calibrate"]
     cmds = {}
 
+    # 0. the benchmark by itself: what its HIP events read without a profiler attached
+    cmds["plain"] = bench
+    run(cmds["plain"], os.path.join(out, name + "_plain.log"))
     # 1. durations
     d_stats = os.path.join(out, name + "_stats")
-    cmds["stats"] = ["rocprofv3", "--kernel-trace", "--stats", "--output-format", "csv", "-d", d_stats, "-o", "bench", "--"] + bench + ["--no-cpu-baseline"]
+    cmds["stats"] = ["rocprofv3", "--kernel-trace", "--stats", "--output-format", "csv", "-d", d_stats, "-o", "bench", "--"] + bench
     run(cmds["stats"], d_stats + ".log")
     # 2.-4. counters, one group per run
     groups = {"fetch": ["FETCH_SIZE"], "write": ["WRITE_SIZE"], "sq": SQ_COUNTERS}
@@ -102,7 +113,7 @@ def main(argv=None) -> int:
              "| kernel | calls | avg us | min us | max us | % of GPU time |", "|---|---|---|---|---|---|"]
     for r in csv.DictReader(open(find(d_stats, "kernel_stats.csv"))):
         if kernel_key(r["Name"]):
-            lines.append(f'| {r["Name"]} | {r["Calls"]} | {float(r["AverageNs"]) / 1e3:.2f} | {float(r["MinNs"]) / 1e3:.2f} | '
+            lines.append(f'| {short_name(r["Name"])} | {r["Calls"]} | {float(r["AverageNs"]) / 1e3:.2f} | {float(r["MinNs"]) / 1e3:.2f} | '
                          f'{float(r["MaxNs"]) / 1e3:.2f} | {r["Percentage"]} |')
     # the attention kernel without the full-prefill comparison's launches (the long ones)
     durs = collections.defaultdict(list)
@@ -116,12 +127,14 @@ def main(argv=None) -> int:
         lines += ["", f"Attention kernel over its {len(hot)} hot-path launches alone (launches shorter than 5x the median; the others "
                       f"are the full-prefill comparison): average **{sum(hot) / len(hot):.2f} us**, median {statistics.median(hot):.2f} us."]
     bench_line = None
-    for ln in open(d_stats + ".log"):
+    for ln in open(os.path.join(out, name + "_plain.log")):
         if ln.startswith("{"):
             bench_line = json.loads(ln)
     if bench_line:
-        lines += ["", "`bench.py` in the same run (HIP events carried by the launches): " + json.dumps(bench_line.get("kernels_us")) +
-                  f", {bench_line['per_layer']['cached_us']} us per layer, value {bench_line['value']}."]
+        lines += ["", "`" + " ".join(cmds["plain"]) + "` just before, on the same machine, without the profiler (HIP events carried by the "
+                  "launches; average us per launch): " + json.dumps(bench_line.get("kernels_us")) +
+                  f", {bench_line['per_layer']['cached_us']} us per layer, value {bench_line['value']}, roofline.frac {bench_line.get('roofline', {}).get('frac')}.",
+                  "The profiler's own cost per dispatch is inside its durations; a kernel that does nothing measures 3.9 us with either method."]
 
     # ---- HBM traffic
     fetch, write = counters(find(dirs["fetch"], "counter_collection.csv")), counters(find(dirs["write"], "counter_collection.csv"))
@@ -148,9 +161,11 @@ def main(argv=None) -> int:
     for c in sorted(sq.get("attn", {})):
         lines.append(f"| {c} | {statistics.median(sq['attn'][c]):.0f} |")
     a = sq.get("attn", {})
-    if "SQ_VALU_MFMA_BUSY_CYCLES" in a and "SQ_BUSY_CYCLES" in a:
-        lines += ["", f"Matrix pipes busy {statistics.median(a['SQ_VALU_MFMA_BUSY_CYCLES']) / max(statistics.median(a['SQ_BUSY_CYCLES']), 1) / 4:.3f} "
-                      "of the SIMD-cycles the kernel is resident (SQ_VALU_MFMA_BUSY_CYCLES / (4 x SQ_BUSY_CYCLES))."]
+    if "SQ_VALU_MFMA_BUSY_CYCLES" in a and "GRBM_GUI_ACTIVE" in a:
+        cycles = statistics.median(a["GRBM_GUI_ACTIVE"]) / 8.0    # the counter is summed over the 8 XCDs
+        lines += ["", f"GRBM_GUI_ACTIVE is summed over the 8 XCDs: {cycles:.0f} cycles per XCD.  Matrix pipes busy = SQ_VALU_MFMA_BUSY_CYCLES / "
+                      f"(cycles x 1024 SIMDs) = {statistics.median(a['SQ_VALU_MFMA_BUSY_CYCLES']) / (cycles * 1024):.3f} of the launch "
+                      "(launch, prologue and epilogue included; counters slow the kernel down a little)."]
 
     md = os.path.join(out, name + "_hot_path.md")
     with open(md, "w") as f:
