@@ -1241,6 +1241,12 @@ def test_attention_deterministic_split_kv(in_place):
     _determinism_run(W.long_doc_8k(), in_place)
 
 
+@pytest.mark.parametrize("in_place", [False, True])
+def test_attention_deterministic_many_splits(in_place):
+    """Config 4: one row block per kv head and 17 or more KV splits."""
+    _determinism_run(W.sparse_selection(seed=0, n_prompts=1), in_place)
+
+
 def test_attention_deterministic_register_staged_kernel():
     """head_dim 64 and few query rows: the kernel that stages K/V through registers."""
     w = W.custom("det_d64", "bf16", 8, 8, 64, [4096, 2048, 1000], None,
