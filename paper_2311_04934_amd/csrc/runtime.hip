@@ -248,7 +248,13 @@ bool by_copy_engine(const pc_ctx *ctx, const ModuleEntry *m) { return m->host &&
 // for launches that would otherwise leave CUs without a workgroup (smaller tiles cost more per byte).
 // `extra_wgs` are the workgroups the same launch runs for appended rows.  Launches of hundreds of megabytes
 // run ~6 % faster with two passes per workgroup.  `n_layers` layers' modules go into the launch.
-int gather_rows_per_tile(const pc_ctx *ctx, const PlanRef &pr, long extra_wgs = 0, int n_layers = 1)
+// Rows per tile of a gather launch.  All workgroups of a launch are resident at once and the launch lasts as long as
+// its busiest CU, so the tile size is the one that gives the busiest CU the fewest bytes when workgroup i runs on CU
+// i mod n_cu: tiles first, then `extra_wgs` workgroups that move `extra_bytes` each (the appended rows of the fused
+// launch).  Candidates are 32, 24 and 16 KiB of K (and as much of V) per tile; ties go to the larger tile.  (Measured,
+// one module of 2 KiB rows: 512 tiles of 32 KiB 11.7 us, 528 tiles 15.1 us, the same 8448 rows in 704 tiles of 24 KiB
+// 12.6 us; rows of 8 KiB, 2112 rows and 128 appended rows: 528 tiles 15.5 us, 705 tiles of 24 KiB 12.8 us.)
+int gather_rows_per_tile(const pc_ctx *ctx, const PlanRef &pr, long extra_wgs = 0, int n_layers = 1, size_t extra_bytes = 0)
 {
     const size_t n = pr.plan->items.size();
     size_t rows = 0;
@@ -262,11 +268,28 @@ int gather_rows_per_tile(const pc_ctx *ctx, const PlanRef &pr, long extra_wgs = 
             if (pr.plan->items[i].n_rows > 0 && !by_copy_engine(ctx, pr.entry[i])) tiles += (pr.plan->items[i].n_rows + rpt - 1) / rpt;
         return tiles * n_layers;
     };
-    const int r32 = std::max(1, (int)(32768 / rb)), r24 = std::max(1, (int)(24576 / rb)), r16 = std::max(1, (int)(16384 / rb));
-    if (tiles_with(r24) + extra_wgs < n_cu) return r16;
-    const long c32 = ((tiles_with(r32) + extra_wgs + n_cu - 1) / n_cu) * r32;
-    const long c24 = ((tiles_with(r24) + extra_wgs + n_cu - 1) / n_cu) * r24;
-    return c24 < c32 ? r24 : r32;
+    auto busiest_cu_bytes = [&](int rpt) {
+        const long tiles = tiles_with(rpt);
+        const size_t tile_bytes = (size_t)rpt * rb;
+        const long base = tiles / n_cu, rem = tiles % n_cu;          // CUs [0, rem) run one tile more
+        const long eb = extra_wgs / n_cu, er = extra_wgs % n_cu;     // CUs [rem, rem + er) mod n_cu one extra workgroup more
+        const size_t most_tiles = (size_t)(base + (rem > 0)) * tile_bytes + (size_t)eb * extra_bytes;
+        const size_t most_extra = (size_t)base * tile_bytes + (size_t)(eb + (er > 0)) * extra_bytes;
+        if (rem > 0 && rem + er > n_cu) return (size_t)(base + 1) * tile_bytes + (size_t)(eb + 1) * extra_bytes;   // a CU has both
+        return std::max(most_tiles, most_extra);
+    };
+    int best = 0;
+    size_t best_bytes = 0;
+    for (const size_t kib : {32, 24, 16}) {
+        const int rpt = std::max(1, (int)(kib * 1024 / rb));
+        if (rpt == best) continue;
+        const size_t bytes = busiest_cu_bytes(rpt);
+        if (best == 0 || bytes < best_bytes) {
+            best = rpt;
+            best_bytes = bytes;
+        }
+    }
+    return best;
 }
 
 int tiles_of(const GatherSeg &sg, int rows_per_tile)
@@ -879,7 +902,9 @@ static int assemble_append_impl(pc_ctx *ctx, int layer, const int *module_ids_fl
     const int n_segs = count_segments(pr);
     if (n_segs <= kMaxGatherSegs && n_prompts <= kMaxFusedAppendSegs) {
         FusedKvArgs a;
-        const int rows_per_tile = gather_rows_per_tile(ctx, pr, new_rows);
+        // an appended row's workgroup moves the token's K and V rows and, when it rotates Q as well, its Q row
+        const size_t app_bytes = ctx->row_bytes + (Q_rot ? (size_t)ctx->cfg.n_q_heads * ctx->cfg.head_dim * ctx->elem_bytes / 2 : 0);
+        const int rows_per_tile = gather_rows_per_tile(ctx, pr, new_rows, 1, app_bytes);
         a.g.n_segs = 0;
         a.g.rows_per_tile = rows_per_tile;
         a.g.row_bytes = (int)ctx->row_bytes;
