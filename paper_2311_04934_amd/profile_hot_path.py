@@ -1,6 +1,6 @@
 """rocprofv3 profile of the benchmark's hot path: kernel durations, HBM bytes per launch, matrix-unit counters.
 
-    python -m paper_2311_04934_amd.profile_hot_path [--workload long_doc_8k] [--out gpurun_out/profile] [bench flags ...]
+    python -m paper_2311_04934_amd.profile_hot_path [--workload long_doc_8k] [--out profile_out] [bench flags ...]
 
 Runs `bench.py` once by itself and four times under rocprofv3 (one run per counter group: the profiler does not
 split counters over passes) and writes, under --out:
@@ -70,7 +70,7 @@ def counters(path):
 def main(argv=None) -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", default="long_doc_8k")
-    ap.add_argument("--out", default=os.path.join("gpurun_out", "profile"))
+    ap.add_argument("--out", default="profile_out", help="folder for the raw profiler output and the summaries (relative to the repository root)")
     ap.add_argument("--tag", default="", help="suffix of the output names (e.g. the bench mode)")
     ap.add_argument("--merge", default=None, help="traffic json to merge the result into (e.g. profiles/traffic.json)")
     args, bench_flags = ap.parse_known_args(argv)
