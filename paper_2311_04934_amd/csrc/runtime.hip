@@ -240,20 +240,15 @@ int get_plan(pc_ctx *ctx, int layer, const int *ids_flat, const int *mod_offsets
 // writes its rows' position IDs only.
 bool by_copy_engine(const pc_ctx *ctx, const ModuleEntry *m) { return m->host && ctx->host_copy_mode == PC_HOST_COPY_ENGINE; }
 
-// Rows per gather tile.  A workgroup moves up to 32 KiB of K and 32 KiB of V in one pass (512 lanes x 4 x 16
-// bytes, all loads issued before the first store).  Measured: a launch takes about as long as its busiest CU,
-// i.e. (workgroups on that CU) x (tile bytes): 528 tiles of 32 KiB (two per CU on 240 CUs, three on 16) take
-// 25 % longer than 512, while the same rows cut into 704 tiles of 24 KiB take 7 % longer.  So 24 KiB tiles are
-// used where they make ceil(workgroups / CUs) x tile bytes smaller than 32 KiB tiles do, and 16 KiB tiles only
-// for launches that would otherwise leave CUs without a workgroup (smaller tiles cost more per byte).
-// `extra_wgs` are the workgroups the same launch runs for appended rows.  Launches of hundreds of megabytes
-// run ~6 % faster with two passes per workgroup.  `n_layers` layers' modules go into the launch.
 // Rows per tile of a gather launch.  All workgroups of a launch are resident at once and the launch lasts as long as
 // its busiest CU, so the tile size is the one that gives the busiest CU the fewest bytes when workgroup i runs on CU
 // i mod n_cu: tiles first, then `extra_wgs` workgroups that move `extra_bytes` each (the appended rows of the fused
 // launch).  Candidates are 32, 24 and 16 KiB of K (and as much of V) per tile; ties go to the larger tile.  (Measured,
 // one module of 2 KiB rows: 512 tiles of 32 KiB 11.7 us, 528 tiles 15.1 us, the same 8448 rows in 704 tiles of 24 KiB
 // 12.6 us; rows of 8 KiB, 2112 rows and 128 appended rows: 528 tiles 15.5 us, 705 tiles of 24 KiB 12.8 us.)
+// A workgroup moves a tile in one pass (512 lanes x 4 x 16 bytes of K and of V, all loads issued before the first
+// store).  Launches of more than 128 MiB take 64 KiB tiles, two passes per workgroup (~6 % faster there).
+// `n_layers` layers' modules go into the launch.
 int gather_rows_per_tile(const pc_ctx *ctx, const PlanRef &pr, long extra_wgs = 0, int n_layers = 1, size_t extra_bytes = 0)
 {
     const size_t n = pr.plan->items.size();

@@ -229,3 +229,38 @@ def test_a_layer_that_stores_a_module_differently_gets_a_plan_of_its_own():
         assert (h, m) == (1, 2)
     finally:
         pc.close()
+
+
+def test_more_prompts_than_kept_plans_replace_the_least_recently_used_one():
+    """The context keeps 8 plans.  Ten different import lists in turn: the ninth replaces the first, so the first
+    plans again when it comes back, while one used in between is still kept; every assembly stays bit-exact."""
+    dev = torch.device("cuda:0")
+    sizes = [20 + 3 * i for i in range(10)]
+    w = W.custom("plan_lru", "bf16", 4, 2, 64, sizes, None, [W.Prompt([i], 1) for i in range(10)], max_pos=1024)
+    pc, starts, mods = _store_all(w, 1)
+    try:
+        aK = torch.zeros((64, 2, 64), dtype=torch.bfloat16, device=dev)
+        aV, aP = torch.zeros_like(aK), torch.zeros((64,), dtype=torch.int32, device=dev)
+
+        def serve(i):
+            assert pc.pc_assemble_kv(0, [i], aK, aV, aP) == sizes[i]
+            torch.cuda.synchronize()
+            oK, _, oP = _expected(w, starts, mods, 0, w.prompts[i])
+            assert np.array_equal(as_words(aK.cpu()[:sizes[i]]), oK) and np.array_equal(aP.cpu().numpy()[:sizes[i]], oP)
+
+        for i in range(8):
+            serve(i)
+        h, m, _ = pc.pc_plan_stats()
+        assert (h, m) == (0, 8)
+        serve(1)                       # kept: a hit, and now more recently used than prompt 0
+        serve(8)                       # a ninth list replaces the least recently used plan, prompt 0's
+        serve(1)
+        assert pc.pc_plan_stats()[:2] == (2, 9)
+        serve(0)                       # gone: plans again (and replaces prompt 2's)
+        assert pc.pc_plan_stats()[:2] == (2, 10)
+        serve(1)
+        serve(9)
+        serve(8)
+        assert pc.pc_plan_stats()[:2] == (4, 11)
+    finally:
+        pc.close()
