@@ -31,6 +31,13 @@ FLAGS = [
 ]
 
 
+# Kernels whose leading arguments are plain pointers and integers get them in scalar registers at wave start instead of
+# loading them from the argument buffer first: the kernel that merges KV splits runs in 4.6 instead of 5.0 us.  Not for
+# the gather kernels: their dispatch got 0.2 us slower with it (measured), and kernels that take a struct first are
+# not affected either way.
+PER_SOURCE_FLAGS = {"attn_bf16.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=14"]}
+
+
 def library_path() -> str:
     return LIB
 
@@ -40,7 +47,7 @@ HASH_FILE = LIB + ".sha256"
 
 def source_hash() -> str:
     """Hash of everything the library is built from: the sources, the headers and the compiler flags."""
-    h = hashlib.sha256(" ".join(FLAGS[:-4]).encode())
+    h = hashlib.sha256((" ".join(FLAGS[:-4]) + repr(sorted(PER_SOURCE_FLAGS.items()))).encode())
     for d in (CSRC, INCLUDE):
         for name in sorted(os.listdir(d)):
             if name.endswith((".hip", ".h")):
@@ -71,7 +78,7 @@ def build(verbose: bool = False, extra_flags=()) -> str:
     for src in SOURCES:
         obj = os.path.join(OBJDIR, src.replace(".hip", ".o"))
         objs.append(obj)
-        cmd = [HIPCC, *FLAGS, *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [HIPCC, *FLAGS, *PER_SOURCE_FLAGS.get(src, []), *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))

@@ -15,11 +15,13 @@
 namespace pc {
 namespace {
 
-__global__ __launch_bounds__(kv::kThreads) void gather_kv_kernel(const GatherArgs a, uint8_t *__restrict__ out_k,
-                                                                  uint8_t *__restrict__ out_v,
+__global__ __launch_bounds__(kv::kThreads) void gather_kv_kernel(const kv::i32x4 f0, const kv::i32x4 f1, const kv::i32x4 f2,
+                                                                  const kv::i32x2 n, const GatherArgs a,
+                                                                  uint8_t *__restrict__ out_k, uint8_t *__restrict__ out_v,
                                                                   int32_t *__restrict__ out_pos)
 {
-    kv::gather_tile(a, blockIdx.x, out_k, out_v, out_pos);
+    const GatherSeg sg = a.seg[kv::gather_segment(a, n, f0, f1, f2, blockIdx.x)];
+    kv::gather_tile_of(a, sg, blockIdx.x, out_k, out_v, out_pos);
 }
 
 // The same gather over the modules of several layers: a segment's tiles go to the packed buffers of its layer.
@@ -36,18 +38,20 @@ __global__ __launch_bounds__(kv::kThreads) void gather_layers_kernel(const Gathe
 // rows, a chain of dependent loads, run fastest at the end of the grid, when the copy stream drains.)  The two write disjoint rows of the same packed buffers, and a kernel
 // launch costs more than the whole append, so a prompt's KV is complete after a single launch.
 template <typename T>
-__global__ __launch_bounds__(kv::kThreads) void gather_append_kernel(const FusedKvArgs a, uint8_t *__restrict__ out_k,
-                                                                      uint8_t *__restrict__ out_v,
+__global__ __launch_bounds__(kv::kThreads) void gather_append_kernel(const kv::i32x4 f0, const kv::i32x4 f1, const kv::i32x4 f2,
+                                                                      const kv::i32x2 n, const FusedKvArgs a,
+                                                                      uint8_t *__restrict__ out_k, uint8_t *__restrict__ out_v,
                                                                       int32_t *__restrict__ out_pos, const T *k_new,
                                                                       const T *v_new, const int32_t *q_pos,
                                                                       int n_kv_heads, int d, const float2 *table,
                                                                       int max_pos, const kv::QRotate<T> qr)
 {
     const int b = blockIdx.x;
-    if (b < a.g.total_tiles)
-        kv::gather_tile(a.g, b, out_k, out_v, out_pos);
-    else
-        kv::append_row<T>(a.app, a.n_app, b - a.g.total_tiles, k_new, v_new, q_pos, reinterpret_cast<T *>(out_k),
+    if (b < n[1]) {
+        const GatherSeg sg = a.g.seg[kv::gather_segment(a.g, n, f0, f1, f2, b)];
+        kv::gather_tile_of(a.g, sg, b, out_k, out_v, out_pos);
+    } else
+        kv::append_row<T>(a.app, a.n_app, b - n[1], k_new, v_new, q_pos, reinterpret_cast<T *>(out_k),
                              reinterpret_cast<T *>(out_v), out_pos, n_kv_heads, d, table, max_pos, qr);
 }
 
@@ -57,8 +61,9 @@ int launch_gather(pc_ctx *ctx, const GatherArgs &args, uint8_t *out_k, uint8_t *
                   hipStream_t stream)
 {
     if (args.total_tiles <= 0) return PC_OK;
+    const kv::GatherHead h = kv::gather_head(args);
     return launch_kernel(ctx, kProfGather, gather_kv_kernel, dim3(args.total_tiles), dim3(kv::kThreads), 0, stream,
-                         args, out_k, out_v, out_pos);
+                         h.ft[0], h.ft[1], h.ft[2], h.n, args, out_k, out_v, out_pos);
 }
 
 int launch_gather_layers(pc_ctx *ctx, const GatherLayersArgs &args, hipStream_t stream)
@@ -75,6 +80,7 @@ int launch_gather_append(pc_ctx *ctx, const FusedKvArgs &args, uint8_t *out_k, u
     if (blocks <= 0) return PC_OK;
     const int n_kv_heads = ctx->cfg.n_kv_heads, head_dim = ctx->cfg.head_dim, max_pos = ctx->cfg.max_pos;
     const float2 *table = ctx->use_alibi ? nullptr : ctx->rope_table;
+    const kv::GatherHead h = kv::gather_head(args.g);
     if (ctx->cfg.dtype == PC_F32) {
         kv::QRotate<float> qr;
         qr.q_new = static_cast<const float *>(q_new);
@@ -82,7 +88,7 @@ int launch_gather_append(pc_ctx *ctx, const FusedKvArgs &args, uint8_t *out_k, u
         qr.n_q_heads = ctx->cfg.n_q_heads;
         qr.scale = q_scale;
         return launch_kernel(ctx, kProfGather, gather_append_kernel<float>, dim3(blocks), dim3(kv::kThreads), 0, stream,
-                             args, out_k, out_v, out_pos, static_cast<const float *>(k_new),
+                             h.ft[0], h.ft[1], h.ft[2], h.n, args, out_k, out_v, out_pos, static_cast<const float *>(k_new),
                              static_cast<const float *>(v_new), q_pos, n_kv_heads, head_dim, table, max_pos, qr);
     }
     kv::QRotate<uint16_t> qr;
@@ -91,7 +97,7 @@ int launch_gather_append(pc_ctx *ctx, const FusedKvArgs &args, uint8_t *out_k, u
     qr.n_q_heads = ctx->cfg.n_q_heads;
     qr.scale = q_scale;
     return launch_kernel(ctx, kProfGather, gather_append_kernel<uint16_t>, dim3(blocks), dim3(kv::kThreads), 0, stream,
-                         args, out_k, out_v, out_pos, static_cast<const uint16_t *>(k_new),
+                         h.ft[0], h.ft[1], h.ft[2], h.n, args, out_k, out_v, out_pos, static_cast<const uint16_t *>(k_new),
                          static_cast<const uint16_t *>(v_new), q_pos, n_kv_heads, head_dim, table, max_pos, qr);
 }
 

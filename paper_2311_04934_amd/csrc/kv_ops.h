@@ -42,6 +42,33 @@ __device__ __forceinline__ int gather_segment(const GatherArgs &a, int tile)
 __device__ __forceinline__ void gather_tile_of(const GatherArgs &a, const GatherSeg &sg, int tile, uint8_t *__restrict__ out_k,
                                                uint8_t *__restrict__ out_v, int32_t *__restrict__ out_pos);
 
+// The head of a gather's arguments once more, as 14 dwords at the front of the kernel's argument list: one scalar
+// load brings them all, and a launch of up to kHeadSegs segments then finds a tile's segment by comparisons, where the
+// search over the table costs one dependent scalar load per step before the workgroup's first vector load can go
+// out (12 segments: four).
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x2 __attribute__((ext_vector_type(2)));
+constexpr int kHeadSegs = 12;
+struct GatherHead {   // passed as ft[0], ft[1], ft[2], n: 14 dwords without padding
+    i32x4 ft[3];    // first_tile of segments 0..11 (INT_MAX beyond n_segs)
+    i32x2 n;        // n_segs, total_tiles
+};
+inline GatherHead gather_head(const GatherArgs &a)
+{
+    GatherHead h;
+    h.n = i32x2{a.n_segs, a.total_tiles};
+    for (int i = 0; i < kHeadSegs; ++i) h.ft[i >> 2][i & 3] = i < a.n_segs ? a.seg[i].first_tile : 0x7fffffff;
+    return h;
+}
+__device__ __forceinline__ int gather_segment(const GatherArgs &a, i32x2 n, i32x4 f0, i32x4 f1, i32x4 f2, int tile)
+{
+    if (n[0] > kHeadSegs) return gather_segment(a, tile);
+    int si = -1;   // segments whose first tile is <= tile, minus one (first_tile is ascending, INT_MAX past the end)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) si += (f0[i] <= tile) + (f1[i] <= tile) + (f2[i] <= tile);
+    return si;
+}
+
 // Tile `tile` of the gather's flat work list: rows of one module copied verbatim, plus their position IDs.
 __device__ __forceinline__ void gather_tile(const GatherArgs &a, int tile, uint8_t *__restrict__ out_k,
                                             uint8_t *__restrict__ out_v, int32_t *__restrict__ out_pos)
