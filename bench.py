@@ -488,8 +488,13 @@ def main(argv=None) -> int:
     # ---------------- algorithmic work per layer
     flops_layer = attn_flops(w, n_mod, n_new)
 
-    def assembly_bytes_per_layer(form_all_layers):
-        b = sum(n_mod) * (2 * 2 * w.row_bytes + 4)       # K and V, read + write, + int32 position
+    # Algorithmic bytes of a layer's assembly: bytes written plus UNIQUE bytes read (a module imported by several
+    # prompts of the batch is read from HBM once, the other reads are cache hits), + the int32 position per row.
+    # `logical=True` counts every prompt's reads (twice the written bytes).
+    unique_mod_rows = sum(w.sizes[m] for m in used)
+
+    def assembly_bytes_per_layer(form_all_layers, logical=False):
+        b = sum(n_mod) * (2 * w.row_bytes + 4) + (sum(n_mod) if logical else unique_mod_rows) * 2 * w.row_bytes
         if in_place:   # only the uncached tokens' rows move: read raw, written rotated, + position IDs
             return sum(n_new) * (2 * 2 * w.row_bytes + 8)
         if form_all_layers:   # the gather launch moves the module rows and nothing else
@@ -500,6 +505,7 @@ def main(argv=None) -> int:
             b += sum(n_new) * 2 * w.n_q_heads * w.head_dim * w.elem_bytes
         return b
     gather_bytes_layer = assembly_bytes_per_layer(all_layers)
+    gather_bytes_logical = assembly_bytes_per_layer(all_layers, logical=True)
     attn_tflops_step = flops_layer * L / (ms_per_step * 1e-3) / 1e12
 
     result = {
@@ -551,6 +557,10 @@ def main(argv=None) -> int:
                                        "bound": "hbm", "achieved": round(gat_gbs, 1),
                                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gat_gbs / HBM_PEAK_GBS, 4),
                                        "traffic": traffic_known.get("append" if in_place else "gather")}
+        if gather_bytes_logical != gather_bytes_layer:   # modules shared inside the batch: the rate with every prompt's reads counted
+            result["roofline_assemble"]["logical"] = {"mbytes_per_launch": round(gather_bytes_logical * L * args.steps / gk["launches"] / 1e6, 2),
+                                                      "GBps": round(gat_gbs * gather_bytes_logical / gather_bytes_layer, 1),
+                                                      "frac": round(gat_gbs * gather_bytes_logical / gather_bytes_layer / HBM_PEAK_GBS, 4)}
 
     if other is not None:
         # the other assembly form over the same K steps (same buffers, same attention calls)
