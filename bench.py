@@ -525,6 +525,8 @@ def main(argv=None) -> int:
                    "uncached_tokens": n_new[0], "attn_launch": {"kv_splits": launch[0], "workgroups": launch[1],
                                                               "waves_per_wg": launch[2]}},
         "per_layer": {"attn_gflop": round(flops_layer / 1e9, 3), "assemble_mbytes": round(gather_bytes_layer / 1e6, 3),
+                      # attention: K and V read once, Q read, output written (partials of KV splits come on top)
+                      "attn_mbytes": round((2 * total_kv * w.row_bytes + 2 * total_q * w.n_q_heads * w.head_dim * w.elem_bytes) / 1e6, 3),
                       "cached_us": round(ms_per_step * 1e3 / L, 2)},
     }
     if kern.get("attn", {}).get("avg_us"):

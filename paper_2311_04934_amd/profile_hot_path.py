@@ -29,8 +29,8 @@ import subprocess
 import sys
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-SQ_COUNTERS = ["SQ_VALU_MFMA_BUSY_CYCLES", "SQ_BUSY_CYCLES", "SQ_INSTS_VALU", "SQ_INSTS_MFMA", "SQ_WAVE_CYCLES",
-               "SQ_ACTIVE_INST_VALU", "SQ_WAIT_INST_ANY", "GRBM_GUI_ACTIVE"]
+SQ_COUNTERS = ["SQ_VALU_MFMA_BUSY_CYCLES", "SQ_INSTS_VALU", "SQ_INSTS_MFMA", "SQ_WAVE_CYCLES", "SQ_WAIT_INST_ANY",
+               "SQ_LDS_BANK_CONFLICT", "SQ_LDS_IDX_ACTIVE", "SQ_WAVES", "GRBM_GUI_ACTIVE"]
 
 
 def kernel_key(name: str):
@@ -146,6 +146,11 @@ def main(argv=None) -> int:
               f"Calibration: `calib_copy_kernel` copies 1 GiB; FETCH_SIZE reads {f_raw / 1024:.0f} KiB for it (factor {f_scale:.3f}), "
               f"WRITE_SIZE {w_raw / 1024:.0f} KiB (factor {w_scale:.3f}).", "",
               "| kernel | launches | FETCH_SIZE raw KiB (median) | fetched MB | WRITE_SIZE raw KiB (median) | written MB |", "|---|---|---|---|---|---|"]
+    if bench_line:
+        pl = bench_line["per_layer"]
+        lines += ["", f"Algorithmic bytes (`bench.py`, per layer): assembly {pl['assemble_mbytes']} MB (written + unique read), attention "
+                  f"{pl.get('attn_mbytes')} MB (K and V once, Q read, output written; the partial results of KV splits, "
+                  "n_splits x rows x heads x 264 B written by the attention kernel and read by the merge, come on top)."]
     traffic = {}
     for k in ("gather", "append", "attn", "combine"):
         if k not in fetch:
@@ -167,6 +172,9 @@ def main(argv=None) -> int:
                       f"(cycles x 1024 SIMDs) = {statistics.median(a['SQ_VALU_MFMA_BUSY_CYCLES']) / (cycles * 1024):.3f} of the launch "
                       "(launch, prologue and epilogue included; counters slow the kernel down a little)."]
 
+    if "SQ_LDS_BANK_CONFLICT" in a and "SQ_LDS_IDX_ACTIVE" in a:
+        lines += [f"LDS: {statistics.median(a['SQ_LDS_BANK_CONFLICT']) / max(statistics.median(a['SQ_LDS_IDX_ACTIVE']), 1):.3f} of the LDS-active cycles are "
+                  "bank-conflict cycles (SQ_LDS_BANK_CONFLICT / SQ_LDS_IDX_ACTIVE)."]
     md = os.path.join(out, name + "_hot_path.md")
     with open(md, "w") as f:
         f.write("\n".join(lines) + "\n")
