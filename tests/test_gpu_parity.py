@@ -127,6 +127,16 @@ def test_text_in_a_gap_with_whole_modules_after_it(hq, hkv, d):
         _shared_run(w, 0, None)
 
 
+@pytest.mark.parametrize("hq,hkv,d,n", [(8, 2, 128, 1000), (4, 4, 128, 2300), (8, 8, 64, 700)])
+def test_ordinary_causal_prefill_of_a_whole_prompt(hq, hkv, d, n):
+    """No module at all: every token is uncached, positions 0..n-1, so the rule pos_k <= pos_q is the ordinary causal
+    mask (the comparison the benchmark times as full prefill).  Every row tile then sees a different number of key
+    tiles: the tiles after its diagonal hold nothing it can see and cost it no arithmetic, the diagonal tiles are
+    masked per element, and with several row blocks per kv head the workgroups differ too."""
+    w = W.custom(f"bf16_causal_{hq}_{hkv}_{d}_{n}", "bf16", hq, hkv, d, [5], None, [W.Prompt([], n)], max_pos=4096)
+    run_and_check(w)
+
+
 def test_hidden_keys_do_not_change_a_bit_of_the_result():
     """Keys at position IDs above every query's (whole tiles of them: the kernel skips those tiles, or masks them) are
     appended to a prompt; the output must keep every bit.  One pass over the keys, so that both runs cut the visible
@@ -1270,6 +1280,18 @@ def test_config3_long_doc_8k_full_size_every_row(layer):
 @pytest.mark.parametrize("seed", [0, 1])
 def test_config4_sparse_selection_full_size_every_row(seed):
     run_and_check(W.sparse_selection(seed=seed, n_prompts=2), layer=seed * 31)
+
+
+def test_config3_full_prefill_comparison_full_size_sampled_rows():
+    """What the benchmark times as full prefill: config 3's whole prompt (8448 tokens) as uncached tokens under the
+    ordinary causal mask, the same attention kernel.  The oracle needs minutes for all 8448 x 32 rows of this shape,
+    so 264 rows drawn over the whole range are compared here (every row of smaller causal prompts is compared by
+    test_ordinary_causal_prefill_of_a_whole_prompt)."""
+    w3 = W.long_doc_8k()
+    n = sum(w3.sizes) + w3.prompts[0].n_new
+    w = W.custom("config3_full_prefill", "bf16", w3.n_q_heads, w3.n_kv_heads, w3.head_dim, [5], None, [W.Prompt([], n)],
+                 max_pos=w3.max_pos)
+    run_and_check(w, q_sample=264)
 
 
 def test_config3_long_doc_8k_fused_assembly_full_size_every_row():
