@@ -264,3 +264,51 @@ def test_more_prompts_than_kept_plans_replace_the_least_recently_used_one():
         assert pc.pc_plan_stats()[:2] == (4, 11)
     finally:
         pc.close()
+
+
+@pytest.mark.parametrize("which", ["long_doc_8k", "sparse_selection"])
+def test_the_step_the_benchmark_times_in_its_all_layers_form(which):
+    """pc_assemble_kv_layers for two layers at once, then, per layer, pc_append_rotate_batched behind the modules of
+    the packed buffers and pc_prefill_attn_rotated_batched: the sequence `bench.py --assembly all-layers` runs, at the
+    benchmark's sizes, every row of layer 1 against the oracle (assembly and appended V bit-exact)."""
+    from test_gpu_parity import check_append, check_assembly, check_attention
+    from gpu_util import GpuRunner, build_case
+    dev = torch.device("cuda:0")
+    w = {"long_doc_8k": W.long_doc_8k, "sparse_selection": lambda: W.sparse_selection(seed=3, n_prompts=2)}[which]()
+    c = build_case(w, 1)
+    r = GpuRunner(c)          # stores layer 1's modules
+    try:
+        for m in sorted(c.mod_K):   # layer 0 gets the same modules: both layers of the call must be there
+            r.pc.pc_store_module(0, m, c.mod_K[m].to(dev), c.mod_V[m].to(dev), c.starts[m])
+        B = len(c.prompts)
+        ids = [p.module_ids for p in c.prompts]
+        n_mod = [sum(w.sizes[m] for m in p.module_ids) for p in c.prompts]
+        n_new = [len(p.q_pos) for p in c.prompts]
+        lens = [a + b for a, b in zip(n_mod, n_new)]
+        kv_off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+        q_off = np.concatenate([[0], np.cumsum(n_new)]).astype(np.int64)
+        total = int(kv_off[-1])
+        bK = [torch.full((total, w.n_kv_heads, w.head_dim), float("nan"), dtype=w.torch_dtype, device=dev) for _ in range(2)]
+        bV = [torch.full_like(t, float("nan")) for t in bK]
+        bP = [torch.full((total,), -7, dtype=torch.int32, device=dev) for _ in range(2)]
+        assert r.pc.pc_assemble_kv_layers(0, ids, bK, bV, bP, kv_off) == n_mod
+        Q = torch.cat([p.Q for p in c.prompts]).to(dev)
+        Kn = torch.cat([p.K_new for p in c.prompts]).to(dev)
+        Vn = torch.cat([p.V_new for p in c.prompts]).to(dev)
+        qp = torch.from_numpy(np.concatenate([p.q_pos for p in c.prompts])).to(dev)
+        Q_rot = torch.full_like(Q, float("nan"))
+        out = torch.full_like(Q, float("nan"))
+        r.pc.pc_append_rotate_batched(1, Kn, Vn, Q, qp, q_off, bK[1], bV[1], bP[1], kv_off, n_mod, Q_rot)
+        r.pc.pc_prefill_attn_rotated_batched(1, Q_rot, qp, q_off, bK[1], bV[1], bP[1], kv_off, lens, out)
+        torch.cuda.synchronize()
+        launch = r.pc.pc_last_attn_launch()
+        hK, hV, hP, o = bK[1].cpu(), bV[1].cpu(), bP[1].cpu().numpy(), out.cpu()
+    finally:
+        r.close()
+    for b in range(B):
+        lo, hi = int(kv_off[b]), int(kv_off[b + 1])
+        res = dict(asm_K=hK[lo:hi], asm_V=hV[lo:hi], asm_pos=hP[lo:hi], n_mod=n_mod[b], n_kv=lens[b],
+                   out=o[int(q_off[b]):int(q_off[b + 1])], launch=launch)
+        check_assembly(c, b, res)
+        check_append(c, b, res)
+        check_attention(c, b, res, None, "/all-layers form")
