@@ -262,7 +262,7 @@ int pc_assemble_kv_batched(pc_ctx *ctx, int layer, const int *module_ids_flat, c
                            const int *kv_offsets, int *out_n_tokens, void *stream);
 
 /*
- * Sec. 3.4: retrieving the cached modules "solely requires memory copy" and does not depend on the
+ * Sec. 3.4: bringing the cached modules in is a copy of stored states and does not depend on the
  * forward pass, so the modules of ALL layers can be concatenated when the request arrives, before
  * the first layer runs.  This call does pc_assemble_kv_batched for layers first_layer ..
  * first_layer+n_layers-1 with as few kernel launches as the kernels' segment tables allow (64

@@ -1,5 +1,5 @@
 """GPU parity of pc_assemble_kv_layers (the imported modules of all layers concatenated at the start of a request,
-Sec. 3.4: retrieval "solely requires memory copy") against the oracle's concatenation, layer by layer and bit for
+Sec. 3.4: retrieval is a copy of stored states) against the oracle's concatenation, layer by layer and bit for
 bit; and the request plan being made once per prompt (same section: imports are validated and modules retrieved
 once), shown with the library's own counters."""
 import numpy as np
