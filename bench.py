@@ -579,6 +579,10 @@ def main(argv=None) -> int:
                                       "mbytes_per_launch": round(o_bytes * L * args.steps / gk["launches"] / 1e6, 2), "bound": "hbm",
                                       "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4)}
         result["other_assembly_form"] = o
+        if "roofline_assemble" in result and "roofline_assemble" in o:   # both forms' HBM fractions side by side
+            result["roofline_assemble"]["this_form"] = result["config"]["assembly"]
+            result["roofline_assemble"]["other_form"] = {"assembly": o["assembly"], "kernel": o["roofline_assemble"]["kernel"],
+                                                         "achieved": o["roofline_assemble"]["achieved"], "frac": o["roofline_assemble"]["frac"]}
 
     if args.host_tier:
         # PCIe-inclusive view: the modules' K and V cross the host link once per layer and step
