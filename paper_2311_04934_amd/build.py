@@ -35,7 +35,8 @@ FLAGS = [
 # loading them from the argument buffer first: the kernel that merges KV splits runs in 4.6 instead of 5.0 us.  Not for
 # the gather kernels: their dispatch got 0.2 us slower with it (measured), and kernels that take a struct first are
 # not affected either way.
-PER_SOURCE_FLAGS = {"attn_bf16.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=14"]}
+PER_SOURCE_FLAGS = {"attn_bf16.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=14"],
+                    "attn_bf16_wide.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=14"]}
 
 
 def library_path() -> str:

@@ -64,6 +64,8 @@ constexpr int LDS_TOTAL = LDS_MAIN;
 
 typedef __attribute__((address_space(3))) uint8_t lds_u8;
 typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x2 __attribute__((ext_vector_type(2)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
 // s_waitcnt that only waits for the vector-memory counter to drop to n (gfx9 encoding:
@@ -118,9 +120,22 @@ struct NoSegTable {
 // ALIBI: position enters as the linear bias -slope[head] * (pos_q - pos_k) on the scores (Sec. 4.2 of the
 // paper: the bias follows the given position IDs) instead of a rotation of Q; keys are stored unrotated.
 template <int NQT, int NW, bool PAGED, bool ALIBI>
-__global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams p,
+__global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const i32x4 h0, const i32x4 h1, const i32x4 h2, const i32x2 h3,
+                                                                const AttnParams p,
                                                                 const std::conditional_t<PAGED, KvSegTable, NoSegTable> tab)
 {
+    // What the first copies of the kernel depend on (which work unit, which rows, which keys, where K, V and the
+    // position IDs are) comes a second time as the first 14 dwords of the argument list, which the dispatcher puts
+    // into scalar registers before the wave starts (the build asks for that): the first K/V tile is requested
+    // without a trip to the argument buffer (measured: ~1000 cycles per dependent round of scalar loads at the start
+    // of a kernel), and the loads of everything else, issued at once, arrive behind it.  See attn_head() for the packing.
+    const int a_n_groups = h0[0], a_rb_max = h0[1];
+    const int a_Hkv = h0[2] & 0xff, a_n_splits = (h0[2] >> 8) & 0xff, a_G = (h0[2] >> 16) & 0xff, a_q_rotated = (h0[2] >> 24) & 1;
+    const int a_n_seqs = h0[3] & 0xff, a_Hq = (int)((unsigned)h0[3] >> 8);
+    const AttnSeq a_seq0 = {h1[0], h1[1], h1[2], h1[3]};
+    const uint16_t *const a_k = reinterpret_cast<const uint16_t *>(((uint64_t)(uint32_t)h2[1] << 32) | (uint32_t)h2[0]);
+    const uint16_t *const a_v = reinterpret_cast<const uint16_t *>(((uint64_t)(uint32_t)h2[3] << 32) | (uint32_t)h2[2]);
+    const int32_t *const a_kv_pos = reinterpret_cast<const int32_t *>(((uint64_t)(uint32_t)h3[1] << 32) | (uint32_t)h3[0]);
     static_assert(NQT * NW == kWideRowTilesPerWg, "a workgroup covers 8 row tiles");
     static_assert(NQT == 1, "one row tile per wave (the softmax state below is kept per wave)");
     constexpr int GRP_PER_WAVE = 16 / NW;                // 1-KiB (4-row) groups of a tile each wave copies, per tensor
@@ -140,25 +155,25 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
     // ---- work unit (same XCD-aware enumeration as the narrow kernel)
     const int xcd = blockIdx.x & 7;
     const int slot = blockIdx.x >> 3;
-    const int g = (slot / p.rb_max) * 8 + xcd;
-    const int rb = slot % p.rb_max;
-    if (g >= p.n_groups) return;
+    const int g = (slot / a_rb_max) * 8 + xcd;
+    const int rb = slot % a_rb_max;
+    if (g >= a_n_groups) return;
     // the kv head varies fastest, so g % 8 (the XCD) follows the kv head: all KV splits of a (prompt, kv head) run on
     // one XCD and fetch the query rows of that head group once into its L2 (with the split fastest, every XCD
     // fetched the whole Q: 8 x 2.1 MB at config 3), while each K/V range is still read by one XCD only
-    const int kvh = g % p.Hkv;
-    const int split = (g / p.Hkv) % p.n_splits;
-    const int seq_i = g / (p.Hkv * p.n_splits);
-    AttnSeq seq = p.seq0;
-    if (p.n_seqs > 1) seq = p.batch.seq[seq_i];
+    const int kvh = g % a_Hkv;
+    const int split = (g / a_Hkv) % a_n_splits;
+    const int seq_i = g / (a_Hkv * a_n_splits);
+    AttnSeq seq = a_seq0;
+    if (a_n_seqs > 1) seq = p.batch.seq[seq_i];
 
     const int tiles_q = (seq.n_q + RW - 1) / RW;
-    const int row_tiles = p.G * tiles_q;
+    const int row_tiles = a_G * tiles_q;
     if (rb * kWideRowTilesPerWg >= row_tiles) return;
 
     // a split's share of the keys is a whole number of 64-key tiles: only the last split of a prompt then ends in a
     // ragged tile (which costs a masked iteration), and with 16.5 tiles per split every split would have one
-    const int share = (((seq.n_kv + p.n_splits - 1) / p.n_splits) + KT - 1) & ~(KT - 1);
+    const int share = (((seq.n_kv + a_n_splits - 1) / a_n_splits) + KT - 1) & ~(KT - 1);
     const int k_begin = split * share < seq.n_kv ? split * share : seq.n_kv;
     const int k_end = k_begin + share < seq.n_kv ? k_begin + share : seq.n_kv;
     const int n_tiles = (k_end - k_begin + KT - 1) / KT;
@@ -166,7 +181,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
     // Without a rotation to look up (Q arrives rotated, or position enters as a linear bias) nothing depends on the
     // queries' position IDs before the first mask decision: they then travel with the asynchronous copies instead
     // of holding these up (uniform)
-    const bool q_rot = p.q_rotated != 0;   // Q was rotated and scaled by the caller (append/assemble call)
+    const bool q_rot = a_q_rotated != 0;   // Q was rotated and scaled by the caller (append/assemble call)
     const bool q_direct = ALIBI || q_rot;
 
     // ---- this wave's row tile
@@ -177,7 +192,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
         const bool act = rt < row_tiles;
         const int g_head = act ? rt / tiles_q : 0;
         const int tq = act ? rt % tiles_q : 0;
-        qt[x].head = kvh * p.G + g_head;
+        qt[x].head = kvh * a_G + g_head;
         qt[x].tq = tq;
         qt[x].qi = tq * RW + col;
         qt[x].valid = act && qt[x].qi < seq.n_q;
@@ -189,10 +204,10 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
     float slope2 = 0.f;
     if constexpr (ALIBI) slope2 = p.alibi[__builtin_amdgcn_readfirstlane(qt[0].head)] * 1.4426950408889634f;
 
-    const size_t kv_row_stride = (size_t)p.Hkv * D;  // elements
-    const uint16_t *k_base = PAGED ? nullptr : p.k + (size_t)seq.kv_begin * kv_row_stride + (size_t)kvh * D;
-    const uint16_t *v_base = PAGED ? nullptr : p.v + (size_t)seq.kv_begin * kv_row_stride + (size_t)kvh * D;
-    const int32_t *pos_base = PAGED ? nullptr : p.kv_pos + seq.kv_begin;
+    const size_t kv_row_stride = (size_t)a_Hkv * D;  // elements
+    const uint16_t *k_base = PAGED ? nullptr : a_k + (size_t)seq.kv_begin * kv_row_stride + (size_t)kvh * D;
+    const uint16_t *v_base = PAGED ? nullptr : a_v + (size_t)seq.kv_begin * kv_row_stride + (size_t)kvh * D;
+    const int32_t *pos_base = PAGED ? nullptr : a_kv_pos + seq.kv_begin;
     const int last_row = k_end - 1;
 
     // PAGED: which row range holds a given row of the prompt.  The range table stays in the kernel
@@ -398,14 +413,14 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
     auto copy_q_rows = [&]() {
 #pragma unroll
         for (int x = 0; x < NQT; ++x) {
-            const uint8_t *qhead = reinterpret_cast<const uint8_t *>(p.q) + ((size_t)seq.q_begin * p.Hq + qt[x].head) * (D * 2);
+            const uint8_t *qhead = reinterpret_cast<const uint8_t *>(p.q) + ((size_t)seq.q_begin * a_Hq + qt[x].head) * (D * 2);
             const uint32_t dst0 = __builtin_amdgcn_readfirstlane(lds_base + q_region(wave * NQT + x));
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const int r = 4 * j + (lane >> 4), c = lane & 15;   // row of the tile, 16-byte chunk of the row
                 int qi = qt[x].tq * RW + r;
                 qi = qi < seq.n_q ? qi : seq.n_q - 1;                // rows past the prompt's last query: any valid row
-                dma_b128(qhead + (size_t)qi * p.Hq * (D * 2) + ((c ^ (r & 15)) << 4), dst0 + j * 1024);
+                dma_b128(qhead + (size_t)qi * a_Hq * (D * 2) + ((c ^ (r & 15)) << 4), dst0 + j * 1024);
             }
         }
     };
@@ -416,8 +431,8 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
             // strip of the bias area, which nothing uses before the first mask decision), tile 0 and the Q rows are
             // waited for, tile 1 stays in flight until the loop's first barrier
             const int qi0 = qt[0].qi < seq.n_q ? qt[0].qi : seq.n_q - 1;
+            issue_tile(0);   // needs nothing from the argument buffer
             dma_b32(p.q_pos + seq.q_begin + qi0, __builtin_amdgcn_readfirstlane(lds_base + LDS_BIAS + wave * 2 * KT * 4));
-            issue_tile(0);
             copy_q_rows();
             issue_tile(1);
             PC_WAIT_VMCNT(DMA_PER_TILE);
@@ -882,14 +897,14 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
     const int rt_e = rb * kWideRowTilesPerWg + wave;
     if (rt_e >= row_tiles) return;   // wave-uniform: a wave without a row tile
     const float l_tot = sum_across_halves(l_run);
-    const float scale = p.n_splits == 1 ? (l_tot > 0.f ? 1.f / l_tot : 0.f) : 1.f;
-    const int head = kvh * p.G + rt_e / tiles_q;
+    const float scale = a_n_splits == 1 ? (l_tot > 0.f ? 1.f / l_tot : 0.f) : 1.f;
+    const int head = kvh * a_G + rt_e / tiles_q;
     const int qi_e = (rt_e % tiles_q) * RW + col_e;
     // the output is [total_q][Hq] rows; a split's partials are [Hq][total_q] rows, so that the 32 rows of a wave are
     // 8 KiB in one piece (rows 8 KiB apart all fall on one memory channel)
     const size_t q_row = (size_t)(seq.q_begin + (qi_e < seq.n_q ? qi_e : 0));
-    const size_t out_row = p.n_splits > 1 ? ((size_t)split * p.Hq + head) * p.total_q + q_row : q_row * p.Hq + head;
-    uint16_t *dst = (p.n_splits > 1 ? p.part_o : p.out) + out_row * D + hh_e * 16;
+    const size_t out_row = a_n_splits > 1 ? ((size_t)split * a_Hq + head) * p.total_q + q_row : q_row * a_Hq + head;
+    uint16_t *dst = (a_n_splits > 1 ? p.part_o : p.out) + out_row * D + hh_e * 16;
 #pragma unroll
     for (int b = 0; b < DB; ++b) {
         uint32_t w[4][2];   // [i4][pair of d]
@@ -918,7 +933,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const AttnParams
             *reinterpret_cast<u32x4 *>(dst + b * 32 + 8) = c[1];
         }
     }
-    if (p.n_splits > 1 && hh_e == 0 && qi_e < seq.n_q) p.part_ml[out_row] = make_float2(m_run, l_tot);
+    if (a_n_splits > 1 && hh_e == 0 && qi_e < seq.n_q) p.part_ml[out_row] = make_float2(m_run, l_tot);
 }
 
 template <int NQT, int NW, bool PAGED, bool ALIBI, typename Tab>
@@ -932,7 +947,14 @@ int launch_one(pc_ctx *ctx, AttnParams &p, int n_blocks, hipStream_t stream, con
             return PC_E_HIP;
         attr_set[ctx->device & 15] = true;
     }
-    return launch_kernel(ctx, kProfAttn, kern, dim3(n_blocks), dim3(NW * 64), LDS_TOTAL, stream, p,
+    // the 14 dwords the kernel gets in registers: small integers packed, the first prompt, three pointers
+    if (p.Hkv > 255 || p.G > 255 || p.n_splits > 255 || p.n_seqs > 255 || p.Hq >= (1 << 23)) return PC_E_UNSUPPORTED;
+    const uint64_t pk = reinterpret_cast<uint64_t>(p.k), pv = reinterpret_cast<uint64_t>(p.v), pp = reinterpret_cast<uint64_t>(p.kv_pos);
+    const i32x4 h0 = {p.n_groups, p.rb_max, p.Hkv | (p.n_splits << 8) | (p.G << 16) | ((p.q_rotated ? 1 : 0) << 24), p.n_seqs | (int)((unsigned)p.Hq << 8)};
+    const i32x4 h1 = {p.seq0.q_begin, p.seq0.n_q, p.seq0.kv_begin, p.seq0.n_kv};
+    const i32x4 h2 = {(int)(uint32_t)pk, (int)(uint32_t)(pk >> 32), (int)(uint32_t)pv, (int)(uint32_t)(pv >> 32)};
+    const i32x2 h3 = {(int)(uint32_t)pp, (int)(uint32_t)(pp >> 32)};
+    return launch_kernel(ctx, kProfAttn, kern, dim3(n_blocks), dim3(NW * 64), LDS_TOTAL, stream, h0, h1, h2, h3, p,
                          tab);
 }
 
