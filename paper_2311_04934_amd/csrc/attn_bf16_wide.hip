@@ -104,6 +104,24 @@ __device__ __forceinline__ void dma_b32_u(uint64_t base, uint32_t lane_off, uint
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" ::"s"(lds_addr), "v"(lane_off), "s"(base) : "memory", "m0");
 }
 
+// Row tile rt of a kv head's stack (query heads of the group one after the other, tiles_q tiles each): which head of the
+// group and which tile of the prompt's queries.  rt is wave-uniform and groups are small: a few scalar subtractions
+// instead of a division.
+__device__ __forceinline__ void split_row_tile(int rt, int tiles_q, int G, int &g_head, int &tq)
+{
+    if (G <= 8) {
+        g_head = 0;
+        tq = rt;
+        while (tq >= tiles_q) {
+            tq -= tiles_q;
+            ++g_head;
+        }
+    } else {
+        g_head = rt / tiles_q;
+        tq = rt - g_head * tiles_q;
+    }
+}
+
 struct QTile {        // one 32-query row tile of a wave
     bool valid;       // this lane's query exists
     int head;
@@ -129,7 +147,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const i32x4 h0, 
     // into scalar registers before the wave starts (the build asks for that): the first K/V tile is requested
     // without a trip to the argument buffer (measured: ~1000 cycles per dependent round of scalar loads at the start
     // of a kernel), and the loads of everything else, issued at once, arrive behind it.  See attn_head() for the packing.
-    const int a_n_groups = h0[0], a_rb_max = h0[1];
+    const int a_hkv_shift = h0[0], a_share0 = h0[1];   // log2 of the kv heads padded to a power of two; first prompt's keys per split
     const int a_Hkv = h0[2] & 0xff, a_n_splits = (h0[2] >> 8) & 0xff, a_G = (h0[2] >> 16) & 0xff, a_q_rotated = (h0[2] >> 24) & 1;
     const int a_n_seqs = h0[3] & 0xff, a_Hq = (int)((unsigned)h0[3] >> 8);
     const AttnSeq a_seq0 = {h1[0], h1[1], h1[2], h1[3]};
@@ -152,18 +170,17 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const i32x4 h0, 
     const int col = lane & 31;
     const int hh = lane >> 5;
 
-    // ---- work unit (same XCD-aware enumeration as the narrow kernel)
-    const int xcd = blockIdx.x & 7;
-    const int slot = blockIdx.x >> 3;
-    const int g = (slot / a_rb_max) * 8 + xcd;
-    const int rb = slot % a_rb_max;
-    if (g >= a_n_groups) return;
-    // the kv head varies fastest, so g % 8 (the XCD) follows the kv head: all KV splits of a (prompt, kv head) run on
-    // one XCD and fetch the query rows of that head group once into its L2 (with the split fastest, every XCD
-    // fetched the whole Q: 8 x 2.1 MB at config 3), while each K/V range is still read by one XCD only
-    const int kvh = g % a_Hkv;
-    const int split = (g / a_Hkv) % a_n_splits;
-    const int seq_i = g / (a_Hkv * a_n_splits);
+    // ---- work unit.  The grid is (kv heads padded to a power of two x row blocks, KV splits, prompts): no division
+    // stands between the wave's start and its first copy.  Workgroups are dealt to the 8 XCDs in the order of their
+    // linear index, x fastest, so with the kv head fastest the XCD follows the kv head (8 or more of them): all KV
+    // splits of a (prompt, kv head) run on one XCD and fetch the query rows of that head group once into its L2
+    // (with the split fastest, every XCD fetched the whole Q: 8 x 2.1 MB at config 3), while each K/V range is
+    // still read by one XCD only.
+    const int kvh = blockIdx.x & ((1 << a_hkv_shift) - 1);
+    const int rb = blockIdx.x >> a_hkv_shift;
+    const int split = blockIdx.y;
+    const int seq_i = blockIdx.z;
+    if (kvh >= a_Hkv) return;
     AttnSeq seq = a_seq0;
     if (a_n_seqs > 1) seq = p.batch.seq[seq_i];
 
@@ -173,7 +190,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const i32x4 h0, 
 
     // a split's share of the keys is a whole number of 64-key tiles: only the last split of a prompt then ends in a
     // ragged tile (which costs a masked iteration), and with 16.5 tiles per split every split would have one
-    const int share = (((seq.n_kv + a_n_splits - 1) / a_n_splits) + KT - 1) & ~(KT - 1);
+    const int share = a_n_seqs > 1 ? (((seq.n_kv + a_n_splits - 1) / a_n_splits) + KT - 1) & ~(KT - 1) : a_share0;
     const int k_begin = split * share < seq.n_kv ? split * share : seq.n_kv;
     const int k_end = k_begin + share < seq.n_kv ? k_begin + share : seq.n_kv;
     const int n_tiles = (k_end - k_begin + KT - 1) / KT;
@@ -190,8 +207,8 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const i32x4 h0, 
     for (int x = 0; x < NQT; ++x) {
         const int rt = rb * kWideRowTilesPerWg + wave * NQT + x;
         const bool act = rt < row_tiles;
-        const int g_head = act ? rt / tiles_q : 0;
-        const int tq = act ? rt % tiles_q : 0;
+        int g_head = 0, tq = 0;
+        if (act) split_row_tile(rt, tiles_q, a_G, g_head, tq);
         qt[x].head = kvh * a_G + g_head;
         qt[x].tq = tq;
         qt[x].qi = tq * RW + col;
@@ -898,8 +915,10 @@ __global__ __launch_bounds__(NW * 64) void attn_bf16_dma_kernel(const i32x4 h0, 
     if (rt_e >= row_tiles) return;   // wave-uniform: a wave without a row tile
     const float l_tot = sum_across_halves(l_run);
     const float scale = a_n_splits == 1 ? (l_tot > 0.f ? 1.f / l_tot : 0.f) : 1.f;
-    const int head = kvh * a_G + rt_e / tiles_q;
-    const int qi_e = (rt_e % tiles_q) * RW + col_e;
+    int g_head_e, tq_e;
+    split_row_tile(rt_e, tiles_q, a_G, g_head_e, tq_e);
+    const int head = kvh * a_G + g_head_e;
+    const int qi_e = tq_e * RW + col_e;
     // the output is [total_q][Hq] rows; a split's partials are [Hq][total_q] rows, so that the 32 rows of a wave are
     // 8 KiB in one piece (rows 8 KiB apart all fall on one memory channel)
     const size_t q_row = (size_t)(seq.q_begin + (qi_e < seq.n_q ? qi_e : 0));
@@ -950,12 +969,16 @@ int launch_one(pc_ctx *ctx, AttnParams &p, int n_blocks, hipStream_t stream, con
     // the 14 dwords the kernel gets in registers: small integers packed, the first prompt, three pointers
     if (p.Hkv > 255 || p.G > 255 || p.n_splits > 255 || p.n_seqs > 255 || p.Hq >= (1 << 23)) return PC_E_UNSUPPORTED;
     const uint64_t pk = reinterpret_cast<uint64_t>(p.k), pv = reinterpret_cast<uint64_t>(p.v), pp = reinterpret_cast<uint64_t>(p.kv_pos);
-    const i32x4 h0 = {p.n_groups, p.rb_max, p.Hkv | (p.n_splits << 8) | (p.G << 16) | ((p.q_rotated ? 1 : 0) << 24), p.n_seqs | (int)((unsigned)p.Hq << 8)};
+    int hkv_shift = 0;
+    while ((1 << hkv_shift) < p.Hkv) ++hkv_shift;
+    const int share0 = (((p.seq0.n_kv + p.n_splits - 1) / p.n_splits) + KT - 1) & ~(KT - 1);   // keys per split, whole 64-key tiles
+    const i32x4 h0 = {hkv_shift, share0, p.Hkv | (p.n_splits << 8) | (p.G << 16) | ((p.q_rotated ? 1 : 0) << 24), p.n_seqs | (int)((unsigned)p.Hq << 8)};
     const i32x4 h1 = {p.seq0.q_begin, p.seq0.n_q, p.seq0.kv_begin, p.seq0.n_kv};
     const i32x4 h2 = {(int)(uint32_t)pk, (int)(uint32_t)(pk >> 32), (int)(uint32_t)pv, (int)(uint32_t)(pv >> 32)};
     const i32x2 h3 = {(int)(uint32_t)pp, (int)(uint32_t)(pp >> 32)};
-    return launch_kernel(ctx, kProfAttn, kern, dim3(n_blocks), dim3(NW * 64), LDS_TOTAL, stream, h0, h1, h2, h3, p,
-                         tab);
+    (void)n_blocks;
+    const dim3 grid((unsigned)(p.rb_max << hkv_shift), (unsigned)p.n_splits, (unsigned)p.n_seqs);
+    return launch_kernel(ctx, kProfAttn, kern, grid, dim3(NW * 64), LDS_TOTAL, stream, h0, h1, h2, h3, p, tab);
 }
 
 }  // namespace

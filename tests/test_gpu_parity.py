@@ -84,7 +84,9 @@ def test_fp32_gqa_ragged_gaps_and_text_inside_a_gap():
 
 
 # ------------------------------------------------------------------ bf16, reduced shapes (full check)
-@pytest.mark.parametrize("hq,hkv,d", [(8, 2, 128), (4, 4, 128), (8, 8, 64), (8, 1, 64)])
+@pytest.mark.parametrize("hq,hkv,d", [(8, 2, 128), (4, 4, 128), (8, 8, 64), (8, 1, 64),
+                                       (12, 3, 128),     # kv heads that are not a power of two (the grid pads them)
+                                       (24, 2, 128)])    # 12 query heads per kv head (row tiles found by division)
 def test_bf16_reduced_shapes_ragged(hq, hkv, d):
     # several 64-key tiles, ragged tails in keys and queries, a module omitted (gap), shuffled order
     w = W.custom(f"bf16_{hq}_{hkv}_{d}", "bf16", hq, hkv, d, [200, 333, 64, 77], None,
